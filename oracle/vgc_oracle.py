@@ -1,0 +1,299 @@
+"""Plain CPU oracle of the per-worker compression step of variance-based gradient
+compression (Tsuzuku, Imachi, Akiba, arXiv 1802.06058).
+
+TEST INFRASTRUCTURE ONLY.  It is slow and obviously correct on purpose, shares no
+code with the HIP path, and is imported only by the tests, the smoke check and the
+benchmark's CPU-baseline leg.
+
+What is implemented, in the paper's order and notation:
+
+  sqgrad_*            the two per-parameter sums of Alg. 1,
+                      g_i = sum_z (grad_i f_z / B) and s_i = sum_z (grad_i f_z / B)^2,
+                      from the definition of a per-sample gradient (Section 4.1).
+                      float64 throughout.
+  accumulate_select   the body of the `foreach parameters` loop of Alg. 1 with the
+                      criterion of Eq. 2 and the decay of Section 4.4; float32, one
+                      rounding per operation.
+  quantise_prose      Section 4.2 read literally in real arithmetic.
+  quantise_bits       the integer recipe of Section 4.4 (truncate the mantissa; round
+                      by adding one at the mantissa's top bit).
+  pack                Encode() of Alg. 1: per weight-matrix group, floor(log2 M_k),
+                      4-bit value code and 28-bit index in one 32-bit word (Section 4.2).
+  unpack_add          the decode-and-sum half of CommunicateAndUpdate() (Section 4.3).
+
+Readings taken where the paper is silent are stated at the function that needs them.
+Every function here is pinned by tests that do not go through this module's own
+arithmetic (hand-computed values, the worked example of Appendix B, the identity of
+Appendix A, closed forms and brute force); no part is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+F32 = np.float32
+U32 = np.uint32
+
+INDEX_BITS = 28                      # Section 4.2: "the rest 28-bits" hold the index
+INDEX_MASK = (1 << INDEX_BITS) - 1
+MAX_GROUP = 1 << INDEX_BITS
+D_MAX = 7                            # Section 4.2: three exponent bits, d in 0..7
+
+
+# --------------------------------------------------------------------------------------
+# (a) per-parameter sums over the mini-batch  (Alg. 1, first two lines of the loop body)
+# --------------------------------------------------------------------------------------
+
+def sqgrad_bruteforce_fc(X, D, c):
+    """Materialise every per-sample gradient of a fully-connected weight and sum.
+
+    For sample z the gradient of its loss w.r.t. W[i, j] is x_z[i] * delta_z[j]
+    (Section 4.1 defines grad_i f_z as the gradient of sample z's loss).  `c` is the
+    1/B of Alg. 1 (or 1 if delta already carries it).  Pure loops, float64; tiny
+    inputs only.
+    """
+    X = np.asarray(X, dtype=np.float64)
+    D = np.asarray(D, dtype=np.float64)
+    B, J = X.shape
+    _, C = D.shape
+    g = np.zeros((J, C))
+    s = np.zeros((J, C))
+    for z in range(B):
+        for i in range(J):
+            for j in range(C):
+                grad = c * X[z, i] * D[z, j]
+                g[i, j] += grad
+                s[i, j] += grad * grad
+    return g, s
+
+
+def sqgrad_bruteforce_conv(U, D, c):
+    """Same for a weight shared over P positions (a convolution seen through im2col).
+
+    Sample z's gradient w.r.t. W[j, k] is sum_p U[z, p, j] * D[z, p, k]; the square is
+    taken of that per-sample gradient, i.e. after the sum over positions
+    (Section 4.1: the variance is over the samples z of the mini-batch).
+    """
+    U = np.asarray(U, dtype=np.float64)
+    D = np.asarray(D, dtype=np.float64)
+    B, P, J = U.shape
+    C = D.shape[2]
+    g = np.zeros((J, C))
+    s = np.zeros((J, C))
+    for z in range(B):
+        for j in range(J):
+            for k in range(C):
+                grad = 0.0
+                for p in range(P):
+                    grad += U[z, p, j] * D[z, p, k]
+                grad *= c
+                g[j, k] += grad
+                s[j, k] += grad * grad
+    return g, s
+
+
+def sqgrad_fc(X, D, c):
+    """FC layer at config sizes: the per-sample gradient is an outer product, so
+    s = c^2 (X.X)^T (D.D) and g = c X^T D exactly.  Cost 2*N*B multiply-adds per
+    output array, the count Section 5 gives for the statistic.  float64."""
+    X = np.asarray(X, dtype=np.float64)
+    D = np.asarray(D, dtype=np.float64)
+    g = (X.T @ D) * c
+    s = ((X * X).T @ (D * D)) * (c * c)
+    return g, s
+
+
+def sqgrad_conv(U, D, c):
+    """Shared-weight layer at config sizes: one per-sample gradient matrix at a time
+    (G_z = U_z^T D_z), accumulated and square-accumulated.  float64."""
+    U = np.asarray(U)
+    D = np.asarray(D)
+    B, P, J = U.shape
+    C = D.shape[2]
+    g = np.zeros((J, C))
+    s = np.zeros((J, C))
+    for z in range(B):
+        G = (U[z].astype(np.float64).T @ D[z].astype(np.float64)) * c
+        g += G
+        s += G * G
+    return g, s
+
+
+# --------------------------------------------------------------------------------------
+# (b) accumulate, test, reset or decay  (Alg. 1 loop body, Eq. 2, Section 4.4)
+# --------------------------------------------------------------------------------------
+
+def accumulate_select(g, s, r, v, alpha, zeta):
+    """One step of Alg. 1 for every parameter.
+
+    float32 state, every operation rounded once, no fused multiply-add; alpha and zeta
+    are rounded to float32 first.  The comparison is strict as printed in Eq. 2 and
+    Alg. 1: equality is not sent.
+
+    Returns (r_acc, r_out, v_out, send): r_acc is the accumulated value handed to
+    Encode() (before the reset), r_out / v_out the state after the step.
+    """
+    g = np.asarray(g, dtype=F32)
+    s = np.asarray(s, dtype=F32)
+    r = np.asarray(r, dtype=F32)
+    v = np.asarray(v, dtype=F32)
+    a32 = F32(alpha)
+    z32 = F32(zeta)
+    r_acc = r + g                     # r_i += sum grad/B
+    v_acc = v + s                     # v_i += sum (grad/B)^2
+    lhs = r_acc * r_acc               # r_i^2
+    rhs = a32 * v_acc                 # alpha v_i
+    send = lhs > rhs
+    zero = F32(0.0)
+    v_out = np.where(send, zero, z32 * v_acc).astype(F32)   # reset, else v_i *= zeta
+    r_out = np.where(send, zero, r_acc).astype(F32)         # reset, else keep
+    assert r_acc.dtype == F32 and v_out.dtype == F32 and lhs.dtype == F32 and rhs.dtype == F32
+    return r_acc, r_out, v_out, send
+
+
+# --------------------------------------------------------------------------------------
+# (c) quantise and encode  (Section 4.2, Section 4.4, Appendix B)
+# --------------------------------------------------------------------------------------
+
+def floor_log2(a):
+    """floor(log2 a) for a positive finite float, exactly (math.frexp, no logarithm)."""
+    m, ex = math.frexp(float(a))      # a = m * 2**ex with 0.5 <= m < 1
+    return ex - 1
+
+
+def quantise_prose(a, E):
+    """Section 4.2 literally, in exact real arithmetic (float64 holds every float32 and
+    every 1.5 * 2**e exactly).
+
+    a : positive magnitudes of the elements to send (any float array);  E : floor(log2 M_k).
+    Returns (lq, keep): lq = log2 of the preprocessed magnitude g'_i, keep = (d_i <= 7)
+    with d_i = E - lq, and additionally g'_i must be a normal float32 power of two
+    (lq >= -126) so that the receiver can rebuild it from an exponent field.
+
+    Readings: "round to the closer value" is the linear midpoint 1.5 * 2**e and a tie
+    goes up, which is what the integer recipe of Section 4.4 does.
+    """
+    a = np.asarray(a, dtype=np.float64)
+    _, ex = np.frexp(a)
+    e = ex.astype(np.int64) - 1                       # floor(log2 a)
+    lower = np.ldexp(1.0, e)
+    lq = np.where(a >= 1.5 * lower, e + 1, e)         # closer of 2**floor, 2**ceil
+    lq = np.where(a > math.ldexp(1.0, E), E, lq)      # larger than 2**E: truncate to it
+    d = E - lq
+    keep = (d <= D_MAX) & (lq >= -126)
+    return lq, keep
+
+
+def quantise_bits(abs_bits, exp_field):
+    """The integer recipe of Section 4.4 on the float32 bit pattern with the sign cleared.
+
+    Adding one at the mantissa's top bit carries into the exponent exactly when the
+    mantissa is at least one half; dropping the mantissa then leaves the rounded
+    power of two.  `exp_field` is the biased exponent field of M_k, i.e. its mantissa
+    truncated.  Returns (e_field, d, keep): the biased exponent of g'_i, the 3-bit
+    code, and whether the element is encoded at all (d <= 7 and a non-zero exponent
+    field; a zero field cannot be decoded as a power of two).
+    """
+    abs_bits = np.asarray(abs_bits, dtype=np.uint64)
+    rounded = (abs_bits + np.uint64(0x00400000)) >> np.uint64(23)
+    e_field = np.minimum(rounded, np.uint64(exp_field)).astype(np.int64)
+    d = np.int64(exp_field) - e_field
+    keep = (d <= D_MAX) & (e_field >= 1)
+    return e_field, d, keep
+
+
+def pack(r_acc, send, groups, max_over="sent", check=True):
+    """Encode() of Alg. 1 for a whole model.
+
+    r_acc  : float32 accumulated values (before the reset), length N
+    send   : boolean mask of Alg. 1's test
+    groups : list of (offset, size) tiling [0, N); one group per weight matrix / tensor
+             (Section 4.2), size <= 2**28.
+
+    Per group k: M_k = largest magnitude among the elements being sent (Section 4.2
+    opens "after deciding which gradient elements to send"; `max_over="all"` takes the
+    other reading, the whole group).  Header = (biased exponent field of M_k, count,
+    offset of the group's first word).  An empty group has header (0, 0, offset).
+    Word = sign << 31 | d << 28 | index, index local to the group and 0-based, words in
+    ascending index order.  Elements with d > 7 are rounded to zero: no word.
+
+    Returns (words uint32[], headers list[(exp_field, count, word_offset)],
+             encoded bool[N]  -- True where a word was written).
+    """
+    r_acc = np.asarray(r_acc, dtype=F32)
+    send = np.asarray(send, dtype=bool)
+    bits = r_acc.view(U32)
+    abs_bits = bits & U32(0x7FFFFFFF)
+    words = []
+    headers = []
+    encoded = np.zeros(r_acc.shape[0], dtype=bool)
+    word_offset = 0
+    for (off, size) in groups:
+        assert 0 < size <= MAX_GROUP
+        sl = slice(off, off + size)
+        idx = np.flatnonzero(send[sl])                 # ascending local indices
+        if idx.size == 0:
+            headers.append((0, 0, word_offset))
+            continue
+        ab = abs_bits[sl][idx]
+        if max_over == "sent":
+            m_bits = int(ab.max())                     # monotone in |x| for finite floats
+        elif max_over == "all":
+            m_bits = int(abs_bits[sl].max())
+        else:
+            raise ValueError(max_over)
+        exp_field = m_bits >> 23                       # truncate the mantissa
+        e_field, d, keep = quantise_bits(ab, exp_field)
+        if check and exp_field >= 1:
+            # the prose of Section 4.2 must give the same answer for normal magnitudes
+            a = np.abs(r_acc[sl][idx].astype(np.float64))
+            normal = ab >= (1 << 23)
+            lq, keep_p = quantise_prose(a[normal], exp_field - 127)
+            assert np.array_equal(lq + 127, e_field[normal])
+            assert np.array_equal(keep_p, keep[normal])
+        sign = (bits[sl][idx] >> U32(31)).astype(np.uint64)
+        w = (sign << np.uint64(31)) | (d.astype(np.uint64) << np.uint64(28)) | idx.astype(np.uint64)
+        w = w[keep].astype(U32)
+        encoded[off + idx[keep]] = True
+        count = int(w.size)
+        headers.append((exp_field if count else 0, count, word_offset))
+        words.append(w)
+        word_offset += count
+    words = np.concatenate(words) if words else np.zeros(0, dtype=U32)
+    return words, headers, encoded
+
+
+# --------------------------------------------------------------------------------------
+# (d) decode and sum  (Section 4.3; CommunicateAndUpdate() of Alg. 1)
+# --------------------------------------------------------------------------------------
+
+def decode_words(words, exp_field):
+    """Split words into (local index, float32 value).  The value is the power of two
+    whose biased exponent is exp_field - d, with the word's sign bit."""
+    words = np.asarray(words, dtype=U32)
+    idx = (words & U32(INDEX_MASK)).astype(np.int64)
+    d = (words >> U32(28)) & U32(7)
+    sign = words & U32(0x80000000)
+    vbits = ((U32(exp_field) - d) << U32(23)) | sign
+    return idx, vbits.astype(U32).view(F32)
+
+
+def unpack_add(words, headers, groups, scale, out):
+    """Add one worker's message into the dense float32 buffer `out`, in place.
+
+    out[base_k + idx] = fl32(out[...] + fl32(scale * value)); indices inside one message
+    are distinct, and several messages are applied by calling this once per message in
+    worker order, which fixes the order of the float32 additions (Section 4.3 sums the
+    workers' contributions; `scale` = 1/p gives the mean it also mentions).
+    """
+    assert out.dtype == F32
+    sc = F32(scale)
+    for (off, size), (exp_field, count, word_offset) in zip(groups, headers):
+        if count == 0:
+            continue
+        idx, val = decode_words(words[word_offset:word_offset + count], exp_field)
+        assert idx.max() < size
+        contrib = (sc * val).astype(F32)
+        out[off + idx] = out[off + idx] + contrib
+    return out
