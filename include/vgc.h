@@ -1,0 +1,180 @@
+/*
+ * vgc.h -- C ABI of the per-worker hot path of variance-based gradient compression
+ * (Tsuzuku, Imachi, Akiba, "Variance-based Gradient Compression for Efficient
+ * Distributed Deep Learning", arXiv 1802.06058) for AMD MI355X (gfx950).
+ *
+ * One training iteration of one worker (Alg. 1) maps onto the calls like this:
+ *
+ *   CalcGrad()                              the framework's forward/backward (not here)
+ *   sum grad/B, sum (grad/B)^2  per param   vgc_sqgrad            (per layer)
+ *   foreach parameter: accumulate, test,
+ *     reset or decay                        vgc_accumulate_select (whole model, one launch)
+ *     Encode()                              vgc_pack              (whole model)
+ *   CommunicateAndUpdate(): decode + sum    vgc_unpack_add        (once per received message)
+ *
+ * Conventions
+ *   - Pointers marked DEVICE point to GPU memory owned by the caller; pointers marked HOST
+ *     to ordinary host memory.  The library never allocates, frees or keeps device memory.
+ *   - Every compute call only enqueues kernels on `stream` (a hipStream_t passed as void*,
+ *     NULL = the default stream) and returns without synchronising.
+ *   - Return value: VGC_OK (0) or a negative vgc_status.  On an argument error nothing is
+ *     launched and no buffer is touched.  vgc_last_error() gives a text for the calling thread.
+ *   - A "group" is the set of elements of one weight matrix / weight tensor (Section 4.2):
+ *     the unit that shares one floor(log2 M_k) and inside which the 28-bit index counts.
+ */
+#ifndef VGC_H
+#define VGC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    VGC_OK = 0,
+    VGC_ERR_NULL = -1,            /* a required pointer is NULL */
+    VGC_ERR_SIZE = -2,            /* n == 0, a zero dimension, groups not tiling [0, n), buffer too small */
+    VGC_ERR_GROUP_TOO_LARGE = -3, /* a group has more than 2^28 elements (28-bit index, Section 4.2) */
+    VGC_ERR_DTYPE = -4,           /* unknown dtype / kind enum */
+    VGC_ERR_ALIGN = -5,           /* pointer not aligned as documented */
+    VGC_ERR_PARAM = -6,           /* alpha negative or non-finite, zeta outside (0, 1], scale non-finite */
+    VGC_ERR_HIP = -7              /* a HIP runtime call failed; see vgc_last_error() */
+} vgc_status;
+
+enum { VGC_F32 = 0, VGC_BF16 = 1 };   /* element type of the activations / output-gradients */
+enum { VGC_FC = 0, VGC_CONV = 1 };    /* fully-connected form / shared-weight (convolution) form */
+
+/* One weight matrix: elements [offset, offset + size) of the flat parameter space. */
+typedef struct {
+    uint64_t offset;
+    uint32_t size;        /* 1 .. 2^28 */
+    uint32_t reserved;    /* must be 0 */
+} vgc_group;
+
+/* Header of one group inside a packed message (Section 4.2: floor(log2 M_k) "is also sent
+ * for every weight matrix"; the count is what a variable-length gather needs, Section 5). */
+typedef struct {
+    uint32_t exp_field;   /* biased float32 exponent field of M_k, i.e. floor(log2 M_k) + 127; 0 if count == 0 */
+    uint32_t count;       /* words of this group */
+    uint64_t word_offset; /* index of the group's first word in the message's word array */
+} vgc_group_hdr;
+
+/* Result record of vgc_pack (DEVICE memory, written by the device). */
+typedef struct {
+    uint64_t total_words; /* words the message has (also when they did not all fit) */
+    uint32_t overflow;    /* 1 if total_words > words_cap: words beyond the capacity were not written */
+    uint32_t reserved;
+} vgc_pack_status;
+
+/* Word layout (Section 4.2: 4-bit value, 28-bit index, one 32-bit word per sent element):
+ *   bit 31      sign of the accumulated gradient
+ *   bits 30..28 d = floor(log2 M_k) - log2 g'   (0..7; elements with d > 7 are not encoded)
+ *   bits 27..0  index of the element inside its group, 0-based
+ * Words of a group are in ascending index order; groups follow each other in order. */
+#define VGC_WORD_SIGN(w)  ((uint32_t)(w) >> 31)
+#define VGC_WORD_D(w)     (((uint32_t)(w) >> 28) & 7u)
+#define VGC_WORD_INDEX(w) ((uint32_t)(w) & 0x0FFFFFFFu)
+#define VGC_MAX_GROUP_SIZE (1u << 28)
+
+/* ---- library information ------------------------------------------------------------------ */
+
+const char* vgc_last_error(void);   /* text of the last error on this thread ("" if none) */
+uint32_t    vgc_tile_size(void);    /* elements per tile of the accumulate/pack kernels (a tile never spans two groups) */
+
+/* ---- plan and scratch ----------------------------------------------------------------------
+ * The plan is a read-only device table derived from the group list (group table + tile table);
+ * it can be shared by every worker state and by the decoder.  The scratch is per-worker working
+ * memory that carries the staged result of vgc_accumulate_select to vgc_pack.
+ */
+
+/* Number of tiles the groups split into.  groups: HOST.  Returns 0 and sets the error text if the
+ * groups are invalid (empty, zero-sized, larger than 2^28, or not tiling [0, n) in order). */
+uint64_t vgc_tile_count(const vgc_group* groups, uint32_t n_groups, uint64_t n);
+
+/* Bytes of the plan / of one scratch buffer for this group list (0 on invalid groups). */
+size_t vgc_plan_bytes(const vgc_group* groups, uint32_t n_groups, uint64_t n);
+size_t vgc_scratch_bytes(const vgc_group* groups, uint32_t n_groups, uint64_t n);
+
+/* Build the plan on the host.  plan_host: HOST buffer of vgc_plan_bytes() bytes that the caller
+ * then copies to device memory (256-byte aligned) and passes as `plan` below.  Pure host code. */
+int vgc_plan_build(const vgc_group* groups, uint32_t n_groups, uint64_t n, void* plan_host, size_t plan_bytes);
+
+/* Byte offset inside the scratch of the send bitmap that vgc_accumulate_select leaves behind:
+ * one bit per element in tile order, i.e. bit (t * vgc_tile_size() + i) is element i of tile t
+ * (tiles are numbered group after group, ceil(size / tile) per group); bit i lives in byte i/8,
+ * bit position i%8.  1 = the element passed the test of Eq. 2 in this step. */
+size_t vgc_scratch_bitmap_offset(const vgc_group* groups, uint32_t n_groups, uint64_t n);
+
+/* ---- (a) per-parameter sums over the mini-batch ---------------------------------------------
+ * Alg. 1, first two lines of the loop body: g_i = sum_z grad_i f_z * c and
+ * s_i = sum_z (grad_i f_z * c)^2 with c = 1/B (or 1 if the output-gradients already carry it),
+ * where grad f_z is the gradient of sample z's own loss (Section 4.1).  Section 5 counts
+ * 2 N |B| multiply-adds for this statistic.
+ *
+ *   VGC_FC:   X [B, J], D [B, C] row-major; sample z's gradient of W[j, c] is X[z, j] * D[z, c]:
+ *             g = c * X^T D,  s = c^2 * (X.X)^T (D.D).   P must be 1.
+ *   VGC_CONV: X [B, P, J] (im2col patches), D [B, P, C]; sample z's gradient is
+ *             G_z = sum_p X[z, p, :]^T D[z, p, :]:  g = c * sum_z G_z,  s = c^2 * sum_z G_z . G_z
+ *             (the square is taken after the sum over the P positions).
+ *
+ * X, D: DEVICE, dtype VGC_F32 (float) or VGC_BF16 (bfloat16 bits), 16-byte aligned.
+ * g_out (may be NULL), s_out: DEVICE float [J, C] row-major (the weight's own layout), 16-byte aligned.
+ * Accumulation is in float32.  Errors: NULL, SIZE (a zero dimension, P != 1 for FC), DTYPE, ALIGN, PARAM.
+ */
+int vgc_sqgrad(int kind, int dtype, const void* X, const void* D,
+               uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+               float* g_out, float* s_out, void* stream);
+
+/* ---- (b) accumulate, test, reset or decay ---------------------------------------------------
+ * The body of Alg. 1's parameter loop with the criterion of Eq. 2 and the decay of Section 4.4,
+ * for all n parameters in one launch, in float32 with one rounding per operation:
+ *     r' = r + g;  v' = v + s;  send = (r'*r' > alpha*v')        (strict)
+ *     r  = send ? 0 : r';        v = send ? 0 : zeta*v'
+ * For every element that is sent the kernel also takes the first half of Encode(): it rounds
+ * |r'| to a power of two with the integer recipe of Section 4.4 and stages (sign, exponent,
+ * position) in `scratch`, together with per-tile exponent statistics and the send bitmap, for
+ * vgc_pack to finish.  After this call r and v hold Alg. 1's post-step state.
+ *
+ * g, s (read), r, v (read and written): DEVICE float[n], 4-byte aligned (16-byte alignment of
+ * base + group offset enables the vector path).  groups: HOST, the list the plan was built from.
+ * plan, scratch: DEVICE, 256-byte aligned.  alpha >= 0 finite, 0 < zeta <= 1.
+ * Non-finite inputs give an unspecified mask but no fault.
+ */
+int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, uint64_t n,
+                          const vgc_group* groups, uint32_t n_groups, const void* plan,
+                          float alpha, float zeta, void* scratch, void* stream);
+
+/* ---- (c) quantise, compact, pack ------------------------------------------------------------
+ * Encode() of Alg. 1 (Sections 4.2 and 4.4): per group, M_k = the largest magnitude among the
+ * elements being sent, header = floor(log2 M_k); each sent element becomes one word (layout
+ * above) unless its d exceeds 7, in which case it is rounded to zero and not encoded.
+ * Consumes the scratch left by the preceding vgc_accumulate_select on the same stream.
+ *
+ * words_out: DEVICE uint32[words_cap]; never written past words_cap (words_cap >= n cannot overflow).
+ * hdrs_out:  DEVICE vgc_group_hdr[n_groups].   status_out: DEVICE vgc_pack_status.
+ */
+int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void* plan, void* scratch,
+             uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
+             vgc_pack_status* status_out, void* stream);
+
+/* ---- (d) decode and sum ---------------------------------------------------------------------
+ * The receiving half of CommunicateAndUpdate() (Section 4.3): decode one worker's message and
+ * add it into the dense gradient buffer:
+ *     dense_out[offset_k + index] += scale * (+-)2^(exp_field_k - d - 127)
+ * with one float32 multiply and one float32 add per word.  Indices inside one message are
+ * distinct, so the result is deterministic; several messages are applied by several calls on
+ * the same stream, in call order.  scale = 1/p gives the mean over p workers.
+ *
+ * words, hdrs: DEVICE (as written by vgc_pack; n_words = the message's total word count, known to
+ * the receiver from the transfer size).  plan: DEVICE.  dense_out: DEVICE float[n].
+ */
+int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
+                   const vgc_group* groups, uint32_t n_groups, const void* plan,
+                   float scale, float* dense_out, uint64_t n, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VGC_H */

@@ -1,0 +1,213 @@
+// C-ABI entry points of libvgc: argument checking, plan construction, kernel dispatch.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "vgc_internal.h"
+
+namespace vgc {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+int hip_check(hipError_t e, const char* what) {
+    if (e == hipSuccess) return VGC_OK;
+    set_error("%s: %s", what, hipGetErrorString(e));
+    return VGC_ERR_HIP;
+}
+
+// Validates the group list and counts tiles.  Returns a vgc_status.
+static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, uint64_t* n_tiles_out) {
+    if (!groups) { set_error("groups is NULL"); return VGC_ERR_NULL; }
+    if (n == 0 || n_groups == 0) { set_error("n and n_groups must be positive"); return VGC_ERR_SIZE; }
+    uint64_t off = 0, tiles = 0;
+    for (uint32_t k = 0; k < n_groups; ++k) {
+        if (groups[k].size == 0) { set_error("group %u is empty", k); return VGC_ERR_SIZE; }
+        if (groups[k].size > VGC_MAX_GROUP_SIZE) {
+            set_error("group %u has %u elements; a 28-bit index holds at most 2^28", k, groups[k].size);
+            return VGC_ERR_GROUP_TOO_LARGE;
+        }
+        if (groups[k].offset != off || groups[k].reserved != 0) {
+            set_error("group %u starts at %llu, expected %llu: groups must tile [0, n) in order", k,
+                      (unsigned long long)groups[k].offset, (unsigned long long)off);
+            return VGC_ERR_SIZE;
+        }
+        off += groups[k].size;
+        tiles += (groups[k].size + kTile - 1) / kTile;
+    }
+    if (off != n) {
+        set_error("groups cover %llu elements, n = %llu", (unsigned long long)off, (unsigned long long)n);
+        return VGC_ERR_SIZE;
+    }
+    if (tiles > 0x7FFFFFFFull) { set_error("too many tiles (%llu)", (unsigned long long)tiles); return VGC_ERR_SIZE; }
+    if (n_tiles_out) *n_tiles_out = tiles;
+    return VGC_OK;
+}
+
+static size_t plan_bytes_for(uint64_t n_tiles, uint32_t n_groups, size_t* groups_off, size_t* tiles_off) {
+    size_t off = sizeof(PlanHeader);
+    if (groups_off) *groups_off = off;
+    off = align_up(off + (size_t)n_groups * sizeof(PlanGroup), 256);
+    if (tiles_off) *tiles_off = off;
+    off = align_up(off + n_tiles * sizeof(PlanTile), 256);
+    return off;
+}
+
+static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+struct PlanView { const PlanGroup* groups; const PlanTile* tiles; };
+
+static PlanView plan_view(const void* plan_dev, uint64_t n_tiles, uint32_t n_groups) {
+    size_t go, to;
+    plan_bytes_for(n_tiles, n_groups, &go, &to);
+    const char* b = static_cast<const char*>(plan_dev);
+    return PlanView{reinterpret_cast<const PlanGroup*>(b + go), reinterpret_cast<const PlanTile*>(b + to)};
+}
+
+}  // namespace vgc
+
+using namespace vgc;
+
+extern "C" {
+
+const char* vgc_last_error(void) { return g_err; }
+
+uint32_t vgc_tile_size(void) { return kTile; }
+
+uint64_t vgc_tile_count(const vgc_group* groups, uint32_t n_groups, uint64_t n) {
+    uint64_t t = 0;
+    return check_groups(groups, n_groups, n, &t) == VGC_OK ? t : 0;
+}
+
+size_t vgc_plan_bytes(const vgc_group* groups, uint32_t n_groups, uint64_t n) {
+    uint64_t t = 0;
+    if (check_groups(groups, n_groups, n, &t) != VGC_OK) return 0;
+    return plan_bytes_for(t, n_groups, nullptr, nullptr);
+}
+
+size_t vgc_scratch_bytes(const vgc_group* groups, uint32_t n_groups, uint64_t n) {
+    uint64_t t = 0;
+    if (check_groups(groups, n_groups, n, &t) != VGC_OK) return 0;
+    return scratch_layout(t, n_groups).total;
+}
+
+size_t vgc_scratch_bitmap_offset(const vgc_group* groups, uint32_t n_groups, uint64_t n) {
+    uint64_t t = 0;
+    if (check_groups(groups, n_groups, n, &t) != VGC_OK) return 0;
+    return scratch_layout(t, n_groups).bitmap_off;
+}
+
+int vgc_plan_build(const vgc_group* groups, uint32_t n_groups, uint64_t n, void* plan_host, size_t plan_bytes) {
+    uint64_t n_tiles = 0;
+    int rc = check_groups(groups, n_groups, n, &n_tiles);
+    if (rc != VGC_OK) return rc;
+    if (!plan_host) { set_error("plan_host is NULL"); return VGC_ERR_NULL; }
+    size_t go, to;
+    const size_t need = plan_bytes_for(n_tiles, n_groups, &go, &to);
+    if (plan_bytes < need) { set_error("plan buffer has %zu bytes, %zu needed", plan_bytes, need); return VGC_ERR_SIZE; }
+    char* b = static_cast<char*>(plan_host);
+    memset(b, 0, need);
+    PlanHeader* h = reinterpret_cast<PlanHeader*>(b);
+    h->magic = kPlanMagic; h->n = n; h->n_tiles = n_tiles; h->n_groups = n_groups; h->tile = kTile;
+    h->groups_off = go; h->tiles_off = to;
+    PlanGroup* G = reinterpret_cast<PlanGroup*>(b + go);
+    PlanTile* T = reinterpret_cast<PlanTile*>(b + to);
+    uint64_t t = 0;
+    for (uint32_t k = 0; k < n_groups; ++k) {
+        G[k].offset = groups[k].offset; G[k].size = groups[k].size; G[k].first_tile = (uint32_t)t;
+        for (uint64_t start = 0; start < groups[k].size; start += kTile, ++t) {
+            T[t].group = k; T[t].start = (uint32_t)start;
+        }
+    }
+    return VGC_OK;
+}
+
+int vgc_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
+               float c, float* g_out, float* s_out, void* stream) {
+    if (kind != VGC_FC && kind != VGC_CONV) { set_error("vgc_sqgrad: unknown kind %d", kind); return VGC_ERR_DTYPE; }
+    if (dtype != VGC_F32 && dtype != VGC_BF16) { set_error("vgc_sqgrad: unknown dtype %d", dtype); return VGC_ERR_DTYPE; }
+    if (!X || !D || !s_out) { set_error("vgc_sqgrad: X, D and s_out are required"); return VGC_ERR_NULL; }
+    if (B == 0 || P == 0 || J == 0 || C == 0) { set_error("vgc_sqgrad: zero dimension"); return VGC_ERR_SIZE; }
+    if (kind == VGC_FC && P != 1) { set_error("vgc_sqgrad: the FC form has P = 1"); return VGC_ERR_SIZE; }
+    if (!aligned(X, 16) || !aligned(D, 16) || !aligned(s_out, 16) || (g_out && !aligned(g_out, 16))) {
+        set_error("vgc_sqgrad: pointers must be 16-byte aligned");
+        return VGC_ERR_ALIGN;
+    }
+    if (!std::isfinite(c)) { set_error("vgc_sqgrad: c is not finite"); return VGC_ERR_PARAM; }
+    return launch_sqgrad(kind, dtype, X, D, B, P, J, C, c, g_out, s_out, static_cast<hipStream_t>(stream));
+}
+
+int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, uint64_t n,
+                          const vgc_group* groups, uint32_t n_groups, const void* plan,
+                          float alpha, float zeta, void* scratch, void* stream) {
+    if (!g || !s || !r || !v || !plan || !scratch) { set_error("vgc_accumulate_select: NULL pointer"); return VGC_ERR_NULL; }
+    uint64_t n_tiles = 0;
+    int rc = check_groups(groups, n_groups, n, &n_tiles);
+    if (rc != VGC_OK) return rc;
+    if (!aligned(g, 4) || !aligned(s, 4) || !aligned(r, 4) || !aligned(v, 4) || !aligned(plan, 256) || !aligned(scratch, 256)) {
+        set_error("vgc_accumulate_select: g, s, r, v need 4-byte, plan and scratch 256-byte alignment");
+        return VGC_ERR_ALIGN;
+    }
+    if (!(alpha >= 0.0f) || !std::isfinite(alpha) || !(zeta > 0.0f) || !(zeta <= 1.0f)) {
+        set_error("vgc_accumulate_select: need alpha >= 0 finite and 0 < zeta <= 1 (got %g, %g)", alpha, zeta);
+        return VGC_ERR_PARAM;
+    }
+    const ScratchLayout L = scratch_layout(n_tiles, n_groups);
+    const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    char* sc = static_cast<char*>(scratch);
+    const bool vec = aligned(g, 16) && aligned(s, 16) && aligned(r, 16) && aligned(v, 16);
+    return launch_accumulate_select(g, s, r, v, pv.groups, pv.tiles, n_tiles,
+                                    reinterpret_cast<TileHdr*>(sc + L.tile_hdr_off),
+                                    reinterpret_cast<uint32_t*>(sc + L.bitmap_off),
+                                    reinterpret_cast<uint16_t*>(sc + L.staging_off),
+                                    alpha, zeta, vec, static_cast<hipStream_t>(stream));
+}
+
+int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void* plan, void* scratch,
+             uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
+             vgc_pack_status* status_out, void* stream) {
+    if (!plan || !scratch || !hdrs_out || !status_out || (!words_out && words_cap)) {
+        set_error("vgc_pack: NULL pointer");
+        return VGC_ERR_NULL;
+    }
+    uint64_t n_tiles = 0;
+    int rc = check_groups(groups, n_groups, n, &n_tiles);
+    if (rc != VGC_OK) return rc;
+    if (!aligned(plan, 256) || !aligned(scratch, 256) || !aligned(words_out, 4) || !aligned(hdrs_out, 8) || !aligned(status_out, 8)) {
+        set_error("vgc_pack: misaligned pointer");
+        return VGC_ERR_ALIGN;
+    }
+    const ScratchLayout L = scratch_layout(n_tiles, n_groups);
+    const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    char* sc = static_cast<char*>(scratch);
+    return launch_pack(pv.groups, pv.tiles, n_tiles, n_groups,
+                       reinterpret_cast<TileHdr*>(sc + L.tile_hdr_off),
+                       reinterpret_cast<GroupTmp*>(sc + L.group_tmp_off),
+                       reinterpret_cast<const uint16_t*>(sc + L.staging_off),
+                       words_out, words_cap, hdrs_out, status_out, static_cast<hipStream_t>(stream));
+}
+
+int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
+                   const vgc_group* groups, uint32_t n_groups, const void* plan,
+                   float scale, float* dense_out, uint64_t n, void* stream) {
+    if (!hdrs || !plan || !dense_out || (!words && n_words)) { set_error("vgc_unpack_add: NULL pointer"); return VGC_ERR_NULL; }
+    uint64_t n_tiles = 0;
+    int rc = check_groups(groups, n_groups, n, &n_tiles);
+    if (rc != VGC_OK) return rc;
+    if (!aligned(plan, 256) || !aligned(words, 4) || !aligned(hdrs, 8) || !aligned(dense_out, 4)) {
+        set_error("vgc_unpack_add: misaligned pointer");
+        return VGC_ERR_ALIGN;
+    }
+    if (!std::isfinite(scale)) { set_error("vgc_unpack_add: scale is not finite"); return VGC_ERR_PARAM; }
+    const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    return launch_unpack_add(words, n_words, hdrs, pv.groups, n_groups, scale, dense_out, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

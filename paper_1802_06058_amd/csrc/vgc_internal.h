@@ -1,0 +1,107 @@
+// Internal layout shared by the host entry points and the kernels of libvgc.
+#ifndef VGC_INTERNAL_H
+#define VGC_INTERNAL_H
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "vgc.h"
+
+namespace vgc {
+
+// A tile is the unit one workgroup of the accumulate kernel owns.  2048 elements lets a staged
+// entry fit 16 bits: 4 bits exponent code, 1 bit sign, 11 bits position inside the tile.
+constexpr uint32_t kTile = 2048;
+constexpr uint32_t kTileShift = 11;
+constexpr uint32_t kThreads = 256;
+constexpr uint32_t kElemsPerThread = kTile / kThreads;   // 8
+constexpr uint32_t kRelBins = 9;                          // staged exponent codes 0..8 (see StagedEntry)
+
+constexpr uint64_t kPlanMagic = 0x31304E414C504756ull;    // "VGPLAN01"
+
+struct PlanHeader {            // 64 bytes at the start of the plan blob
+    uint64_t magic;
+    uint64_t n;
+    uint64_t n_tiles;
+    uint32_t n_groups;
+    uint32_t tile;
+    uint64_t groups_off;       // byte offset of PlanGroup[n_groups]
+    uint64_t tiles_off;        // byte offset of PlanTile[n_tiles]
+    uint64_t pad[2];
+};
+
+struct PlanGroup {             // 16 bytes
+    uint64_t offset;           // first element of the group in the flat parameter space
+    uint32_t size;
+    uint32_t first_tile;       // would overflow only beyond 2^43 parameters
+};
+
+struct PlanTile {              // 8 bytes
+    uint32_t group;
+    uint32_t start;            // element offset of the tile inside its group (multiple of kTile)
+};
+
+// Per-tile record in the scratch.  Written by the accumulate kernel (w[0..4]) and completed by
+// the first pack kernel (w[5..7]).
+//   w[0..3]  : hist[0..7], two 16-bit counters per word (low half = even bin)
+//   w[4]     : low half hist[8]; high half = largest truncated exponent field among the tile's sent elements
+//   w[5]     : number of words the group's earlier tiles produce (exclusive prefix inside the group)
+//   w[6]     : shift = E_k - tile exponent
+//   w[7]     : words this tile produces
+struct TileHdr { uint32_t w[8]; };
+
+// Staged entry (uint16): rel << 12 | sign << 11 | position in tile, where
+// rel = (tile exponent + 1) - rounded exponent field of the element, 0..8.
+// With shift = E_k - tile exponent the final code is d = max(shift + rel - 1, 0)
+// and the element is encoded iff rel <= 8 - shift.
+
+struct GroupTmp { uint32_t exp_field; uint32_t count; };
+
+struct ScratchLayout {
+    uint64_t n_tiles;
+    size_t tile_hdr_off;       // TileHdr[n_tiles]
+    size_t group_tmp_off;      // GroupTmp[n_groups]
+    size_t bitmap_off;         // uint32[n_tiles * kTile / 32]
+    size_t staging_off;        // uint16[n_tiles * kTile]
+    size_t total;
+};
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+inline ScratchLayout scratch_layout(uint64_t n_tiles, uint32_t n_groups) {
+    ScratchLayout L;
+    L.n_tiles = n_tiles;
+    size_t off = 0;
+    L.tile_hdr_off = off;  off = align_up(off + n_tiles * sizeof(TileHdr), 256);
+    L.group_tmp_off = off; off = align_up(off + (size_t)n_groups * sizeof(GroupTmp), 256);
+    L.bitmap_off = off;    off = align_up(off + n_tiles * (kTile / 8), 256);
+    L.staging_off = off;   off = align_up(off + n_tiles * (size_t)kTile * 2, 256);
+    L.total = off;
+    return L;
+}
+
+// host-side helpers (vgc_api.hip)
+void set_error(const char* fmt, ...);
+int hip_check(hipError_t e, const char* what);
+
+// kernel launchers
+int launch_accumulate_select(const float* g, const float* s, float* r, float* v,
+                             const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles,
+                             TileHdr* hdrs, uint32_t* bitmap, uint16_t* staging,
+                             float alpha, float zeta, bool ptrs_vec_aligned, hipStream_t stream);
+
+int launch_pack(const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles, uint32_t n_groups,
+                TileHdr* hdrs, GroupTmp* gtmp, const uint16_t* staging,
+                uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
+                vgc_pack_status* status_out, hipStream_t stream);
+
+int launch_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
+                      const PlanGroup* groups, uint32_t n_groups, float scale, float* dense,
+                      hipStream_t stream);
+
+int launch_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
+                  uint32_t J, uint32_t C, float c, float* g_out, float* s_out, hipStream_t stream);
+
+}  // namespace vgc
+#endif

@@ -1,0 +1,178 @@
+// Second half of Encode() (Sections 4.2 and 4.4): fix floor(log2 M_k) per group, turn the staged
+// tile-relative exponent codes into the final 3-bit codes, drop what falls below 2^(E_k-7), and
+// write the words of every group contiguously, in ascending index order.
+//
+//   k_group_scan   one workgroup per group: E_k = max of the tile exponents, then per tile the
+//                  number of words it keeps and its exclusive prefix inside the group.
+//   k_header_scan  one workgroup: exclusive scan of the group counts -> headers and status.
+//   k_emit         one wave per tile: read the staged entries, filter, re-rank, write words.
+#include "vgc_internal.h"
+
+namespace vgc {
+
+__device__ __forceinline__ uint32_t rank_below64(uint64_t mask) {
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+// Inclusive scan over a 1024-thread workgroup; returns the inclusive value, total through `total`.
+__device__ __forceinline__ uint32_t block_scan_1024(uint32_t x, uint32_t* sh /*[16]*/, uint32_t& total) {
+    const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
+    uint32_t incl = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const uint32_t y = (uint32_t)__shfl_up((int)incl, off);
+        if (lane >= (uint32_t)off) incl += y;
+    }
+    __syncthreads();                       // protects sh against the previous use
+    if (lane == 63) sh[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) {
+        const uint32_t c = sh[w];
+        if ((uint32_t)w < wave) base += c;
+        tot += c;
+    }
+    total = tot;
+    return incl + base;
+}
+
+__global__ __launch_bounds__(1024) void k_group_scan(const PlanGroup* __restrict__ groups,
+                                                     TileHdr* __restrict__ hdrs, GroupTmp* __restrict__ gtmp) {
+    __shared__ uint32_t sh[16];
+    __shared__ uint32_t sh_e;
+    const uint32_t k = blockIdx.x;
+    const PlanGroup pg = groups[k];
+    const uint32_t nt = (pg.size + kTile - 1) / kTile;
+    TileHdr* H = hdrs + pg.first_tile;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+
+    // E_k: the largest exponent among all sent elements of the group
+    uint32_t e = 0;
+    for (uint32_t i = tid; i < nt; i += 1024) e = max(e, H[i].w[4] >> 16);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) e = max(e, (uint32_t)__shfl_xor((int)e, off));
+    if (lane == 0) sh[wave] = e;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t m = 0;
+        for (int w = 0; w < 16; ++w) m = max(m, sh[w]);
+        sh_e = m;
+    }
+    __syncthreads();
+    const uint32_t E = sh_e;
+
+    uint32_t running = 0;
+    for (uint32_t base = 0; base < nt; base += 1024) {
+        const uint32_t i = base + tid;
+        uint32_t kept = 0, shift = 0;
+        if (i < nt) {
+            const uint4 lo = reinterpret_cast<const uint4*>(H + i)[0];
+            const uint32_t w4 = H[i].w[4];
+            shift = E - (w4 >> 16);
+            if (E != 0 && shift <= 8) {
+                const uint32_t h[9] = {lo.x & 0xFFFFu, lo.x >> 16, lo.y & 0xFFFFu, lo.y >> 16, lo.z & 0xFFFFu,
+                                       lo.z >> 16, lo.w & 0xFFFFu, lo.w >> 16, w4 & 0xFFFFu};
+                const uint32_t lim = 8 - shift;            // entries with rel <= lim are encoded
+#pragma unroll
+                for (int j = 0; j < 9; ++j) kept += ((uint32_t)j <= lim) ? h[j] : 0u;
+            }
+        }
+        uint32_t total;
+        const uint32_t incl = block_scan_1024(kept, sh, total);
+        if (i < nt) {
+            H[i].w[5] = running + incl - kept;
+            H[i].w[6] = shift;
+            H[i].w[7] = kept;
+        }
+        running += total;
+    }
+    if (tid == 0) {
+        GroupTmp t;
+        t.exp_field = running ? E : 0u;
+        t.count = running;
+        gtmp[k] = t;
+    }
+}
+
+__global__ __launch_bounds__(1024) void k_header_scan(const GroupTmp* __restrict__ gtmp, uint32_t n_groups,
+                                                      vgc_group_hdr* __restrict__ hdrs_out,
+                                                      vgc_pack_status* __restrict__ status, uint64_t words_cap) {
+    __shared__ uint32_t sh[16];
+    uint64_t running = 0;
+    for (uint32_t base = 0; base < n_groups; base += 1024) {
+        const uint32_t k = base + threadIdx.x;
+        GroupTmp t = {0u, 0u};
+        if (k < n_groups) t = gtmp[k];
+        // a chunk of 1024 groups holds at most 1024 * 2^28 words: scan the low and high parts separately
+        const uint32_t lo = t.count & 0xFFFFu, hi = t.count >> 16;
+        uint32_t tot_lo, tot_hi;
+        const uint32_t incl_lo = block_scan_1024(lo, sh, tot_lo);
+        const uint32_t incl_hi = block_scan_1024(hi, sh, tot_hi);
+        const uint64_t incl = (uint64_t)incl_lo + ((uint64_t)incl_hi << 16);
+        if (k < n_groups) {
+            vgc_group_hdr h;
+            h.exp_field = t.exp_field;
+            h.count = t.count;
+            h.word_offset = running + incl - t.count;
+            hdrs_out[k] = h;
+        }
+        running += (uint64_t)tot_lo + ((uint64_t)tot_hi << 16);
+    }
+    if (threadIdx.x == 0) {
+        vgc_pack_status st;
+        st.total_words = running;
+        st.overflow = running > words_cap ? 1u : 0u;
+        st.reserved = 0;
+        *status = st;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_emit(const PlanTile* __restrict__ tiles, uint64_t n_tiles,
+                                              const TileHdr* __restrict__ hdrs, const uint16_t* __restrict__ staging,
+                                              const vgc_group_hdr* __restrict__ ghdrs,
+                                              uint32_t* __restrict__ words, uint64_t words_cap) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint64_t t = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= n_tiles) return;
+    const TileHdr* H = hdrs + t;
+    const uint32_t kept = H->w[7];
+    if (kept == 0) return;
+    const uint4 lo = reinterpret_cast<const uint4*>(H)[0];
+    const uint32_t w4 = H->w[4];
+    const uint32_t cnt = (lo.x & 0xFFFFu) + (lo.x >> 16) + (lo.y & 0xFFFFu) + (lo.y >> 16) + (lo.z & 0xFFFFu) +
+                         (lo.z >> 16) + (lo.w & 0xFFFFu) + (lo.w >> 16) + (w4 & 0xFFFFu);
+    const uint32_t shift = H->w[6];
+    const uint32_t lim = 8 - shift;                         // kept != 0 implies shift <= 8
+    const PlanTile pt = tiles[t];
+    uint64_t out = ghdrs[pt.group].word_offset + H->w[5];
+    const uint16_t* st = staging + t * kTile;
+    for (uint32_t j0 = 0; j0 < cnt; j0 += 64) {
+        const uint32_t j = j0 + lane;
+        uint32_t e = 0xFFFFu;
+        if (j < cnt) e = st[j];
+        const uint32_t rel = e >> 12;
+        const bool keep = (j < cnt) && (rel <= lim);
+        const uint32_t sr = shift + rel;
+        const uint32_t d = sr ? sr - 1u : 0u;               // min(rounded exponent, E_k) subtracted from E_k
+        const uint32_t word = (((e >> 11) & 1u) << 31) | (d << 28) | (pt.start + (e & 0x7FFu));
+        const uint64_t b = __ballot(keep);
+        const uint64_t pos = out + rank_below64(b);
+        if (keep && pos < words_cap) words[pos] = word;
+        out += (uint32_t)__popcll(b);
+    }
+}
+
+int launch_pack(const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles, uint32_t n_groups,
+                TileHdr* hdrs, GroupTmp* gtmp, const uint16_t* staging,
+                uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
+                vgc_pack_status* status_out, hipStream_t stream) {
+    hipLaunchKernelGGL(k_group_scan, dim3(n_groups), dim3(1024), 0, stream, groups, hdrs, gtmp);
+    hipLaunchKernelGGL(k_header_scan, dim3(1), dim3(1024), 0, stream, gtmp, n_groups, hdrs_out, status_out, words_cap);
+    const uint64_t blocks = (n_tiles + 3) / 4;
+    hipLaunchKernelGGL(k_emit, dim3((uint32_t)blocks), dim3(256), 0, stream, tiles, n_tiles, hdrs, staging,
+                       hdrs_out, words_out, words_cap);
+    return hip_check(hipGetLastError(), "launch pack kernels");
+}
+
+}  // namespace vgc

@@ -1,0 +1,185 @@
+"""ctypes binding of libvgc.so: same names as the C ABI in include/vgc.h, argument
+marshalling only.  torch tensors supply device memory (`data_ptr()`) and the current
+HIP stream; every step of the path runs in the library's kernels.
+
+There is no fallback: if the library is missing or a call fails, this raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libvgc.so")
+
+F32, BF16 = 0, 1
+FC, CONV = 0, 1
+
+
+class VgcError(RuntimeError):
+    pass
+
+
+class Group(C.Structure):
+    _fields_ = [("offset", C.c_uint64), ("size", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+class GroupHdr(C.Structure):
+    _fields_ = [("exp_field", C.c_uint32), ("count", C.c_uint32), ("word_offset", C.c_uint64)]
+
+
+class PackStatus(C.Structure):
+    _fields_ = [("total_words", C.c_uint64), ("overflow", C.c_uint32), ("reserved", C.c_uint32)]
+
+
+HDR_DTYPE = np.dtype([("exp_field", "<u4"), ("count", "<u4"), ("word_offset", "<u8")])
+
+EXPORTS = {
+    # name: (restype, argtypes)
+    "vgc_last_error": (C.c_char_p, []),
+    "vgc_tile_size": (C.c_uint32, []),
+    "vgc_tile_count": (C.c_uint64, [C.c_void_p, C.c_uint32, C.c_uint64]),
+    "vgc_plan_bytes": (C.c_size_t, [C.c_void_p, C.c_uint32, C.c_uint64]),
+    "vgc_scratch_bytes": (C.c_size_t, [C.c_void_p, C.c_uint32, C.c_uint64]),
+    "vgc_scratch_bitmap_offset": (C.c_size_t, [C.c_void_p, C.c_uint32, C.c_uint64]),
+    "vgc_plan_build": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_size_t]),
+    "vgc_sqgrad": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
+                             C.c_uint32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "vgc_accumulate_select": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
+                                        C.c_uint32, C.c_void_p, C.c_float, C.c_float, C.c_void_p, C.c_void_p]),
+    "vgc_pack": (C.c_int, [C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
+                           C.c_void_p, C.c_void_p, C.c_void_p]),
+    "vgc_unpack_add": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
+                                 C.c_float, C.c_void_p, C.c_uint64, C.c_void_p]),
+}
+
+_lib = None
+
+
+def load():
+    """Load libvgc.so (built by `python -m paper_1802_06058_amd.build`)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise VgcError(f"{LIB_PATH} is not built; run `python -m paper_1802_06058_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in EXPORTS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise VgcError(f"vgc error {rc}: {load().vgc_last_error().decode()}")
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def tile_size():
+    return int(load().vgc_tile_size())
+
+
+class Plan:
+    """Host group list + the device plan table built from it (shared by all worker
+    states and by the decoder)."""
+
+    def __init__(self, groups, device="cuda"):
+        import torch
+        lib = load()
+        self.n_groups = len(groups)
+        self.groups = [(int(o), int(s)) for o, s in groups]
+        self.n = sum(s for _, s in self.groups)
+        arr = (Group * self.n_groups)()
+        for k, (o, s) in enumerate(self.groups):
+            arr[k].offset, arr[k].size, arr[k].reserved = o, s, 0
+        self.c_groups = arr
+        nbytes = lib.vgc_plan_bytes(arr, self.n_groups, self.n)
+        if nbytes == 0:
+            raise VgcError(lib.vgc_last_error().decode())
+        host = torch.empty(nbytes, dtype=torch.uint8)
+        _check(lib.vgc_plan_build(arr, self.n_groups, self.n, C.c_void_p(host.data_ptr()), nbytes))
+        self.plan_host = host
+        self.plan = host.to(device)
+        self.n_tiles = int(lib.vgc_tile_count(arr, self.n_groups, self.n))
+        self.scratch_bytes = int(lib.vgc_scratch_bytes(arr, self.n_groups, self.n))
+        self.bitmap_offset = int(lib.vgc_scratch_bitmap_offset(arr, self.n_groups, self.n))
+        self.device = device
+
+    def new_scratch(self):
+        import torch
+        return torch.empty(self.scratch_bytes, dtype=torch.uint8, device=self.device)
+
+    def new_headers(self):
+        import torch
+        return torch.zeros(self.n_groups * C.sizeof(GroupHdr), dtype=torch.uint8, device=self.device)
+
+    def new_status(self):
+        import torch
+        return torch.zeros(C.sizeof(PackStatus), dtype=torch.uint8, device=self.device)
+
+    def send_mask(self, scratch):
+        """Send bitmap of the last vgc_accumulate_select, reordered from tile order to
+        the flat parameter order (host side; for inspection and tests)."""
+        T = tile_size()
+        raw = scratch[self.bitmap_offset:self.bitmap_offset + self.n_tiles * (T // 8)].cpu().numpy()
+        bits = np.unpackbits(raw, bitorder="little").reshape(self.n_tiles, T).astype(bool)
+        out = np.empty(self.n, dtype=bool)
+        t = 0
+        for off, size in self.groups:
+            nt = (size + T - 1) // T
+            out[off:off + size] = bits[t:t + nt].reshape(-1)[:size]
+            t += nt
+        return out
+
+
+def read_headers(hdrs):
+    """[(exp_field, count, word_offset)] from a device header tensor."""
+    a = hdrs.cpu().numpy().view(HDR_DTYPE)
+    return [(int(x["exp_field"]), int(x["count"]), int(x["word_offset"])) for x in a]
+
+
+def read_status(status):
+    """(total_words, overflow) from a device status tensor (synchronises)."""
+    a = status.cpu().numpy()
+    return int(a[:8].view("<u8")[0]), int(a[8:12].view("<u4")[0])
+
+
+def sqgrad(kind, X, D, c, s_out, g_out=None):
+    """vgc_sqgrad.  X, D: float32 or bfloat16 tensors, [B, J]/[B, C] (FC) or [B, P, J]/[B, P, C] (CONV)."""
+    import torch
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(X.dtype)
+    if dtype is None or D.dtype != X.dtype:
+        raise VgcError(f"unsupported dtypes {X.dtype}, {D.dtype}")
+    if kind == FC:
+        B, J = X.shape
+        P, Cc = 1, D.shape[1]
+    else:
+        B, P, J = X.shape
+        Cc = D.shape[2]
+    _check(load().vgc_sqgrad(kind, dtype, _ptr(X), _ptr(D), B, P, J, Cc, float(c), _ptr(g_out), _ptr(s_out), _stream()))
+
+
+def accumulate_select(g, s, r, v, plan, alpha, zeta, scratch):
+    _check(load().vgc_accumulate_select(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups, plan.n_groups,
+                                        _ptr(plan.plan), float(alpha), float(zeta), _ptr(scratch), _stream()))
+
+
+def pack(plan, scratch, words, hdrs, status):
+    _check(load().vgc_pack(plan.n, plan.c_groups, plan.n_groups, _ptr(plan.plan), _ptr(scratch), _ptr(words),
+                           words.numel(), _ptr(hdrs), _ptr(status), _stream()))
+
+
+def unpack_add(words, n_words, hdrs, plan, scale, dense):
+    _check(load().vgc_unpack_add(_ptr(words), int(n_words), _ptr(hdrs), plan.c_groups, plan.n_groups,
+                                 _ptr(plan.plan), float(scale), _ptr(dense), plan.n, _stream()))

@@ -12,6 +12,11 @@ GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # tests load the library that is built; only if none is there do they build it
+    from paper_1802_06058_amd import vgc
+    if not os.path.exists(vgc.LIB_PATH):
+        from paper_1802_06058_amd import build
+        build.build(verbose=False)
 
 
 def read_golden(name):

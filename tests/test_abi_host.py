@@ -1,0 +1,109 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+function the header declares, and its pure-host entry points (plan construction, argument
+validation) behave as documented."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_1802_06058_amd import vgc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "vgc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vgc_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    lib = vgc.load()
+    names = _declared()
+    assert {"vgc_sqgrad", "vgc_accumulate_select", "vgc_pack", "vgc_unpack_add"} <= set(names)
+    for name in names:
+        assert hasattr(lib, name), f"{name} is declared in vgc.h but not exported"
+    assert set(names) == set(vgc.EXPORTS), "binding and header disagree"
+
+
+def _groups(sizes):
+    arr = (vgc.Group * len(sizes))()
+    off = 0
+    for k, s in enumerate(sizes):
+        arr[k].offset, arr[k].size, arr[k].reserved = off, s, 0
+        off += s
+    return arr, off
+
+
+def test_plan_build_tiles_never_span_groups():
+    lib = vgc.load()
+    T = lib.vgc_tile_size()
+    assert T == 2048
+    sizes = [1, T, T + 1, 5 * T - 3, 10]
+    arr, n = _groups(sizes)
+    n_tiles = lib.vgc_tile_count(arr, len(sizes), n)
+    assert n_tiles == sum((s + T - 1) // T for s in sizes)
+    nbytes = lib.vgc_plan_bytes(arr, len(sizes), n)
+    buf = np.zeros(nbytes, np.uint8)
+    assert lib.vgc_plan_build(arr, len(sizes), n, buf.ctypes.data, nbytes) == 0
+    hdr = buf[:64].view("<u8")
+    assert hdr[1] == n and hdr[2] == n_tiles
+    groups_off, tiles_off = int(buf[32:40].view("<u8")[0]), int(buf[40:48].view("<u8")[0])
+    G = buf[groups_off:groups_off + 16 * len(sizes)].view(np.dtype([("offset", "<u8"), ("size", "<u4"), ("first", "<u4")]))
+    Tt = buf[tiles_off:tiles_off + 8 * n_tiles].view(np.dtype([("group", "<u4"), ("start", "<u4")]))
+    covered = np.zeros(n, np.int32)
+    for t in range(n_tiles):
+        k, start = int(Tt[t]["group"]), int(Tt[t]["start"])
+        assert start % T == 0 and start < sizes[k]
+        lo = int(G[k]["offset"]) + start
+        covered[lo:lo + min(T, sizes[k] - start)] += 1
+        if start == 0:
+            assert int(G[k]["first"]) == t
+    assert np.all(covered == 1)
+    assert lib.vgc_plan_build(arr, len(sizes), n, buf.ctypes.data, nbytes - 1) == -2
+    assert lib.vgc_scratch_bytes(arr, len(sizes), n) >= n_tiles * (32 + T // 8 + 2 * T)
+    assert lib.vgc_scratch_bitmap_offset(arr, len(sizes), n) % 256 == 0
+
+
+def test_group_validation():
+    lib = vgc.load()
+    arr, n = _groups([10, 20])
+    assert lib.vgc_tile_count(arr, 2, n) == 2
+    assert lib.vgc_tile_count(arr, 2, n + 1) == 0 and b"cover" in lib.vgc_last_error()
+    arr[1].offset = 11
+    assert lib.vgc_tile_count(arr, 2, 31) == 0 and b"tile" in lib.vgc_last_error()
+    arr, n = _groups([10, 0])
+    assert lib.vgc_plan_bytes(arr, 2, 10) == 0 and b"empty" in lib.vgc_last_error()
+    big = (vgc.Group * 1)()
+    big[0].offset, big[0].size = 0, (1 << 28) + 1
+    buf = np.zeros(64, np.uint8)
+    assert lib.vgc_plan_build(big, 1, (1 << 28) + 1, buf.ctypes.data, 64) == -3
+    big[0].size = 1 << 28
+    assert lib.vgc_tile_count(big, 1, 1 << 28) == (1 << 28) // 2048
+    assert lib.vgc_tile_count(None, 1, 5) == 0
+
+
+def test_compute_calls_validate_before_touching_the_gpu():
+    """Argument errors are detected on the host: these return without any HIP call."""
+    lib = vgc.load()
+    arr, n = _groups([100])
+    one = C.c_void_p(256)          # non-NULL, aligned, never dereferenced on an argument error
+    assert lib.vgc_accumulate_select(None, one, one, one, n, arr, 1, one, 1.0, 0.999, one, None) == -1
+    assert lib.vgc_accumulate_select(one, one, one, one, n, arr, 1, one, float("nan"), 0.999, one, None) == -6
+    assert lib.vgc_accumulate_select(one, one, one, one, n, arr, 1, one, 1.0, 0.0, one, None) == -6
+    assert lib.vgc_accumulate_select(one, one, one, one, n + 1, arr, 1, one, 1.0, 0.999, one, None) == -2
+    assert lib.vgc_accumulate_select(C.c_void_p(258), one, one, one, n, arr, 1, one, 1.0, 0.999, one, None) == -5
+    assert lib.vgc_pack(n, arr, 1, one, one, None, 10, one, one, None) == -1
+    assert lib.vgc_unpack_add(one, 5, one, arr, 1, one, float("inf"), one, n, None) == -6
+    assert lib.vgc_sqgrad(2, 0, one, one, 1, 1, 1, 1, 1.0, None, one, None) == -4
+    assert lib.vgc_sqgrad(0, 0, one, one, 0, 1, 1, 1, 1.0, None, one, None) == -2
+    assert lib.vgc_sqgrad(0, 0, C.c_void_p(260), one, 1, 1, 1, 1, 1.0, None, one, None) == -5
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    monkeypatch.setattr(vgc, "_lib", None)
+    monkeypatch.setattr(vgc, "LIB_PATH", str(tmp_path / "libvgc.so"))
+    with pytest.raises(vgc.VgcError):
+        vgc.load()
