@@ -1,0 +1,218 @@
+#!/usr/bin/env python3
+"""Benchmark of the variance-based gradient compression hot path on one MI355X.
+
+Workload (default): the flat 1e9-parameter fp32 stream (Student-t(3) per-sample gradients,
+batch 16, squared sums precomputed), 8 simulated workers on the one GPU, groups of 2^24,
+alpha 1, zeta 0.999.  One step = one training iteration's compression work for all workers:
+for each worker vgc_accumulate_select + vgc_pack on its (r, v) state, then the dense buffer is
+cleared and the 8 packed messages are decoded into it with vgc_unpack_add.  Inputs (g, s for
+every worker and step) are resident in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` = parameters compressed per second (workers x N x steps / time).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--n", type=int, default=1_000_000_000, help="parameters per worker")
+    ap.add_argument("--workers", type=int, default=8)
+    ap.add_argument("--alpha", type=float, default=1.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sqgrad", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="upper bound on the parameters of the oracle-timed sample")
+    return ap.parse_args()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1802_06058_amd import vgc, workloads as W
+
+    if not os.path.exists(vgc.LIB_PATH):
+        from paper_1802_06058_amd import build
+        build.build()
+    vgc.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    cfg = W.CONFIGS["C5"]
+    N, P = a.n, a.workers
+    zeta, batch, nu = cfg["zeta"], cfg["batch"], cfg["nu"]
+    groups = W.flat_groups(N, cfg["group"])
+    plan = vgc.Plan(groups, dev)
+
+    # ---- inputs: a pool of P (g, s) pairs; worker w uses pair (w + step) % P at a step, so no worker
+    # sees a pair twice within P steps and every pair is resident before timing starts
+    t0 = time.time()
+    pool = [W.device_student_stream(N, batch, nu, cfg["seed"] + 1000 * i, dev) for i in range(P)]
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+
+    r = [torch.zeros(N, dtype=torch.float32, device=dev) for _ in range(P)]
+    v = [torch.zeros(N, dtype=torch.float32, device=dev) for _ in range(P)]
+    scratch = plan.new_scratch()
+    cap = N
+    words = [torch.empty(cap, dtype=torch.int32, device=dev) for _ in range(P)]
+    hdrs = [plan.new_headers() for _ in range(P)]
+    status = [plan.new_status() for _ in range(P)]
+    dense = torch.zeros(N, dtype=torch.float32, device=dev)
+    scale = 1.0 / P
+
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    sel_ms, pack_ms, dec_ms, sent_words = [], [], [], []
+
+    def step(k, record):
+        marks = []
+        for w in range(P):
+            g, s = pool[(w + k) % P]
+            e0, e1, e2 = ev(), ev(), ev()
+            e0.record()
+            vgc.accumulate_select(g, s, r[w], v[w], plan, a.alpha, zeta, scratch)
+            e1.record()
+            vgc.pack(plan, scratch, words[w], hdrs[w], status[w])
+            e2.record()
+            marks.append((e0, e1, e2))
+        torch.cuda.synchronize()                       # a receiver learns the message sizes from the transfer
+        counts = [vgc.read_status(status[w]) for w in range(P)]
+        d0, d1 = ev(), ev()
+        d0.record()
+        dense.zero_()
+        for w in range(P):
+            vgc.unpack_add(words[w], counts[w][0], hdrs[w], plan, scale, dense)
+        d1.record()
+        if record:
+            torch.cuda.synchronize()
+            for e0, e1, e2 in marks:
+                sel_ms.append(e0.elapsed_time(e1))
+                pack_ms.append(e1.elapsed_time(e2))
+            dec_ms.append(d0.elapsed_time(d1))
+            sent_words.append([c[0] for c in counts])
+            assert not any(c[1] for c in counts), "word buffer overflow"
+
+    for k in range(a.warmup):
+        step(k, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(a.warmup, a.warmup + a.steps):
+        step(k, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed * 1e3 / a.steps
+    value = P * N * a.steps / elapsed / 1e9
+    rho = float(np.mean(sent_words)) / N
+    sel = float(np.mean(sel_ms))
+    pk = float(np.mean(pack_ms))
+    dec = float(np.mean(dec_ms))
+    sel_gbs = 24.0 * N / (sel * 1e-3) / 1e9
+    sp_gbs = (24.0 + 4.0 * rho) * N / ((sel + pk) * 1e-3) / 1e9
+    dec_gbs = 12.0 * rho * N * P / (dec * 1e-3) / 1e9
+
+    out = {
+        "metric": "compressed params/sec", "value": round(value, 3), "unit": "Gparams/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "C5: flat 1e9-param fp32 stream, Student-t(3) per-sample gradients, batch 16, "
+                               "8 simulated workers, groups of 2^24, alpha 1, zeta 0.999",
+                   "n_params_per_worker": N, "workers": P, "alpha": a.alpha, "zeta": zeta,
+                   "n_groups": len(groups), "tile": vgc.tile_size(), "sent_fraction": round(rho, 5)},
+        "roofline": {"bound": "hbm", "kernel": "k_accumulate_select", "achieved": round(sel_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(sel_gbs / HBM_PEAK_GBS, 4),
+                     "traffic": None, "algorithmic_bytes_per_launch": 24.0 * N, "avg_launch_ms": round(sel, 4)},
+        "stages": {
+            "select_ms": round(sel, 4), "pack_ms": round(pk, 4), "decode_all_workers_ms": round(dec, 4),
+            "select_plus_pack": {"algorithmic_GBs": round(sp_gbs, 1), "frac_of_peak": round(sp_gbs / HBM_PEAK_GBS, 4),
+                                 "bytes_per_param": round(24.0 + 4.0 * rho, 3),
+                                 "Gparams_per_s": round(N / ((sel + pk) * 1e-3) / 1e9, 2)},
+            "decode": {"algorithmic_GBs": round(dec_gbs, 1), "frac_of_peak": round(dec_gbs / HBM_PEAK_GBS, 4),
+                       "bytes_per_word": 12},
+        },
+        "input_generation_s": round(gen_s, 1),
+    }
+
+    if not a.no_sqgrad:
+        out["stages"]["sqgrad"] = bench_sqgrad(dev)
+    if not a.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(pool[0], a, cfg, min(a.cpu_sample, N))
+    print(json.dumps(out))
+
+
+def bench_sqgrad(dev):
+    """Part (a) on two layer shapes of the VGG-16 configuration (bf16 inputs, batch 64)."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    res = {}
+    shapes = [("fc6_25088x4096_B64_bf16", vgc.FC, 64, 1, 25088, 4096),
+              ("conv4_2_P784_4608x512_B64_bf16", vgc.CONV, 64, 784, 4608, 512)]
+    for name, kind, B, P, J, C in shapes:
+        gen = torch.Generator(device=dev); gen.manual_seed(1)
+        shp_x = (B, J) if kind == vgc.FC else (B, P, J)
+        shp_d = (B, C) if kind == vgc.FC else (B, P, C)
+        X = torch.randn(shp_x, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        D = (torch.randn(shp_d, generator=gen, device=dev, dtype=torch.float32) * 1e-3).to(torch.bfloat16)
+        g = torch.empty(J, C, dtype=torch.float32, device=dev)
+        s = torch.empty(J, C, dtype=torch.float32, device=dev)
+        vgc.sqgrad(kind, X, D, 1.0 / B, s, g)
+        torch.cuda.synchronize()
+        reps = 3
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            vgc.sqgrad(kind, X, D, 1.0 / B, s, g)
+        e1.record(); torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        flops = (4.0 if kind == vgc.FC else 2.0) * B * P * J * C      # FC: two contractions; conv: one
+        byts = 8.0 * J * C + 2.0 * B * P * (J + C)
+        res[name] = {"ms": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 2),
+                     "GBs": round(byts / (ms * 1e-3) / 1e9, 1)}
+        del X, D, g, s
+    return res
+
+
+def cpu_baseline(pair, a, cfg, sample):
+    """The oracle, as it stands, on the leading groups of worker 0's first step: accumulate/select
+    + pack + decode of that message (NumPy, one thread).  Runs group after group (2^24 parameters
+    each) until about 10 s of CPU time are spent or `sample` parameters are done."""
+    from oracle import vgc_oracle as O
+    from paper_1802_06058_amd import workloads as W
+    gsz = cfg["group"]
+    done, dt = 0, 0.0
+    while done < sample and dt < 10.0:
+        m = min(gsz, sample - done)
+        g = pair[0][done:done + m].cpu().numpy()
+        s = pair[1][done:done + m].cpu().numpy()
+        groups = W.flat_groups(m, gsz)
+        z = np.zeros(m, np.float32)
+        t0 = time.perf_counter()
+        r_acc, r_out, v_out, send = O.accumulate_select(g, s, z, z, a.alpha, cfg["zeta"])
+        words, hdrs, _ = O.pack(r_acc, send, groups)
+        dense = np.zeros(m, np.float32)
+        O.unpack_add(words, hdrs, groups, 1.0 / a.workers, dense)
+        dt += time.perf_counter() - t0
+        done += m
+    return {"value": round(done / dt / 1e9, 5), "unit": "Gparams/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {done} parameters of one worker, one step (select + pack + decode of its message), "
+                      f"{dt:.1f} s; host has {os.cpu_count()} logical cores, NumPy element-wise code uses one"}
+
+
+if __name__ == "__main__":
+    main()

@@ -62,6 +62,9 @@ def load():
     """Load libvgc.so (built by `python -m paper_1802_06058_amd.build`)."""
     global _lib
     if _lib is None:
+        # torch first: it brings its own HIP runtime, and the library must bind to that same copy
+        # (device pointers and streams come from torch), not to a second one loaded before it
+        import torch  # noqa: F401
         if not os.path.exists(LIB_PATH):
             raise VgcError(f"{LIB_PATH} is not built; run `python -m paper_1802_06058_amd.build`")
         lib = C.CDLL(LIB_PATH)
