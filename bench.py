@@ -5,7 +5,8 @@ Workload (default): the flat 1e9-parameter fp32 stream (Student-t(3) per-sample 
 batch 16, squared sums precomputed), 8 simulated workers on the one GPU, groups of 2^24,
 alpha 1, zeta 0.999.  One step = one training iteration's compression work for all workers:
 for each worker vgc_accumulate_select + vgc_pack on its (r, v) state, then the dense buffer is
-cleared and the 8 packed messages are decoded into it with vgc_unpack_add.  Inputs (g, s for
+overwritten with the sum of the 8 decoded messages (vgc_unpack_add_batch; `--decode per-message`
+clears it and calls vgc_unpack_add once per message instead).  Inputs (g, s for
 every worker and step) are resident in HBM before the timed region starts.
 
 Prints ONE JSON line.  `value` = parameters compressed per second (workers x N x steps / time).
@@ -34,6 +35,8 @@ def parse():
     ap.add_argument("--n", type=int, default=1_000_000_000, help="parameters per worker")
     ap.add_argument("--workers", type=int, default=8)
     ap.add_argument("--alpha", type=float, default=1.0)
+    ap.add_argument("--decode", choices=["batch", "per-message"], default="batch",
+                    help="batch: all messages in one pass over the dense buffer; per-message: one launch each")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sqgrad", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="upper bound on the parameters of the oracle-timed sample")
@@ -95,9 +98,12 @@ def main():
         counts = [vgc.read_status(status[w]) for w in range(P)]
         d0, d1 = ev(), ev()
         d0.record()
-        dense.zero_()
-        for w in range(P):
-            vgc.unpack_add(words[w], counts[w][0], hdrs[w], plan, scale, dense)
+        if a.decode == "batch":
+            vgc.unpack_add_batch(words, [c[0] for c in counts], hdrs, plan, scale, dense, overwrite=True)
+        else:
+            dense.zero_()
+            for w in range(P):
+                vgc.unpack_add(words[w], counts[w][0], hdrs[w], plan, scale, dense)
         d1.record()
         if record:
             torch.cuda.synchronize()
@@ -144,7 +150,7 @@ def main():
                                  "bytes_per_param": round(24.0 + 4.0 * rho, 3),
                                  "Gparams_per_s": round(N / ((sel + pk) * 1e-3) / 1e9, 2)},
             "decode": {"algorithmic_GBs": round(dec_gbs, 1), "frac_of_peak": round(dec_gbs / HBM_PEAK_GBS, 4),
-                       "bytes_per_word": 12},
+                       "bytes_per_word": 12, "mode": a.decode},
         },
         "input_generation_s": round(gen_s, 1),
     }

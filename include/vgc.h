@@ -174,6 +174,22 @@ int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr*
                    const vgc_group* groups, uint32_t n_groups, const void* plan,
                    float scale, float* dense_out, uint64_t n, void* stream);
 
+/* Several messages in one pass over the dense buffer: the same result, bit for bit, as
+ * (overwrite ? clear dense_out : nothing) followed by vgc_unpack_add(message 0), ..., (message p-1),
+ * but dense_out is read and written once instead of p times.  Worth it when the messages together
+ * touch most of the buffer (Section 4.3 expects few index collisions at high compression ratios;
+ * there one launch per message moves less).
+ *
+ * words, hdrs: HOST arrays of p DEVICE pointers; n_words: HOST array of p counts (upper bounds
+ * allowed).  overwrite != 0: dense_out = sum of messages instead of dense_out += sum (also with p == 0).
+ * Messages must be well-formed (ascending indices inside a group, as vgc_pack writes them); a
+ * malformed one gives unspecified sums but no out-of-range access.
+ */
+int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words,
+                         const vgc_group_hdr* const* hdrs, uint32_t p,
+                         const vgc_group* groups, uint32_t n_groups, const void* plan,
+                         float scale, int overwrite, float* dense_out, uint64_t n, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -24,10 +24,11 @@ int hip_check(hipError_t e, const char* what) {
 }
 
 // Validates the group list and counts tiles.  Returns a vgc_status.
-static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, uint64_t* n_tiles_out) {
+static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, uint64_t* n_tiles_out,
+                        uint64_t* n_runs_out = nullptr) {
     if (!groups) { set_error("groups is NULL"); return VGC_ERR_NULL; }
     if (n == 0 || n_groups == 0) { set_error("n and n_groups must be positive"); return VGC_ERR_SIZE; }
-    uint64_t off = 0, tiles = 0;
+    uint64_t off = 0, tiles = 0, runs = 0;
     for (uint32_t k = 0; k < n_groups; ++k) {
         if (groups[k].size == 0) { set_error("group %u is empty", k); return VGC_ERR_SIZE; }
         if (groups[k].size > VGC_MAX_GROUP_SIZE) {
@@ -40,7 +41,9 @@ static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, 
             return VGC_ERR_SIZE;
         }
         off += groups[k].size;
-        tiles += (groups[k].size + kTile - 1) / kTile;
+        const uint64_t nt = (groups[k].size + kTile - 1) / kTile;
+        tiles += nt;
+        runs += (nt + kRunTiles - 1) / kRunTiles;
     }
     if (off != n) {
         set_error("groups cover %llu elements, n = %llu", (unsigned long long)off, (unsigned long long)n);
@@ -48,27 +51,34 @@ static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, 
     }
     if (tiles > 0x7FFFFFFFull) { set_error("too many tiles (%llu)", (unsigned long long)tiles); return VGC_ERR_SIZE; }
     if (n_tiles_out) *n_tiles_out = tiles;
+    if (n_runs_out) *n_runs_out = runs;
     return VGC_OK;
 }
 
-static size_t plan_bytes_for(uint64_t n_tiles, uint32_t n_groups, size_t* groups_off, size_t* tiles_off) {
+// The run table sits after the tile table; its size is bounded by the tile count, so the layout
+// reserves one PlanRun slot per tile and the offsets depend on (n_tiles, n_groups) only.
+static size_t plan_bytes_for(uint64_t n_tiles, uint32_t n_groups, size_t* groups_off, size_t* tiles_off,
+                             size_t* runs_off = nullptr) {
     size_t off = sizeof(PlanHeader);
     if (groups_off) *groups_off = off;
     off = align_up(off + (size_t)n_groups * sizeof(PlanGroup), 256);
     if (tiles_off) *tiles_off = off;
     off = align_up(off + n_tiles * sizeof(PlanTile), 256);
+    if (runs_off) *runs_off = off;
+    off = align_up(off + (n_tiles / kRunTiles + n_groups) * sizeof(PlanRun), 256);
     return off;
 }
 
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-struct PlanView { const PlanGroup* groups; const PlanTile* tiles; };
+struct PlanView { const PlanGroup* groups; const PlanTile* tiles; const PlanRun* runs; };
 
 static PlanView plan_view(const void* plan_dev, uint64_t n_tiles, uint32_t n_groups) {
-    size_t go, to;
-    plan_bytes_for(n_tiles, n_groups, &go, &to);
+    size_t go, to, ro;
+    plan_bytes_for(n_tiles, n_groups, &go, &to, &ro);
     const char* b = static_cast<const char*>(plan_dev);
-    return PlanView{reinterpret_cast<const PlanGroup*>(b + go), reinterpret_cast<const PlanTile*>(b + to)};
+    return PlanView{reinterpret_cast<const PlanGroup*>(b + go), reinterpret_cast<const PlanTile*>(b + to),
+                    reinterpret_cast<const PlanRun*>(b + ro)};
 }
 
 }  // namespace vgc
@@ -105,25 +115,28 @@ size_t vgc_scratch_bitmap_offset(const vgc_group* groups, uint32_t n_groups, uin
 }
 
 int vgc_plan_build(const vgc_group* groups, uint32_t n_groups, uint64_t n, void* plan_host, size_t plan_bytes) {
-    uint64_t n_tiles = 0;
-    int rc = check_groups(groups, n_groups, n, &n_tiles);
+    uint64_t n_tiles = 0, n_runs = 0;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &n_runs);
     if (rc != VGC_OK) return rc;
     if (!plan_host) { set_error("plan_host is NULL"); return VGC_ERR_NULL; }
-    size_t go, to;
-    const size_t need = plan_bytes_for(n_tiles, n_groups, &go, &to);
+    size_t go, to, ro;
+    const size_t need = plan_bytes_for(n_tiles, n_groups, &go, &to, &ro);
     if (plan_bytes < need) { set_error("plan buffer has %zu bytes, %zu needed", plan_bytes, need); return VGC_ERR_SIZE; }
     char* b = static_cast<char*>(plan_host);
     memset(b, 0, need);
     PlanHeader* h = reinterpret_cast<PlanHeader*>(b);
     h->magic = kPlanMagic; h->n = n; h->n_tiles = n_tiles; h->n_groups = n_groups; h->tile = kTile;
-    h->groups_off = go; h->tiles_off = to;
+    h->groups_off = go; h->tiles_off = to; h->runs_off = ro; h->n_runs = n_runs;
     PlanGroup* G = reinterpret_cast<PlanGroup*>(b + go);
     PlanTile* T = reinterpret_cast<PlanTile*>(b + to);
-    uint64_t t = 0;
+    PlanRun* R = reinterpret_cast<PlanRun*>(b + ro);
+    uint64_t t = 0, rn = 0;
     for (uint32_t k = 0; k < n_groups; ++k) {
         G[k].offset = groups[k].offset; G[k].size = groups[k].size; G[k].first_tile = (uint32_t)t;
-        for (uint64_t start = 0; start < groups[k].size; start += kTile, ++t) {
+        uint32_t in_group = 0;
+        for (uint64_t start = 0; start < groups[k].size; start += kTile, ++t, ++in_group) {
             T[t].group = k; T[t].start = (uint32_t)start;
+            if (in_group % kRunTiles == 0) { R[rn].group = k; R[rn].first_tile = in_group; ++rn; }
         }
     }
     return VGC_OK;
@@ -208,6 +221,25 @@ int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr*
     if (!std::isfinite(scale)) { set_error("vgc_unpack_add: scale is not finite"); return VGC_ERR_PARAM; }
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
     return launch_unpack_add(words, n_words, hdrs, pv.groups, n_groups, scale, dense_out, static_cast<hipStream_t>(stream));
+}
+
+int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+                         uint32_t p, const vgc_group* groups, uint32_t n_groups, const void* plan,
+                         float scale, int overwrite, float* dense_out, uint64_t n, void* stream) {
+    if (!plan || !dense_out || (p && (!words || !n_words || !hdrs))) { set_error("vgc_unpack_add_batch: NULL pointer"); return VGC_ERR_NULL; }
+    uint64_t n_tiles = 0, n_runs = 0;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &n_runs);
+    if (rc != VGC_OK) return rc;
+    for (uint32_t w = 0; w < p; ++w) {
+        if (!hdrs[w] || (!words[w] && n_words[w])) { set_error("vgc_unpack_add_batch: message %u has a NULL pointer", w); return VGC_ERR_NULL; }
+        if (!aligned(words[w], 4) || !aligned(hdrs[w], 8)) { set_error("vgc_unpack_add_batch: message %u is misaligned", w); return VGC_ERR_ALIGN; }
+    }
+    if (!aligned(plan, 256) || !aligned(dense_out, 4)) { set_error("vgc_unpack_add_batch: misaligned pointer"); return VGC_ERR_ALIGN; }
+    if (!std::isfinite(scale)) { set_error("vgc_unpack_add_batch: scale is not finite"); return VGC_ERR_PARAM; }
+    if (p == 0 && !overwrite) return VGC_OK;
+    const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    return launch_unpack_add_batch(words, n_words, hdrs, p, pv.groups, pv.runs, n_runs, scale, overwrite, dense_out,
+                                   static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

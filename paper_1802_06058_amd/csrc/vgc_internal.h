@@ -28,7 +28,8 @@ struct PlanHeader {            // 64 bytes at the start of the plan blob
     uint32_t tile;
     uint64_t groups_off;       // byte offset of PlanGroup[n_groups]
     uint64_t tiles_off;        // byte offset of PlanTile[n_tiles]
-    uint64_t pad[2];
+    uint64_t runs_off;         // byte offset of PlanRun[n_runs]
+    uint64_t n_runs;
 };
 
 struct PlanGroup {             // 16 bytes
@@ -40,6 +41,14 @@ struct PlanGroup {             // 16 bytes
 struct PlanTile {              // 8 bytes
     uint32_t group;
     uint32_t start;            // element offset of the tile inside its group (multiple of kTile)
+};
+
+// A run is up to kRunTiles consecutive tiles of one group: the unit one wave of the batched
+// decoder owns.
+constexpr uint32_t kRunTiles = 64;
+struct PlanRun {               // 8 bytes
+    uint32_t group;
+    uint32_t first_tile;       // index of the run's first tile inside its group
 };
 
 // Per-tile record in the scratch.  Written by the accumulate kernel (w[0..4]) and completed by
@@ -99,6 +108,11 @@ int launch_pack(const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles
 int launch_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
                       const PlanGroup* groups, uint32_t n_groups, float scale, float* dense,
                       hipStream_t stream);
+
+constexpr int kBatchMax = 8;   // messages one launch of the batched decoder takes
+int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+                            uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs,
+                            float scale, int overwrite, float* dense, hipStream_t stream);
 
 int launch_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
                   uint32_t J, uint32_t C, float c, float* g_out, float* s_out, hipStream_t stream);

@@ -53,6 +53,8 @@ EXPORTS = {
                            C.c_void_p, C.c_void_p, C.c_void_p]),
     "vgc_unpack_add": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                  C.c_float, C.c_void_p, C.c_uint64, C.c_void_p]),
+    "vgc_unpack_add_batch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
+                                       C.c_void_p, C.c_float, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
 }
 
 _lib = None
@@ -186,3 +188,13 @@ def pack(plan, scratch, words, hdrs, status):
 def unpack_add(words, n_words, hdrs, plan, scale, dense):
     _check(load().vgc_unpack_add(_ptr(words), int(n_words), _ptr(hdrs), plan.c_groups, plan.n_groups,
                                  _ptr(plan.plan), float(scale), _ptr(dense), plan.n, _stream()))
+
+
+def unpack_add_batch(words, n_words, hdrs, plan, scale, dense, overwrite=False):
+    """vgc_unpack_add_batch: lists of word tensors, counts and header tensors, one per message."""
+    p = len(words)
+    wp = (C.c_void_p * max(p, 1))(*[w.data_ptr() for w in words])
+    hp = (C.c_void_p * max(p, 1))(*[h.data_ptr() for h in hdrs])
+    nw = (C.c_uint64 * max(p, 1))(*[int(x) for x in n_words])
+    _check(load().vgc_unpack_add_batch(wp, nw, hp, p, plan.c_groups, plan.n_groups, _ptr(plan.plan), float(scale),
+                                       1 if overwrite else 0, _ptr(dense), plan.n, _stream()))

@@ -273,3 +273,43 @@ def test_abi_rejects_bad_arguments(dev):
     with pytest.raises(vgc.VgcError):
         vgc.accumulate_select(t, t, t, None, plan, 1.0, 0.999, sc)
     assert float(t.abs().sum()) == 0.0
+
+
+@pytest.mark.parametrize("p,overwrite", [(0, True), (1, False), (3, True), (8, False), (11, True)])
+def test_unpack_add_batch_equals_sequential(dev, p, overwrite):
+    """One pass over the dense buffer for p messages: bit-identical to the oracle applying the
+    messages one after another (and so to p single-message launches).  Groups span several runs
+    of 64 tiles, have ragged tails and odd offsets; message densities differ widely."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    sizes = [2048 * 70 + 5, 3, 5000, 2048 * 130, 1]
+    groups = W.groups_from_sizes(sizes)
+    n = sum(sizes)
+    plan = vgc.Plan(groups, dev)
+    rng = np.random.default_rng(p)
+    dense0 = rng.standard_normal(n).astype(F32)
+    expect = np.zeros(n, F32) if overwrite else dense0.copy()
+    dense = _dev(dense0, dev)
+    dense_seq = torch.zeros(n, dtype=torch.float32, device=dev) if overwrite else _dev(dense0, dev)
+    d_words, d_hdrs, counts = [], [], []
+    scale = 1.0 / 3.0
+    for w in range(p):
+        g, s = W.sample_stream(16, (p, w), n, 16, "student", sigma=10.0 ** rng.uniform(-3, 0))
+        z = np.zeros(n, F32)
+        alpha = [0.0, 1.0, 4.0, 12.0][w % 4]                   # dense, typical, sparse, very sparse messages
+        r_acc, _, _, send = O.accumulate_select(g, s, z, z, alpha, 0.999)
+        if w == 2:
+            send[: 2048 * 70 + 5] = False                      # a whole group absent from this message
+        words, hdrs, _ = O.pack(r_acc, send, groups)
+        O.unpack_add(words, hdrs, groups, scale, expect)
+        pad = np.full(words.size + 100, 0x12345678, np.uint32)  # junk past the message; counts are upper bounds
+        pad[:words.size] = words
+        d_words.append(_dev(pad.view(np.int32), dev))
+        d_hdrs.append(_dev(np.array(hdrs, dtype=vgc.HDR_DTYPE).view(np.uint8), dev))
+        counts.append(words.size + (50 if w % 2 else 0))
+        vgc.unpack_add(d_words[-1], counts[-1], d_hdrs[-1], plan, scale, dense_seq)
+    vgc.unpack_add_batch(d_words, counts, d_hdrs, plan, scale, dense, overwrite=overwrite)
+    torch.cuda.synchronize()
+    got = dense.cpu().numpy()
+    assert np.array_equal(_bits(got), _bits(expect)), f"{np.flatnonzero(_bits(got) != _bits(expect))[:10]}"
+    assert np.array_equal(_bits(dense_seq.cpu().numpy()), _bits(expect))
