@@ -132,34 +132,49 @@ __global__ __launch_bounds__(256) void k_emit(const PlanTile* __restrict__ tiles
                                               const TileHdr* __restrict__ hdrs, const uint16_t* __restrict__ staging,
                                               const vgc_group_hdr* __restrict__ ghdrs,
                                               uint32_t* __restrict__ words, uint64_t words_cap) {
+    constexpr int kAhead = 8;                               // rounds of 64 entries loaded before anything is known
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t t = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= n_tiles) return;
-    const TileHdr* H = hdrs + t;
-    const uint32_t kept = H->w[7];
-    if (kept == 0) return;
-    const uint4 lo = reinterpret_cast<const uint4*>(H)[0];
-    const uint32_t w4 = H->w[4];
-    const uint32_t cnt = (lo.x & 0xFFFFu) + (lo.x >> 16) + (lo.y & 0xFFFFu) + (lo.y >> 16) + (lo.z & 0xFFFFu) +
-                         (lo.z >> 16) + (lo.w & 0xFFFFu) + (lo.w >> 16) + (w4 & 0xFFFFu);
-    const uint32_t shift = H->w[6];
-    const uint32_t lim = 8 - shift;                         // kept != 0 implies shift <= 8
-    const PlanTile pt = tiles[t];
-    uint64_t out = ghdrs[pt.group].word_offset + H->w[5];
     const uint16_t* st = staging + t * kTile;
-    for (uint32_t j0 = 0; j0 < cnt; j0 += 64) {
-        const uint32_t j = j0 + lane;
-        uint32_t e = 0xFFFFu;
-        if (j < cnt) e = st[j];
-        const uint32_t rel = e >> 12;
-        const bool keep = (j < cnt) && (rel <= lim);
-        const uint32_t sr = shift + rel;
-        const uint32_t d = sr ? sr - 1u : 0u;               // min(rounded exponent, E_k) subtracted from E_k
-        const uint32_t word = (((e >> 11) & 1u) << 31) | (d << 28) | (pt.start + (e & 0x7FFu));
-        const uint64_t b = __ballot(keep);
-        const uint64_t pos = out + rank_below64(b);
-        if (keep && pos < words_cap) words[pos] = word;
-        out += (uint32_t)__popcll(b);
+    // Every tile owns kTile staging slots, so the first rounds can be fetched before the tile's count
+    // is known (slots past the count hold stale data and are ignored): the loads overlap the header's.
+    uint32_t e[kAhead];
+#pragma unroll
+    for (int j = 0; j < kAhead; ++j) e[j] = __builtin_nontemporal_load(st + j * 64 + lane);
+    const uint32_t hw = (lane < 8) ? hdrs[t].w[lane] : 0u;  // one 32-byte read per wave
+    const PlanTile pt = tiles[t];
+    uint32_t w[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) w[i] = (uint32_t)__shfl((int)hw, i);
+    const uint32_t kept = w[7];
+    if (kept == 0) return;
+    const uint32_t cnt = (w[0] & 0xFFFFu) + (w[0] >> 16) + (w[1] & 0xFFFFu) + (w[1] >> 16) + (w[2] & 0xFFFFu) +
+                         (w[2] >> 16) + (w[3] & 0xFFFFu) + (w[3] >> 16) + (w[4] & 0xFFFFu);
+    const uint32_t shift = w[6];
+    const uint32_t lim = 8 - shift;                         // kept != 0 implies shift <= 8
+    uint64_t out = ghdrs[pt.group].word_offset + w[5];
+    for (uint32_t j0 = 0; j0 < cnt; j0 += 64 * kAhead) {
+        if (j0) {
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) {
+                const uint32_t jj = j0 + j * 64 + lane;
+                e[j] = (jj < kTile) ? (uint32_t)__builtin_nontemporal_load(st + jj) : 0xFFFFu;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kAhead; ++j) {
+            const uint32_t jj = j0 + j * 64 + lane;
+            const uint32_t rel = e[j] >> 12;
+            const bool keep = (jj < cnt) && (rel <= lim);
+            const uint32_t sr = shift + rel;
+            const uint32_t d = sr ? sr - 1u : 0u;           // E_k minus min(rounded exponent, E_k)
+            const uint32_t word = (((e[j] >> 11) & 1u) << 31) | (d << 28) | (pt.start + (e[j] & 0x7FFu));
+            const uint64_t b = __ballot(keep);
+            const uint64_t pos = out + rank_below64(b);
+            if (keep && pos < words_cap) __builtin_nontemporal_store(word, words + pos);
+            out += (uint32_t)__popcll(b);
+        }
     }
 }
 
