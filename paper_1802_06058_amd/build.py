@@ -14,6 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvgc.so")
+MICROBENCH = os.path.join(HERE, "vgc_microbench")
 OBJDIR = os.path.join(ROOT, "_build", "vgc")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -51,8 +52,15 @@ def build(verbose=True):
     if p.returncode != 0:
         raise RuntimeError("link failed:\n" + p.stderr)
     os.replace(tmp, LIB)
+    # native driver of the C ABI (profiling without a Python process)
+    mb_src = os.path.join(CSRC, "microbench", "vgc_microbench.hip")
+    p = subprocess.run([HIPCC, *FLAGS, mb_src, "-o", MICROBENCH + ".tmp", "-L", HERE, "-lvgc", "-Wl,-rpath,$ORIGIN"],
+                       capture_output=True, text=True)
+    if p.returncode != 0:
+        raise RuntimeError("microbench build failed:\n" + p.stderr)
+    os.replace(MICROBENCH + ".tmp", MICROBENCH)
     if verbose:
-        print(f"built {LIB} ({os.path.getsize(LIB)} bytes) from {len(objs)} sources")
+        print(f"built {LIB} ({os.path.getsize(LIB)} bytes) from {len(objs)} sources, and {MICROBENCH}")
     return LIB
 
 

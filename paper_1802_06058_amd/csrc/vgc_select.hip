@@ -13,6 +13,7 @@
 namespace vgc {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t rank_below(uint64_t mask) {
     return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
@@ -46,6 +47,7 @@ __device__ __forceinline__ void tile_body(const float* __restrict__ g, const flo
     __shared__ uint32_t sh_wmax[4];
     __shared__ uint32_t sh_seg[32];
     __shared__ uint32_t sh_hist[4][kRelBins];
+    __shared__ __attribute__((aligned(16))) uint16_t sh_stage[kTile];
 
     const uint32_t tid = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -205,12 +207,19 @@ __device__ __forceinline__ void tile_body(const float* __restrict__ g, const flo
         if (lane >= (uint32_t)off) incl += y;
     }
     const uint32_t excl = incl - x;
+    const uint32_t n_staged = (uint32_t)__shfl((int)incl, 31);
+    // compact in LDS, then write the tile's entries as whole 16-byte pieces (the tile's staging area is
+    // 4 KiB-aligned; slots between the count and the next multiple of 8 receive stale values that the
+    // reader ignores)
 #pragma unroll
     for (int e = 0; e < E; ++e) {
         const int u = kVec ? (e >> 2) : e;
         const uint32_t segbase = (uint32_t)__shfl((int)excl, u * 4 + (int)wave);
-        if ((stagedmask >> e) & 1u) staging[segbase + rank[e]] = (uint16_t)entry[e];
+        if ((stagedmask >> e) & 1u) sh_stage[segbase + rank[e]] = (uint16_t)entry[e];
     }
+    __syncthreads();
+    if (tid * 8 < n_staged)
+        __builtin_nontemporal_store(reinterpret_cast<const uint4v*>(sh_stage)[tid], reinterpret_cast<uint4v*>(staging) + tid);
 
     if (tid == 0) {
         uint32_t h[kRelBins];
