@@ -148,7 +148,7 @@ def main():
                    "n_groups": len(groups), "tile": vgc.tile_size(), "sent_fraction": round(rho, 5)},
         "roofline": {"bound": "hbm", "kernel": "k_accumulate_select", "achieved": round(sel_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(sel_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None, "algorithmic_bytes_per_launch": 24.0 * N, "avg_launch_ms": round(sel, 4)},
+                     "traffic": measured_traffic(N), "algorithmic_bytes_per_launch": 24.0 * N, "avg_launch_ms": round(sel, 4)},
         "stages": {
             "select_ms": round(sel, 4), "pack_ms": round(pk, 4), "decode_all_workers_ms": round(dec, 4),
             "select_plus_pack": {"algorithmic_GBs": round(sp_gbs, 1), "frac_of_peak": round(sp_gbs / HBM_PEAK_GBS, 4),
@@ -165,6 +165,18 @@ def main():
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(pool[0], a, cfg, min(a.cpu_sample, N))
     print(json.dumps(out))
+
+
+def measured_traffic(N):
+    """HBM bytes per k_accumulate_select launch from the committed counter runs (profiles/), which were
+    taken at N = 1e9 and a sent fraction of about 0.2; None for any other size."""
+    path = os.path.join(ROOT, "profiles", "traffic_c5_microbench_pmc.txt")
+    if N != 1_000_000_000 or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("k_accumulate_select_traffic_bytes_per_launch_n1e9:"):
+            return float(line.split(":")[1])
+    return None
 
 
 def traffic_probe(a, dev, cfg, plan, N):
