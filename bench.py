@@ -37,8 +37,6 @@ def parse():
     ap.add_argument("--alpha", type=float, default=1.0)
     ap.add_argument("--decode", choices=["batch", "per-message"], default="batch",
                     help="batch: all messages in one pass over the dense buffer; per-message: one launch each")
-    ap.add_argument("--traffic-probe", action="store_true",
-                    help="short run for `rocprofv3 --pmc`: a plain copy of known size, then select+pack twice on one worker")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sqgrad", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="upper bound on the parameters of the oracle-timed sample")
@@ -64,9 +62,6 @@ def main():
     zeta, batch, nu = cfg["zeta"], cfg["batch"], cfg["nu"]
     groups = W.flat_groups(N, cfg["group"])
     plan = vgc.Plan(groups, dev)
-
-    if a.traffic_probe:
-        return traffic_probe(a, dev, cfg, plan, N)
 
     # ---- inputs: a pool of P (g, s) pairs; worker w uses pair (w + step) % P at a step, so no worker
     # sees a pair twice within P steps and every pair is resident before timing starts
@@ -177,31 +172,6 @@ def measured_traffic(N):
         if line.startswith("k_accumulate_select_traffic_bytes_per_launch_n1e9:"):
             return float(line.split(":")[1])
     return None
-
-
-def traffic_probe(a, dev, cfg, plan, N):
-    """Dispatches for the HBM-traffic counters: torch's float copy of N elements (reads 4N bytes, writes
-    4N bytes: the calibration kernel), then two steps of select + pack + batched decode of that one message."""
-    import torch
-    from paper_1802_06058_amd import vgc, workloads as W
-    g, s = W.device_student_stream(N, cfg["batch"], cfg["nu"], cfg["seed"], dev)
-    r = torch.zeros(N, dtype=torch.float32, device=dev)
-    v = torch.zeros(N, dtype=torch.float32, device=dev)
-    dense = torch.zeros(N, dtype=torch.float32, device=dev)
-    scratch = plan.new_scratch()
-    words = torch.empty(N, dtype=torch.int32, device=dev)
-    hdrs, status = plan.new_headers(), plan.new_status()
-    torch.cuda.synchronize()
-    dense.copy_(g)                                   # calibration: elementwise copy kernel, 4N read + 4N written
-    torch.cuda.synchronize()
-    for _ in range(2):
-        vgc.accumulate_select(g, s, r, v, plan, a.alpha, cfg["zeta"], scratch)
-        vgc.pack(plan, scratch, words, hdrs, status)
-        torch.cuda.synchronize()
-        total, _ = vgc.read_status(status)
-        vgc.unpack_add_batch([words], [total], [hdrs], plan, 1.0, dense, overwrite=True)
-        torch.cuda.synchronize()
-        print(json.dumps({"traffic_probe": True, "n": N, "words": total}))
 
 
 def bench_sqgrad(dev):

@@ -122,10 +122,16 @@ size_t vgc_scratch_bitmap_offset(const vgc_group* groups, uint32_t n_groups, uin
  * X, D: DEVICE, dtype VGC_F32 (float) or VGC_BF16 (bfloat16 bits), 16-byte aligned.
  * g_out (may be NULL), s_out: DEVICE float [J, C] row-major (the weight's own layout), 16-byte aligned.
  * Accumulation is in float32.  Errors: NULL, SIZE (a zero dimension, P != 1 for FC), DTYPE, ALIGN, PARAM.
+ *
+ * workspace: optional DEVICE buffer (16-byte aligned) of vgc_sqgrad_workspace_bytes() bytes.  When
+ * [J, C] has too few tiles to fill the chip the samples are split over more workgroups and the
+ * partial sums are added from the workspace in a fixed order (the result does not depend on
+ * scheduling).  With workspace == NULL or too small the call still works, without the split.
  */
+size_t vgc_sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C);
 int vgc_sqgrad(int kind, int dtype, const void* X, const void* D,
                uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
-               float* g_out, float* s_out, void* stream);
+               float* g_out, float* s_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /* ---- (b) accumulate, test, reset or decay ---------------------------------------------------
  * The body of Alg. 1's parameter loop with the criterion of Eq. 2 and the decay of Section 4.4,

@@ -142,8 +142,12 @@ int vgc_plan_build(const vgc_group* groups, uint32_t n_groups, uint64_t n, void*
     return VGC_OK;
 }
 
+size_t vgc_sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
+    return sqgrad_workspace_bytes(kind, dtype, B, P, J, C);
+}
+
 int vgc_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
-               float c, float* g_out, float* s_out, void* stream) {
+               float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, void* stream) {
     if (kind != VGC_FC && kind != VGC_CONV) { set_error("vgc_sqgrad: unknown kind %d", kind); return VGC_ERR_DTYPE; }
     if (dtype != VGC_F32 && dtype != VGC_BF16) { set_error("vgc_sqgrad: unknown dtype %d", dtype); return VGC_ERR_DTYPE; }
     if (!X || !D || !s_out) { set_error("vgc_sqgrad: X, D and s_out are required"); return VGC_ERR_NULL; }
@@ -154,7 +158,9 @@ int vgc_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, ui
         return VGC_ERR_ALIGN;
     }
     if (!std::isfinite(c)) { set_error("vgc_sqgrad: c is not finite"); return VGC_ERR_PARAM; }
-    return launch_sqgrad(kind, dtype, X, D, B, P, J, C, c, g_out, s_out, static_cast<hipStream_t>(stream));
+    if (workspace && !aligned(workspace, 16)) { set_error("vgc_sqgrad: workspace must be 16-byte aligned"); return VGC_ERR_ALIGN; }
+    return launch_sqgrad(kind, dtype, X, D, B, P, J, C, c, g_out, s_out, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream));
 }
 
 int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, uint64_t n,

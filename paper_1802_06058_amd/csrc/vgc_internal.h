@@ -115,7 +115,17 @@ int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_word
                             float scale, int overwrite, float* dense, hipStream_t stream);
 
 int launch_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
-                  uint32_t J, uint32_t C, float c, float* g_out, float* s_out, hipStream_t stream);
+                  uint32_t J, uint32_t C, float c, float* g_out, float* s_out,
+                  void* workspace, size_t workspace_bytes, hipStream_t stream);
+int launch_sqgrad_simple(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
+                         uint32_t J, uint32_t C, float c, float* g_out, float* s_out, hipStream_t stream);
+
+// LDS-tiled kernels (vgc_sqgrad_tiled.hip)
+uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C);
+bool conv_tiled_supported(int dtype, uint32_t J, uint32_t C);
+size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C);
+int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
+                      float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream);
 
 }  // namespace vgc
 #endif

@@ -79,7 +79,15 @@ __global__ __launch_bounds__(256) void k_sqgrad_simple(const T* __restrict__ X, 
 }
 
 int launch_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
-                  uint32_t J, uint32_t C, float c, float* g_out, float* s_out, hipStream_t stream) {
+                  uint32_t J, uint32_t C, float c, float* g_out, float* s_out,
+                  void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    if (kind == VGC_CONV && conv_tiled_supported(dtype, J, C))
+        return launch_conv_tiled(dtype, X, D, B, P, J, C, c, g_out, s_out, workspace, workspace_bytes, stream);
+    return launch_sqgrad_simple(kind, dtype, X, D, B, P, J, C, c, g_out, s_out, stream);
+}
+
+int launch_sqgrad_simple(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
+                         uint32_t J, uint32_t C, float c, float* g_out, float* s_out, hipStream_t stream) {
     dim3 grid((C + 63) / 64, (J + 63) / 64), block(256);
     if (grid.y > 65535u) {
         set_error("vgc_sqgrad: J = %u exceeds the launch limit", J);

@@ -45,8 +45,9 @@ EXPORTS = {
     "vgc_scratch_bytes": (C.c_size_t, [C.c_void_p, C.c_uint32, C.c_uint64]),
     "vgc_scratch_bitmap_offset": (C.c_size_t, [C.c_void_p, C.c_uint32, C.c_uint64]),
     "vgc_plan_build": (C.c_int, [C.c_void_p, C.c_uint32, C.c_uint64, C.c_void_p, C.c_size_t]),
+    "vgc_sqgrad_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]),
     "vgc_sqgrad": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
-                             C.c_uint32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
+                             C.c_uint32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "vgc_accumulate_select": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
                                         C.c_uint32, C.c_void_p, C.c_float, C.c_float, C.c_void_p, C.c_void_p]),
     "vgc_pack": (C.c_int, [C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
@@ -160,8 +161,13 @@ def read_status(status):
     return int(a[:8].view("<u8")[0]), int(a[8:12].view("<u4")[0])
 
 
-def sqgrad(kind, X, D, c, s_out, g_out=None):
-    """vgc_sqgrad.  X, D: float32 or bfloat16 tensors, [B, J]/[B, C] (FC) or [B, P, J]/[B, P, C] (CONV)."""
+def sqgrad_workspace_bytes(kind, dtype, B, P, J, Cc):
+    return int(load().vgc_sqgrad_workspace_bytes(kind, dtype, B, P, J, Cc))
+
+
+def sqgrad(kind, X, D, c, s_out, g_out=None, workspace=None):
+    """vgc_sqgrad.  X, D: float32 or bfloat16 tensors, [B, J]/[B, C] (FC) or [B, P, J]/[B, P, C] (CONV).
+    workspace: optional uint8 tensor of sqgrad_workspace_bytes() bytes."""
     import torch
     dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(X.dtype)
     if dtype is None or D.dtype != X.dtype:
@@ -172,7 +178,8 @@ def sqgrad(kind, X, D, c, s_out, g_out=None):
     else:
         B, P, J = X.shape
         Cc = D.shape[2]
-    _check(load().vgc_sqgrad(kind, dtype, _ptr(X), _ptr(D), B, P, J, Cc, float(c), _ptr(g_out), _ptr(s_out), _stream()))
+    _check(load().vgc_sqgrad(kind, dtype, _ptr(X), _ptr(D), B, P, J, Cc, float(c), _ptr(g_out), _ptr(s_out),
+                             _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()))
 
 
 def accumulate_select(g, s, r, v, plan, alpha, zeta, scratch):

@@ -97,9 +97,9 @@ def test_compute_calls_validate_before_touching_the_gpu():
     assert lib.vgc_accumulate_select(C.c_void_p(258), one, one, one, n, arr, 1, one, 1.0, 0.999, one, None) == -5
     assert lib.vgc_pack(n, arr, 1, one, one, None, 10, one, one, None) == -1
     assert lib.vgc_unpack_add(one, 5, one, arr, 1, one, float("inf"), one, n, None) == -6
-    assert lib.vgc_sqgrad(2, 0, one, one, 1, 1, 1, 1, 1.0, None, one, None) == -4
-    assert lib.vgc_sqgrad(0, 0, one, one, 0, 1, 1, 1, 1.0, None, one, None) == -2
-    assert lib.vgc_sqgrad(0, 0, C.c_void_p(260), one, 1, 1, 1, 1, 1.0, None, one, None) == -5
+    assert lib.vgc_sqgrad(2, 0, one, one, 1, 1, 1, 1, 1.0, None, one, None, 0, None) == -4
+    assert lib.vgc_sqgrad(0, 0, one, one, 0, 1, 1, 1, 1.0, None, one, None, 0, None) == -2
+    assert lib.vgc_sqgrad(0, 0, C.c_void_p(260), one, 1, 1, 1, 1, 1.0, None, one, None, 0, None) == -5
 
 
 def test_missing_library_fails_loudly(monkeypatch, tmp_path):
