@@ -26,11 +26,16 @@ typedef float f16v __attribute__((ext_vector_type(16)));
 typedef uint32_t u4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s4v* lds_s4v_ptr;
 
-constexpr int kBM = 128, kBN = 128;      // block tile of [J, C]
 constexpr int kKC = 32;                  // positions per LDS stage
-constexpr int kPitch = 160;              // bf16 elements per staged row: 128 + 32 so that 4 rows x 2 halves hit distinct banks
+constexpr int kDepth = 3;                // chunks in flight from global memory per thread
 
+// Row pitch (bf16 elements) of a staged tile of width W: W + 32, i.e. consecutive rows start 16 banks
+// apart, so the 4 rows x 2 column halves one half-wave reads with a transposing load fall on distinct banks.
+template <int W> struct Pitch { static constexpr int value = W + 32; };
+
+template <int W>
 __device__ __forceinline__ bf8v lds_frag_bf16(const uint16_t* tile, int ks, int mbase, uint32_t lane) {
+    constexpr int kPitch = Pitch<W>::value;
     const uint32_t r = lane & 15u, grp = lane >> 4;
     const uint32_t mhalf = grp & 1u, khalf = grp >> 1;
     const uint16_t* p = tile + (ks * 16 + khalf * 8 + (r >> 2)) * kPitch + mbase + mhalf * 16 + 4 * (r & 3u);
@@ -42,42 +47,65 @@ __device__ __forceinline__ bf8v lds_frag_bf16(const uint16_t* tile, int ks, int 
     return __builtin_bit_cast(bf8v, v);
 }
 
-// One staged chunk of an operand: rows p0 .. p0+31 of a [P, W] bf16 matrix, columns w0 .. w0+127.
-struct ChunkRegs { u4v v[2]; };
+// One staged chunk of an operand: rows p0 .. p0+31 of a [P, W] bf16 matrix, columns w0 .. w0+TW-1,
+// moved by NT threads in 16-byte pieces.
+template <int TW, int NT> struct ChunkRegs { u4v v[kKC * TW / 8 / NT]; };
 
-__device__ __forceinline__ ChunkRegs load_chunk_bf16(const uint16_t* __restrict__ M, uint32_t P, uint32_t W,
-                                                     uint32_t p0, uint32_t w0, uint32_t tid) {
-    ChunkRegs R;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const uint32_t idx = tid + 256u * i, row = idx >> 4, col = w0 + (idx & 15u) * 8u;
-        R.v[i] = (u4v){0u, 0u, 0u, 0u};
-        if (p0 + row < P && col < W) R.v[i] = *reinterpret_cast<const u4v*>(M + (size_t)(p0 + row) * W + col);
-    }
-    return R;
+// Buffer loads with the sample's [P, W] matrix as the bounded range: rows past P fall outside the range
+// and read as zero in hardware, so there is no branch around a load and the compiler can count the
+// outstanding loads exactly (it waits only for the register set about to be staged).  Columns past W
+// wrap into the next row; they only feed outputs that are never stored.
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+__device__ __forceinline__ rsrc_t sample_rsrc(const uint16_t* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, (int)bytes, 0x00020000);
 }
 
-__device__ __forceinline__ void store_chunk_bf16(uint16_t* tile, const ChunkRegs& R, uint32_t tid) {
+template <int TW, int NT>
+__device__ __forceinline__ void load_chunk(ChunkRegs<TW, NT>& R, rsrc_t rs, uint32_t W, uint32_t p0, uint32_t w0, uint32_t tid) {
+    constexpr int kPer = kKC * TW / 8 / NT, kCols = TW / 8;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const uint32_t idx = tid + 256u * i, row = idx >> 4, col = (idx & 15u) * 8u;
+    for (int i = 0; i < kPer; ++i) {
+        const uint32_t idx = tid + (uint32_t)NT * i, row = idx / kCols, col = w0 + (idx % kCols) * 8u;
+        const uint32_t off = ((p0 + row) * W + col) * 2u;
+        R.v[i] = __builtin_bit_cast(u4v, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0));
+    }
+}
+
+template <int TW, int NT>
+__device__ __forceinline__ void store_chunk(uint16_t* tile, const ChunkRegs<TW, NT>& R, uint32_t tid) {
+    constexpr int kPer = kKC * TW / 8 / NT, kCols = TW / 8, kPitch = Pitch<TW>::value;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+        const uint32_t idx = tid + (uint32_t)NT * i, row = idx / kCols, col = (idx % kCols) * 8u;
         *reinterpret_cast<u4v*>(tile + row * kPitch + col) = R.v[i];
     }
 }
 
-template <bool kWantG>
-__global__ __launch_bounds__(256) void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
-                                                   uint32_t B, uint32_t P, uint32_t J, uint32_t C,
-                                                   uint32_t z_per_split, float cg, float cs,
-                                                   float* __restrict__ g_out, float* __restrict__ s_out,
-                                                   float* __restrict__ ws) {
-    __shared__ __attribute__((aligned(16))) uint16_t shA[2][kKC * kPitch];
-    __shared__ __attribute__((aligned(16))) uint16_t shB[2][kKC * kPitch];
+// BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.
+template <int BM, int BN, bool kWantG>
+__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64)
+void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
+                 uint32_t B, uint32_t P, uint32_t J, uint32_t C,
+                 uint32_t z_per_split, uint32_t splits, float cg, float cs,
+                 float* __restrict__ g_out, float* __restrict__ s_out, float* __restrict__ ws) {
+    constexpr int NT = (BM / 64) * (BN / 64) * 64;
+    constexpr int kPA = Pitch<BM>::value, kPB = Pitch<BN>::value;
+    __shared__ __attribute__((aligned(16))) uint16_t shA[2][kKC * kPA];
+    __shared__ __attribute__((aligned(16))) uint16_t shB[2][kKC * kPB];
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
-    const uint32_t wm = wave >> 1, wn = wave & 1u;
-    const uint32_t j0 = blockIdx.y * kBM, c0 = blockIdx.x * kBN;
-    const uint32_t z_begin = blockIdx.z * z_per_split;
+    const uint32_t wm = wave / (BN / 64), wn = wave % (BN / 64);
+    // Workgroups are dealt to the 8 XCDs round-robin by linear id.  Give every XCD a contiguous range
+    // of (split, row tile, column tile) so that the workgroups sharing a sample range and a row tile
+    // also share an L2.
+    const uint32_t tiles_c = (C + BN - 1) / BN, tiles_j = (J + BM - 1) / BM;
+    const uint32_t nblk = gridDim.x, per = nblk / 8u, rem = nblk % 8u;
+    const uint32_t xcd = blockIdx.x % 8u, slot = blockIdx.x / 8u;
+    const uint32_t logical = xcd * per + min(xcd, rem) + slot;
+    const uint32_t tile_c = logical % tiles_c, tile_j = (logical / tiles_c) % tiles_j, split = logical / (tiles_c * tiles_j);
+    const uint32_t j0 = tile_j * BM, c0 = tile_c * BN;
+    const uint32_t z_begin = split * z_per_split;
     const uint32_t z_end = min(B, z_begin + z_per_split);
     const uint32_t n_chunks = (P + kKC - 1) / kKC;
     const uint32_t total = (z_end - z_begin) * n_chunks;
@@ -92,70 +120,79 @@ __global__ __launch_bounds__(256) void k_conv_bf16(const uint16_t* __restrict__ 
             if (kWantG) g_acc[a][b] = (f16v){0};
         }
 
-    // prologue: first chunk of the first sample
-    {
-        const uint16_t* Uz = U + (size_t)z_begin * P * J;
-        const uint16_t* Dz = D + (size_t)z_begin * P * C;
-        const ChunkRegs ra = load_chunk_bf16(Uz, P, J, 0, j0, tid);
-        const ChunkRegs rb = load_chunk_bf16(Dz, P, C, 0, c0, tid);
-        store_chunk_bf16(shA[0], ra, tid);
-        store_chunk_bf16(shB[0], rb, tid);
-    }
+    ChunkRegs<BM, NT> ra[kDepth];
+    ChunkRegs<BN, NT> rb[kDepth];
+    uint32_t zl = z_begin, pcl = 0, issued = 0;          // cursor of the next chunk to request from global memory
+    auto issue = [&](int slot_) {                       // past the last chunk the range is empty: zeros come back
+        const bool live = issued < total;
+        const uint32_t zz = live ? zl : z_begin;
+        load_chunk<BM, NT>(ra[slot_], sample_rsrc(U + (size_t)zz * P * J, live ? P * J * 2u : 0u), J, pcl * kKC, j0, tid);
+        load_chunk<BN, NT>(rb[slot_], sample_rsrc(D + (size_t)zz * P * C, live ? P * C * 2u : 0u), C, pcl * kKC, c0, tid);
+        if (++pcl == n_chunks) { pcl = 0; ++zl; }
+        ++issued;
+    };
+    // prologue: chunks 0 .. kDepth-1 requested, chunk 0 staged, its registers reused for chunk kDepth
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) issue(d);
+    store_chunk<BM, NT>(shA[0], ra[0], tid);
+    store_chunk<BN, NT>(shB[0], rb[0], tid);
+    issue(0);
     __syncthreads();
 
-    uint32_t z = z_begin, pc = 0;
-    for (uint32_t q = 0; q < total; ++q) {
-        const uint32_t buf = q & 1u;
-        // next chunk: global -> registers while this one is multiplied
-        uint32_t zn = z, pcn = pc + 1;
-        if (pcn == n_chunks) { pcn = 0; ++zn; }
-        const bool have_next = (q + 1 < total);
-        ChunkRegs ra, rb;
-        if (have_next) {
-            ra = load_chunk_bf16(U + (size_t)zn * P * J, P, J, pcn * kKC, j0, tid);
-            rb = load_chunk_bf16(D + (size_t)zn * P * C, P, C, pcn * kKC, c0, tid);
-        }
+    // The loop body is free of branches around memory operations (the trip count is rounded up to a
+    // multiple of kDepth; the surplus chunks are all zeros and add nothing), which keeps the compiler's
+    // count of outstanding loads exact.
+    uint32_t pc = 0, zdone = z_begin;
+    for (uint32_t q0 = 0; q0 < total; q0 += kDepth) {
 #pragma unroll
-        for (int ks = 0; ks < kKC / 16; ++ks) {
-            bf8v a[2], b[2];
+        for (int u = 0; u < kDepth; ++u) {
+            const uint32_t q = q0 + u;
+            const uint32_t buf = q & 1u;
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                a[t] = lds_frag_bf16(shA[buf], ks, wm * 64 + t * 32, lane);
-                b[t] = lds_frag_bf16(shB[buf], ks, wn * 64 + t * 32, lane);
-            }
+            for (int ks = 0; ks < kKC / 16; ++ks) {
+                bf8v a[2], b[2];
 #pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
-        }
-        if (have_next) {
-            store_chunk_bf16(shA[buf ^ 1u], ra, tid);
-            store_chunk_bf16(shB[buf ^ 1u], rb, tid);
-        }
-        if (pc + 1 == n_chunks) {                      // sample finished: G_z is complete in acc
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                for (int nt = 0; nt < 2; ++nt) {
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float x = acc[mt][nt][i];
-                        s_acc[mt][nt][i] += x * x;
-                        if (kWantG) g_acc[mt][nt][i] += x;
-                    }
-                    acc[mt][nt] = (f16v){0};
+                for (int t = 0; t < 2; ++t) {
+                    a[t] = lds_frag_bf16<BM>(shA[buf], ks, wm * 64 + t * 32, lane);
+                    b[t] = lds_frag_bf16<BN>(shB[buf], ks, wn * 64 + t * 32, lane);
                 }
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+            }
+            // chunk q+1 sits in register set (u+1) % kDepth: stage it, then reuse the set for chunk q+1+kDepth
+            constexpr int kNextSet[3] = {1, 2, 0};
+            const int ns = kNextSet[u];
+            store_chunk<BM, NT>(shA[buf ^ 1u], ra[ns], tid);
+            store_chunk<BN, NT>(shB[buf ^ 1u], rb[ns], tid);
+            issue(ns);
+            if (++pc == n_chunks && zdone < z_end) {   // sample finished: G_z is complete in acc
+                pc = 0;
+                ++zdone;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float x = acc[mt][nt][i];
+                            s_acc[mt][nt][i] += x * x;
+                            if (kWantG) g_acc[mt][nt][i] += x;
+                        }
+                        acc[mt][nt] = (f16v){0};
+                    }
+            }
+            __syncthreads();
         }
-        __syncthreads();
-        z = zn; pc = pcn;
     }
 
     // ---- epilogue: scaled result, or unscaled partial sums for the fixed-order reduction ----
-    const bool direct = (gridDim.z == 1);
+    const bool direct = (splits == 1);
     const size_t JC = (size_t)J * C;
-    float* so = direct ? s_out : ws + (size_t)blockIdx.z * 2 * JC;
-    float* go = direct ? g_out : ws + (size_t)blockIdx.z * 2 * JC + JC;
+    float* so = direct ? s_out : ws + (size_t)split * 2 * JC;
+    float* go = direct ? g_out : ws + (size_t)split * 2 * JC + JC;
     const float fs = direct ? cs : 1.0f, fg = direct ? cg : 1.0f;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -189,42 +226,64 @@ __global__ __launch_bounds__(256) void k_sqgrad_reduce(const float* __restrict__
     if (g_out) g_out[i] = cg * g;
 }
 
-size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
-    (void)P;
-    if (kind != VGC_CONV || dtype != VGC_BF16) return 0;
-    const uint32_t splits = conv_splits(B, J, C);
-    return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
+// Block tile for a shape: wide in J (256) when J has room, 64 / 128 in C following C.
+struct ConvTile { int bm, bn; };
+static ConvTile conv_tile(uint32_t J, uint32_t C) {
+    ConvTile t;
+    t.bn = (C <= 64) ? 64 : 128;
+    t.bm = (J >= 256) ? 256 : 128;
+    return t;
 }
 
 uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C) {
-    const uint64_t tiles = (uint64_t)((J + kBM - 1) / kBM) * ((C + kBN - 1) / kBN);
-    uint64_t want = (1024 + tiles - 1) / tiles;          // aim for about four workgroups per compute unit
+    const ConvTile t = conv_tile(J, C);
+    const uint64_t tiles = (uint64_t)((J + t.bm - 1) / t.bm) * ((C + t.bn - 1) / t.bn);
+    uint64_t want = (512 + tiles - 1) / tiles;           // aim for about two workgroups per compute unit
     if (want > B) want = B;
     if (want < 1) want = 1;
     return (uint32_t)want;
+}
+
+size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
+    (void)P;
+    if (kind != VGC_CONV || !conv_tiled_supported(dtype, J, C)) return 0;
+    const uint32_t splits = conv_splits(B, J, C);
+    return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
 }
 
 bool conv_tiled_supported(int dtype, uint32_t J, uint32_t C) {
     return dtype == VGC_BF16 && (J % 8 == 0) && (C % 8 == 0);
 }
 
+template <int BM, int BN>
+static void launch_conv_bf16(uint32_t nblk, hipStream_t stream, const void* X, const void* D, uint32_t B, uint32_t P,
+                             uint32_t J, uint32_t C, uint32_t zper, uint32_t splits, float cg, float cs,
+                             float* g_out, float* s_out, float* ws) {
+    constexpr int NT = (BM / 64) * (BN / 64) * 64;
+    if (g_out)
+        hipLaunchKernelGGL((k_conv_bf16<BM, BN, true>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
+                           (const uint16_t*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+    else
+        hipLaunchKernelGGL((k_conv_bf16<BM, BN, false>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
+                           (const uint16_t*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+}
+
 int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
                       float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
     (void)dtype;
+    const ConvTile t = conv_tile(J, C);
     uint32_t splits = conv_splits(B, J, C);
     if (splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * J * C * sizeof(float))) splits = 1;
     const uint32_t zper = (B + splits - 1) / splits;
     splits = (B + zper - 1) / zper;
-    dim3 grid((C + kBN - 1) / kBN, (J + kBM - 1) / kBM, splits);
-    if (grid.y > 65535u || grid.z > 65535u) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
+    const uint64_t nblk = (uint64_t)((C + t.bn - 1) / t.bn) * ((J + t.bm - 1) / t.bm) * splits;
+    if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
-    if (g_out)
-        hipLaunchKernelGGL(k_conv_bf16<true>, grid, dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, P, J, C,
-                           zper, cg, cs, g_out, s_out, ws);
-    else
-        hipLaunchKernelGGL(k_conv_bf16<false>, grid, dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, P, J, C,
-                           zper, cg, cs, g_out, s_out, ws);
+    if (t.bm == 256 && t.bn == 128) launch_conv_bf16<256, 128>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+    else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+    else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+    else launch_conv_bf16<128, 64>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
     if (splits > 1) {
         const size_t JC = (size_t)J * C;
         hipLaunchKernelGGL(k_sqgrad_reduce, dim3((uint32_t)((JC + 255) / 256)), dim3(256), 0, stream, ws, splits, JC, cg, cs,
