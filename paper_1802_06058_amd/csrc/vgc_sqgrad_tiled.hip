@@ -26,8 +26,14 @@ typedef float f16v __attribute__((ext_vector_type(16)));
 typedef uint32_t u4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s4v* lds_s4v_ptr;
 
-constexpr int kKC = 32;                  // positions per LDS stage
-constexpr int kDepth = 3;                // chunks in flight from global memory per thread
+#ifndef VGC_CONV_KC
+#define VGC_CONV_KC 32
+#endif
+#ifndef VGC_CONV_DEPTH
+#define VGC_CONV_DEPTH 3
+#endif
+constexpr int kKC = VGC_CONV_KC;         // positions per LDS stage
+constexpr int kDepthS = VGC_CONV_DEPTH;  // chunks in flight from global memory per thread (s alone; 2 when g is wanted too)
 
 // Row pitch (bf16 elements) of a staged tile of width W: W + 32, i.e. consecutive rows start 16 banks
 // apart, so the 4 rows x 2 column halves one half-wave reads with a transposing load fall on distinct banks.
@@ -84,7 +90,7 @@ __device__ __forceinline__ void store_chunk(uint16_t* tile, const ChunkRegs<TW, 
 
 // BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.
 template <int BM, int BN, bool kWantG>
-__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64)
+__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
 void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                  uint32_t B, uint32_t P, uint32_t J, uint32_t C,
                  uint32_t z_per_split, uint32_t splits, float cg, float cs,
@@ -120,6 +126,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             if (kWantG) g_acc[a][b] = (f16v){0};
         }
 
+    constexpr int kDepth = kWantG ? 2 : kDepthS;      // chunks in flight from global memory per thread
     ChunkRegs<BM, NT> ra[kDepth];
     ChunkRegs<BN, NT> rb[kDepth];
     uint32_t zl = z_begin, pcl = 0, issued = 0;          // cursor of the next chunk to request from global memory
@@ -148,23 +155,31 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         for (int u = 0; u < kDepth; ++u) {
             const uint32_t q = q0 + u;
             const uint32_t buf = q & 1u;
+            // operand fragments of k-step ks+1 are fetched from LDS while the MFMAs of step ks run
+            bf8v fa[2][2], fb[2][2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                fa[0][t] = lds_frag_bf16<BM>(shA[buf], 0, wm * 64 + t * 32, lane);
+                fb[0][t] = lds_frag_bf16<BN>(shB[buf], 0, wn * 64 + t * 32, lane);
+            }
 #pragma unroll
             for (int ks = 0; ks < kKC / 16; ++ks) {
-                bf8v a[2], b[2];
+                const int cur = ks & 1, nxt = cur ^ 1;
+                if (ks + 1 < kKC / 16) {        // (with g the register budget is tighter; the compiler may serialise these)
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    a[t] = lds_frag_bf16<BM>(shA[buf], ks, wm * 64 + t * 32, lane);
-                    b[t] = lds_frag_bf16<BN>(shB[buf], ks, wn * 64 + t * 32, lane);
+                    for (int t = 0; t < 2; ++t) {
+                        fa[nxt][t] = lds_frag_bf16<BM>(shA[buf], ks + 1, wm * 64 + t * 32, lane);
+                        fb[nxt][t] = lds_frag_bf16<BN>(shB[buf], ks + 1, wn * 64 + t * 32, lane);
+                    }
                 }
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
                     for (int nt = 0; nt < 2; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mt], fb[cur][nt], acc[mt][nt], 0, 0, 0);
             }
             // chunk q+1 sits in register set (u+1) % kDepth: stage it, then reuse the set for chunk q+1+kDepth
-            constexpr int kNextSet[3] = {1, 2, 0};
-            const int ns = kNextSet[u];
+            const int ns = (u + 1) % kDepth;
             store_chunk<BM, NT>(shA[buf ^ 1u], ra[ns], tid);
             store_chunk<BN, NT>(shB[buf ^ 1u], rb[ns], tid);
             issue(ns);
@@ -231,17 +246,36 @@ struct ConvTile { int bm, bn; };
 static ConvTile conv_tile(uint32_t J, uint32_t C) {
     ConvTile t;
     t.bn = (C <= 64) ? 64 : 128;
-    t.bm = (J >= 256) ? 256 : 128;
+    // 256 rows unless 128 wastes clearly less of the last tile
+    const uint32_t pad256 = (J + 255) / 256 * 256, pad128 = (J + 127) / 128 * 128;
+    t.bm = (J >= 256 && pad256 * 10 <= pad128 * 11) ? 256 : 128;
     return t;
 }
 
+// How many ways to split the samples.  Workgroups run in rounds of `slots` (compute units x resident
+// workgroups); the cost of a choice is rounds x samples per workgroup, plus one pass over the partial
+// sums per split for the reduction (weighted as a fraction of one sample's work on a tile).
 uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C) {
     const ConvTile t = conv_tile(J, C);
     const uint64_t tiles = (uint64_t)((J + t.bm - 1) / t.bm) * ((C + t.bn - 1) / t.bn);
-    uint64_t want = (512 + tiles - 1) / tiles;           // aim for about two workgroups per compute unit
-    if (want > B) want = B;
-    if (want < 1) want = 1;
-    return (uint32_t)want;
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) n_cu = v;
+        else n_cu = 256;
+    }
+    const uint64_t waves_per_wg = (uint64_t)(t.bm / 64) * (t.bn / 64);
+    const uint64_t slots = (uint64_t)n_cu * (8 / waves_per_wg);
+    double best = 1e300;
+    uint32_t best_s = 1;
+    for (uint32_t s = 1; s <= B; ++s) {
+        const uint32_t zper = (B + s - 1) / s, s2 = (B + zper - 1) / zper;
+        if (s2 != s) continue;
+        const uint64_t rounds = (tiles * s2 + slots - 1) / slots;
+        const double cost = (double)rounds * zper + (s2 > 1 ? 0.5 * s2 * (double)tiles / slots + 0.5 : 0.0);
+        if (cost < best - 1e-9) { best = cost; best_s = s2; }
+    }
+    return best_s;
 }
 
 size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
