@@ -120,9 +120,18 @@ int launch_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B,
 int launch_sqgrad_simple(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
                          uint32_t J, uint32_t C, float c, float* g_out, float* s_out, hipStream_t stream);
 
-// LDS-tiled kernels (vgc_sqgrad_tiled.hip)
+// LDS-tiled kernels (vgc_sqgrad_tiled.hip, vgc_sqgrad_fc.hip)
 uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C);
-bool conv_tiled_supported(int dtype, uint32_t J, uint32_t C);
+bool conv_tiled_supported(int dtype, uint32_t P, uint32_t J, uint32_t C);
+void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg, float cs, float* g_out, float* s_out,
+                          hipStream_t stream);
+bool fc_tiled_supported(int dtype, uint32_t B, uint32_t J, uint32_t C);
+bool conv_f32_tiled_supported(uint32_t P, uint32_t J, uint32_t C);
+uint32_t conv_f32_splits(uint32_t B, uint32_t J, uint32_t C);
+int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t J, uint32_t C, float c,
+                    float* g_out, float* s_out, hipStream_t stream);
+int launch_conv_f32_tiled(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+                          float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream);
 size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C);
 int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
                       float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream);

@@ -81,8 +81,13 @@ __global__ __launch_bounds__(256) void k_sqgrad_simple(const T* __restrict__ X, 
 int launch_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
                   uint32_t J, uint32_t C, float c, float* g_out, float* s_out,
                   void* workspace, size_t workspace_bytes, hipStream_t stream) {
-    if (kind == VGC_CONV && conv_tiled_supported(dtype, J, C))
+    if (kind == VGC_CONV && conv_tiled_supported(dtype, P, J, C))
         return launch_conv_tiled(dtype, X, D, B, P, J, C, c, g_out, s_out, workspace, workspace_bytes, stream);
+    if (kind == VGC_CONV && dtype == VGC_F32 && conv_f32_tiled_supported(P, J, C))
+        return launch_conv_f32_tiled(X, D, B, P, J, C, c, g_out, s_out, workspace, workspace_bytes, stream);
+    if (kind == VGC_FC && fc_tiled_supported(dtype, B, J, C))
+        return launch_fc_tiled(dtype, X, D, B, J, C, c, g_out, s_out, stream);
+    // shapes the tiled kernels do not take (row lengths that are not a multiple of 16 bytes)
     return launch_sqgrad_simple(kind, dtype, X, D, B, P, J, C, c, g_out, s_out, stream);
 }
 

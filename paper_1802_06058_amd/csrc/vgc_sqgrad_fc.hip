@@ -1,0 +1,339 @@
+// LDS-tiled MFMA kernels for the per-parameter sums of Alg. 1 (g = c sum_z G_z, s = c^2 sum_z G_z.G_z):
+//
+//   k_fc_bf16     FC form, bf16 inputs.  G_z is the outer product x_z d_z^T, so s = c^2 (X.X)^T (D.D) and
+//                 g = c X^T D are two contractions over K = B (Section 5's 2 N |B| multiply-adds each).
+//                 The squares are taken in float32 and rounded to bf16 (2^-9 relative per factor, well
+//                 inside the 1e-2 budget for bf16 inputs); v_mfma_f32_32x32x16_bf16, float32 accumulate.
+//                 With K this small the kernel is bound by writing [J, C] floats, not by the matrix cores.
+//   k_tiled_f32   float32 inputs, both forms, v_mfma_f32_32x32x2_f32 (float32 products and sums, which is
+//                 what the 1e-5 tolerance on s needs).  FC: two MFMA chains on (x, d) and (x^2, d^2).
+//                 Conv: per-sample product in the accumulators, squared into s when the sample ends.
+//
+// Block tile 128 x 128 of [J, C], 4 waves (2 x 2), operands staged through LDS k-major (rows of the
+// source matrices as they are in memory).  Rows past the end of a sample's matrix are outside the
+// bounded range of the buffer loads and read as zero.
+#include "vgc_internal.h"
+
+namespace vgc {
+
+typedef short s4v __attribute__((ext_vector_type(4)));
+typedef short s8v __attribute__((ext_vector_type(8)));
+typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s4v* lds_s4v_ptr;
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+constexpr int kT = 128;                  // block tile edge
+constexpr int kPitch16 = kT + 32;        // bf16 row pitch (elements): rows start 16 banks apart
+constexpr int kPitch32 = kT + 32;        // float row pitch (elements): rows start 32 banks apart
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+
+// ds_read_b64_tr_b16 operand fetch: see vgc_sqgrad_tiled.hip for the lane mapping.
+__device__ __forceinline__ bf8v frag16(const uint16_t* tile, int ks, int mbase, uint32_t lane) {
+    const uint32_t r = lane & 15u, grp = lane >> 4;
+    const uint16_t* p = tile + (ks * 16 + (grp >> 1) * 8 + (r >> 2)) * kPitch16 + mbase + (grp & 1u) * 16 + 4 * (r & 3u);
+    const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p));
+    const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p + 4 * kPitch16));
+    s8v v;
+    v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
+    v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+    return __builtin_bit_cast(bf8v, v);
+}
+
+// Square of two packed bf16 values: float32 product, rounded to nearest-even bf16.
+__device__ __forceinline__ uint32_t square_bf16x2(uint32_t w) {
+    const float lo = __uint_as_float(w << 16), hi = __uint_as_float(w & 0xFFFF0000u);
+    const uint32_t a = __float_as_uint(lo * lo), b = __float_as_uint(hi * hi);
+    const uint32_t ra = (a + 0x7FFFu + ((a >> 16) & 1u)) >> 16;
+    const uint32_t rb = (b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u;
+    return ra | rb;
+}
+
+__device__ __forceinline__ void store_tile(float fs, float fg, const f16v (&s_acc)[2][2], const f16v (&g_acc)[2][2],
+                                           bool want_g, float* __restrict__ so, float* __restrict__ go,
+                                           uint32_t j0, uint32_t c0, uint32_t J, uint32_t C, uint32_t wm, uint32_t wn,
+                                           uint32_t lane) {
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) {
+            const uint32_t col = c0 + wn * 64 + nt * 32 + (lane & 31u);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t row = j0 + wm * 64 + mt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                if (row < J && col < C) {
+                    const size_t o = (size_t)row * C + col;
+                    __builtin_nontemporal_store(fs * s_acc[mt][nt][i], so + o);
+                    if (want_g) __builtin_nontemporal_store(fg * g_acc[mt][nt][i], go + o);
+                }
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------------------
+// FC, bf16
+// ------------------------------------------------------------------------------------------------
+template <bool kWantG>
+__global__ __launch_bounds__(256, 2) void k_fc_bf16(const uint16_t* __restrict__ X, const uint16_t* __restrict__ D,
+                                                    uint32_t B, uint32_t J, uint32_t C, float cg, float cs,
+                                                    float* __restrict__ g_out, float* __restrict__ s_out) {
+    constexpr int kRows = 32;
+    __shared__ __attribute__((aligned(16))) uint16_t shX[kRows * kPitch16], shD[kRows * kPitch16];
+    __shared__ __attribute__((aligned(16))) uint16_t shX2[kRows * kPitch16], shD2[kRows * kPitch16];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, wm = wave >> 1, wn = wave & 1u;
+    const uint32_t tiles_c = (C + kT - 1) / kT;
+    const uint32_t j0 = (blockIdx.x / tiles_c) * kT, c0 = (blockIdx.x % tiles_c) * kT;
+    const rsrc_t rx = make_rsrc(X, B * J * 2u), rd = make_rsrc(D, B * C * 2u);
+
+    f16v s_acc[2][2], g_acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) { s_acc[a][b] = (f16v){0}; g_acc[a][b] = (f16v){0}; }
+
+    for (uint32_t z0 = 0; z0 < B; z0 += kRows) {
+        u4v vx[2], vd[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t idx = tid + 256u * i, row = idx >> 4, col = (idx & 15u) * 8u;
+            vx[i] = __builtin_bit_cast(u4v, __builtin_amdgcn_raw_buffer_load_b128(rx, (int)(((z0 + row) * J + j0 + col) * 2u), 0, 0));
+            vd[i] = __builtin_bit_cast(u4v, __builtin_amdgcn_raw_buffer_load_b128(rd, (int)(((z0 + row) * C + c0 + col) * 2u), 0, 0));
+        }
+        if (z0) __syncthreads();                        // the previous chunk has been consumed
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t idx = tid + 256u * i, off = (idx >> 4) * kPitch16 + (idx & 15u) * 8u;
+            // columns past the matrix edge wrapped into the next row: they feed outputs that are not stored
+            if (kWantG) {
+                *reinterpret_cast<u4v*>(shX + off) = vx[i];
+                *reinterpret_cast<u4v*>(shD + off) = vd[i];
+            }
+            u4v x2, d2;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { x2[e] = square_bf16x2(vx[i][e]); d2[e] = square_bf16x2(vd[i][e]); }
+            *reinterpret_cast<u4v*>(shX2 + off) = x2;
+            *reinterpret_cast<u4v*>(shD2 + off) = d2;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < kRows / 16; ++ks) {
+            bf8v a2[2], b2[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) { a2[t] = frag16(shX2, ks, wm * 64 + t * 32, lane); b2[t] = frag16(shD2, ks, wn * 64 + t * 32, lane); }
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt)
+                    s_acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a2[mt], b2[nt], s_acc[mt][nt], 0, 0, 0);
+            if (kWantG) {
+                bf8v a[2], b[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) { a[t] = frag16(shX, ks, wm * 64 + t * 32, lane); b[t] = frag16(shD, ks, wn * 64 + t * 32, lane); }
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+                        g_acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mt], b[nt], g_acc[mt][nt], 0, 0, 0);
+            }
+        }
+    }
+    store_tile(cs, cg, s_acc, g_acc, kWantG, s_out, g_out, j0, c0, J, C, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// float32, FC and conv
+// ------------------------------------------------------------------------------------------------
+constexpr int kR32 = 16;                 // rows per LDS stage
+
+struct Chunk32 { f4v a[2], b[2]; };
+
+__device__ __forceinline__ void load32(Chunk32& R, rsrc_t ra, rsrc_t rb, uint32_t J, uint32_t C, uint32_t p0,
+                                       uint32_t j0, uint32_t c0, uint32_t tid) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t idx = tid + 256u * i, row = idx >> 5, col = (idx & 31u) * 4u;
+        R.a[i] = __builtin_bit_cast(f4v, __builtin_amdgcn_raw_buffer_load_b128(ra, (int)(((p0 + row) * J + j0 + col) * 4u), 0, 0));
+        R.b[i] = __builtin_bit_cast(f4v, __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(((p0 + row) * C + c0 + col) * 4u), 0, 0));
+    }
+}
+
+__device__ __forceinline__ void stage32(float* A, float* Bm, const Chunk32& R, uint32_t tid) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const uint32_t idx = tid + 256u * i, off = (idx >> 5) * kPitch32 + (idx & 31u) * 4u;
+        *reinterpret_cast<f4v*>(A + off) = R.a[i];
+        *reinterpret_cast<f4v*>(Bm + off) = R.b[i];
+    }
+}
+
+// kConv: X is [B, P, J], D is [B, P, C], samples z_begin .. z_end-1 of this workgroup's split.
+// !kConv: X is [B, J], D is [B, C]; treated as one "sample" with P = B rows and no per-sample square
+//         (the two chains run on the values and on their squares instead).
+template <bool kConv, bool kWantG>
+__global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
+                                                      uint32_t B, uint32_t P, uint32_t J, uint32_t C,
+                                                      uint32_t z_per_split, uint32_t splits, float cg, float cs,
+                                                      float* __restrict__ g_out, float* __restrict__ s_out,
+                                                      float* __restrict__ ws) {
+    __shared__ __attribute__((aligned(16))) float shA[2][kR32 * kPitch32];
+    __shared__ __attribute__((aligned(16))) float shB[2][kR32 * kPitch32];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, wm = wave >> 1, wn = wave & 1u;
+    const uint32_t tiles_c = (C + kT - 1) / kT, tiles_j = (J + kT - 1) / kT;
+    const uint32_t nblk = gridDim.x, per = nblk / 8u, rem = nblk % 8u;
+    const uint32_t xcd = blockIdx.x % 8u, slot = blockIdx.x / 8u;
+    const uint32_t logical = xcd * per + min(xcd, rem) + slot;       // contiguous range of tiles per XCD
+    const uint32_t tile_c = logical % tiles_c, tile_j = (logical / tiles_c) % tiles_j, split = logical / (tiles_c * tiles_j);
+    const uint32_t j0 = tile_j * kT, c0 = tile_c * kT;
+    const uint32_t rowsP = kConv ? P : B;                            // K extent of one "sample"
+    const uint32_t z_begin = kConv ? split * z_per_split : 0u;
+    const uint32_t z_end = kConv ? min(B, z_begin + z_per_split) : 1u;
+    const uint32_t n_chunks = (rowsP + kR32 - 1) / kR32;
+    const uint32_t total = (z_end - z_begin) * n_chunks;
+
+    f16v acc[2][2], s_acc[2][2], g_acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) { acc[a][b] = (f16v){0}; s_acc[a][b] = (f16v){0}; g_acc[a][b] = (f16v){0}; }
+
+    Chunk32 R[2];
+    uint32_t zl = z_begin, pcl = 0, issued = 0;
+    auto issue = [&](int slot_) {
+        const bool live = issued < total;
+        const uint32_t zz = live ? zl : z_begin;
+        const rsrc_t ra = make_rsrc(X + (size_t)zz * rowsP * J, live ? rowsP * J * 4u : 0u);
+        const rsrc_t rb = make_rsrc(D + (size_t)zz * rowsP * C, live ? rowsP * C * 4u : 0u);
+        load32(R[slot_], ra, rb, J, C, pcl * kR32, j0, c0, tid);
+        if (++pcl == n_chunks) { pcl = 0; ++zl; }
+        ++issued;
+    };
+    issue(0);
+    issue(1);
+    stage32(shA[0], shB[0], R[0], tid);
+    issue(0);
+    __syncthreads();
+
+    const uint32_t col = lane & 31u, kh = lane >> 5;
+    uint32_t pc = 0, zdone = z_begin;
+    for (uint32_t q0 = 0; q0 < total; q0 += 2) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t buf = (uint32_t)u;                       // q = q0 + u, and q0 is even
+            const float* A = shA[buf];
+            const float* Bm = shB[buf];
+#pragma unroll
+            for (int ks = 0; ks < kR32 / 2; ++ks) {
+                float a[2], b[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    a[t] = A[(ks * 2 + kh) * kPitch32 + wm * 64 + t * 32 + col];
+                    b[t] = Bm[(ks * 2 + kh) * kPitch32 + wn * 64 + t * 32 + col];
+                }
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+                        if (kConv) {
+                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt], b[nt], acc[mt][nt], 0, 0, 0);
+                        } else {
+                            s_acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt] * a[mt], b[nt] * b[nt], s_acc[mt][nt], 0, 0, 0);
+                            if (kWantG) g_acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[mt], b[nt], g_acc[mt][nt], 0, 0, 0);
+                        }
+                    }
+            }
+            const int ns = u ^ 1;
+            stage32(shA[buf ^ 1u], shB[buf ^ 1u], R[ns], tid);
+            issue(ns);
+            if (kConv && ++pc == n_chunks && zdone < z_end) {     // sample finished: G_z is complete in acc
+                pc = 0;
+                ++zdone;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            const float x = acc[mt][nt][i];
+                            s_acc[mt][nt][i] += x * x;
+                            if (kWantG) g_acc[mt][nt][i] += x;
+                        }
+                        acc[mt][nt] = (f16v){0};
+                    }
+            }
+            __syncthreads();
+        }
+    }
+
+    const bool direct = (splits == 1);
+    const size_t JC = (size_t)J * C;
+    float* so = direct ? s_out : ws + (size_t)split * 2 * JC;
+    float* go = direct ? g_out : ws + (size_t)split * 2 * JC + JC;
+    store_tile(direct ? cs : 1.0f, direct ? cg : 1.0f, s_acc, g_acc, kWantG, so, go, j0, c0, J, C, wm, wn, lane);
+}
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+bool fc_tiled_supported(int dtype, uint32_t B, uint32_t J, uint32_t C) {
+    const uint64_t limit = 0x7FFFFFFFull;                            // buffer ranges and offsets are 32-bit
+    if (dtype == VGC_BF16) return J % 8 == 0 && C % 8 == 0 && (uint64_t)(B + 32) * J * 2 < limit && (uint64_t)(B + 32) * C * 2 < limit;
+    return J % 4 == 0 && C % 4 == 0 && (uint64_t)(B + 16) * J * 4 < limit && (uint64_t)(B + 16) * C * 4 < limit;
+}
+
+bool conv_f32_tiled_supported(uint32_t P, uint32_t J, uint32_t C) {
+    const uint64_t limit = 0x7FFFFFFFull;
+    return J % 4 == 0 && C % 4 == 0 && (uint64_t)(P + 16) * J * 4 < limit && (uint64_t)(P + 16) * C * 4 < limit;
+}
+
+uint32_t conv_f32_splits(uint32_t B, uint32_t J, uint32_t C) {
+    const uint64_t tiles = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT);
+    const uint64_t slots = 512;                                      // 256 compute units x 2 resident workgroups
+    double best = 1e300;
+    uint32_t best_s = 1;
+    for (uint32_t s = 1; s <= B; ++s) {
+        const uint32_t zper = (B + s - 1) / s, s2 = (B + zper - 1) / zper;
+        if (s2 != s) continue;
+        const uint64_t rounds = (tiles * s2 + slots - 1) / slots;
+        const double cost = (double)rounds * zper + (s2 > 1 ? 0.5 * s2 * (double)tiles / slots + 0.5 : 0.0);
+        if (cost < best - 1e-9) { best = cost; best_s = s2; }
+    }
+    return best_s;
+}
+
+int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t J, uint32_t C, float c,
+                    float* g_out, float* s_out, hipStream_t stream) {
+    const uint64_t nblk = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT);
+    if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
+    const float cg = c, cs = c * c;
+    if (dtype == VGC_BF16) {
+        if (g_out) hipLaunchKernelGGL(k_fc_bf16<true>, dim3((uint32_t)nblk), dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, J, C, cg, cs, g_out, s_out);
+        else hipLaunchKernelGGL(k_fc_bf16<false>, dim3((uint32_t)nblk), dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, J, C, cg, cs, g_out, s_out);
+    } else {
+        if (g_out) hipLaunchKernelGGL((k_tiled_f32<false, true>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, cg, cs, g_out, s_out, (float*)nullptr);
+        else hipLaunchKernelGGL((k_tiled_f32<false, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, cg, cs, g_out, s_out, (float*)nullptr);
+    }
+    return hip_check(hipGetLastError(), "launch fc tiled");
+}
+
+int launch_conv_f32_tiled(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+                          float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    uint32_t splits = conv_f32_splits(B, J, C);
+    if (splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * J * C * sizeof(float))) splits = 1;
+    const uint32_t zper = (B + splits - 1) / splits;
+    splits = (B + zper - 1) / zper;
+    const uint64_t nblk = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT) * splits;
+    if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
+    const float cg = c, cs = c * c;
+    float* ws = static_cast<float*>(workspace);
+    if (g_out) hipLaunchKernelGGL((k_tiled_f32<true, true>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+    else hipLaunchKernelGGL((k_tiled_f32<true, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+    if (splits > 1) launch_sqgrad_reduce(ws, splits, (size_t)J * C, cg, cs, g_out, s_out, stream);
+    return hip_check(hipGetLastError(), "launch k_tiled_f32");
+}
+
+}  // namespace vgc

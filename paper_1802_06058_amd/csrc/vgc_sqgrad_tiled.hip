@@ -279,14 +279,23 @@ uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C) {
 }
 
 size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
-    (void)P;
-    if (kind != VGC_CONV || !conv_tiled_supported(dtype, J, C)) return 0;
-    const uint32_t splits = conv_splits(B, J, C);
+    if (kind != VGC_CONV) return 0;
+    uint32_t splits = 1;
+    if (conv_tiled_supported(dtype, P, J, C)) splits = conv_splits(B, J, C);
+    else if (dtype == VGC_F32 && conv_f32_tiled_supported(P, J, C)) splits = conv_f32_splits(B, J, C);
     return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
 }
 
-bool conv_tiled_supported(int dtype, uint32_t J, uint32_t C) {
-    return dtype == VGC_BF16 && (J % 8 == 0) && (C % 8 == 0);
+bool conv_tiled_supported(int dtype, uint32_t P, uint32_t J, uint32_t C) {
+    const uint64_t limit = 0x7FFFFFFFull;               // buffer ranges and offsets are 32-bit
+    return dtype == VGC_BF16 && (J % 8 == 0) && (C % 8 == 0) && (uint64_t)(P + 64) * J * 2 < limit &&
+           (uint64_t)(P + 64) * C * 2 < limit;
+}
+
+void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg, float cs, float* g_out, float* s_out,
+                          hipStream_t stream) {
+    hipLaunchKernelGGL(k_sqgrad_reduce, dim3((uint32_t)((JC + 255) / 256)), dim3(256), 0, stream, ws, splits, JC, cg, cs,
+                       g_out, s_out);
 }
 
 template <int BM, int BN>
@@ -318,11 +327,7 @@ int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint3
     else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
     else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
     else launch_conv_bf16<128, 64>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
-    if (splits > 1) {
-        const size_t JC = (size_t)J * C;
-        hipLaunchKernelGGL(k_sqgrad_reduce, dim3((uint32_t)((JC + 255) / 256)), dim3(256), 0, stream, ws, splits, JC, cg, cs,
-                           g_out, s_out);
-    }
+    if (splits > 1) launch_sqgrad_reduce(ws, splits, (size_t)J * C, cg, cs, g_out, s_out, stream);
     return hip_check(hipGetLastError(), "launch k_conv_bf16");
 }
 
