@@ -1,0 +1,170 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times (same plan, same tile size, same entry points).  Where the oracle cannot process the whole
+output in seconds, whole groups / sampled outputs are recomputed by it and the rest is covered by
+properties that hold at any size."""
+import numpy as np
+import pytest
+
+from oracle import vgc_oracle as O
+from paper_1802_06058_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+F32 = np.float32
+U32 = np.uint32
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+    from paper_1802_06058_amd import vgc
+    assert torch.cuda.is_available()
+    vgc.load()
+    return torch.device("cuda:0")
+
+
+def _bits(a):
+    return np.ascontiguousarray(a).view(U32)
+
+
+def test_flat_1e9_stream_select_pack_decode(dev):
+    """Config 5 at full size (1e9 parameters, 60 groups of 2^24, Student-t(3), batch 16): one worker,
+    two steps.  Three groups (first, one in the middle, the partial last one) are recomputed whole by
+    the oracle from the same inputs and compared bit for bit; the rest through size-independent
+    properties of headers, words and state."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    cfg = W.CONFIGS["C5"]
+    N = cfg["n"]
+    groups = W.flat_groups(N, cfg["group"])
+    plan = vgc.Plan(groups, dev)
+    r = torch.zeros(N, dtype=torch.float32, device=dev)
+    v = torch.zeros(N, dtype=torch.float32, device=dev)
+    scratch = plan.new_scratch()
+    words = torch.empty(N // 2, dtype=torch.int32, device=dev)
+    hdrs, status = plan.new_headers(), plan.new_status()
+    dense = torch.empty(N, dtype=torch.float32, device=dev)
+    check = [0, 31, len(groups) - 1]
+    r_ref = {k: np.zeros(groups[k][1], F32) for k in check}
+    v_ref = {k: np.zeros(groups[k][1], F32) for k in check}
+    for step in range(2):
+        g, s = W.device_student_stream(N, cfg["batch"], cfg["nu"], cfg["seed"] + 17 * step, dev)
+        vgc.accumulate_select(g, s, r, v, plan, cfg["alpha"], cfg["zeta"], scratch)
+        vgc.pack(plan, scratch, words, hdrs, status)
+        torch.cuda.synchronize()
+        total, overflow = vgc.read_status(status)
+        H = vgc.read_headers(hdrs)
+        assert overflow == 0 and 0.1 * N < total < 0.45 * N
+        # properties over all groups: offsets chain, counts add up, exponent fields plausible
+        pos = 0
+        for (off, size), (ef, cnt, woff) in zip(groups, H):
+            assert woff == pos and cnt <= size and (cnt == 0) == (ef == 0)
+            pos += cnt
+        assert pos == total
+        vgc.unpack_add_batch([words], [total], [hdrs], plan, 0.125, dense, overwrite=True)
+        torch.cuda.synchronize()
+        for k in check:
+            off, size = groups[k]
+            gk, sk = g[off:off + size].cpu().numpy(), s[off:off + size].cpu().numpy()
+            r_acc, r_out, v_out, send = O.accumulate_select(gk, sk, r_ref[k], v_ref[k], cfg["alpha"], cfg["zeta"])
+            w_ref, h_ref, _ = O.pack(r_acc, send, [(0, size)], check=False)
+            ef, cnt, woff = H[k]
+            assert (ef, cnt) == h_ref[0][:2]
+            assert np.array_equal(words[woff:woff + cnt].cpu().numpy().view(U32), w_ref)
+            assert np.array_equal(_bits(r[off:off + size].cpu().numpy()), _bits(r_out))
+            assert np.array_equal(_bits(v[off:off + size].cpu().numpy()), _bits(v_out))
+            d_ref = np.zeros(size, F32)
+            O.unpack_add(w_ref, h_ref, [(0, size)], 0.125, d_ref)
+            assert np.array_equal(_bits(dense[off:off + size].cpu().numpy()), _bits(d_ref))
+            r_ref[k], v_ref[k] = r_out, v_out
+        # whole-array properties of the state: sent elements are exactly the zeros of (r, v) that decoded or dropped
+        nz = int(torch.count_nonzero(dense))
+        assert nz == total
+        del g, s
+
+
+@pytest.mark.parametrize("name,alpha,steps", [("C3", 1.0, 2), ("C4", 2.0, 1)])
+def test_model_parameter_sets_full_oracle(dev, name, alpha, steps):
+    """ResNet-50-shaped (161 groups, 25.6 M) and VGG-16-shaped (32 groups, 138 M) parameter sets with
+    per-layer gradient scales: every output compared with the oracle (two steps with state carry for the
+    smaller set)."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    cfg = W.CONFIGS[name]
+    layers = cfg["layers"]
+    groups = W.groups_from_sizes([L["size"] for L in layers])
+    plan = vgc.Plan(groups, dev)
+    n = plan.n
+    sig = W.layer_sigmas(cfg["seed"], len(layers))
+    r = torch.zeros(n, dtype=torch.float32, device=dev)
+    v = torch.zeros(n, dtype=torch.float32, device=dev)
+    scratch = plan.new_scratch()
+    words = torch.empty(n, dtype=torch.int32, device=dev)
+    hdrs, status = plan.new_headers(), plan.new_status()
+    r_ref, v_ref = np.zeros(n, F32), np.zeros(n, F32)
+    dense = torch.zeros(n, dtype=torch.float32, device=dev)
+    d_ref = np.zeros(n, F32)
+    rng = np.random.default_rng(5)
+    for step in range(steps):
+        # (g, s) with the distribution of `batch` i.i.d. N(0, sigma_l^2) samples, drawn directly:
+        # mean = sigma z / sqrt(B), sum of squares of y/B = sigma^2 (chi2_{B-1} + z^2) / B^2
+        B = cfg["batch"]
+        sg = np.repeat(sig, [L["size"] for L in layers])
+        z = rng.standard_normal(n)
+        g = (sg * z / np.sqrt(B)).astype(F32)
+        s = (sg * sg * (rng.chisquare(B - 1, n) + z * z) / (B * B)).astype(F32)
+        del z, sg
+        gd, sd = torch.from_numpy(g).to(dev), torch.from_numpy(s).to(dev)
+        vgc.accumulate_select(gd, sd, r, v, plan, alpha, cfg["zeta"], scratch)
+        mask = plan.send_mask(scratch)
+        vgc.pack(plan, scratch, words, hdrs, status)
+        torch.cuda.synchronize()
+        total, overflow = vgc.read_status(status)
+        vgc.unpack_add(words, total, hdrs, plan, 1.0 / 16, dense)
+        r_acc, r_ref, v_ref, send = O.accumulate_select(g, s, r_ref, v_ref, alpha, cfg["zeta"])
+        w_ref, h_ref, _ = O.pack(r_acc, send, groups, check=False)
+        O.unpack_add(w_ref, h_ref, groups, 1.0 / 16, d_ref)
+        assert np.array_equal(mask, send)
+        assert overflow == 0 and total == w_ref.size
+        assert vgc.read_headers(hdrs) == h_ref
+        assert np.array_equal(words[:total].cpu().numpy().view(U32), w_ref)
+        assert np.array_equal(_bits(r.cpu().numpy()), _bits(r_ref))
+        assert np.array_equal(_bits(v.cpu().numpy()), _bits(v_ref))
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(dense.cpu().numpy()), _bits(d_ref))
+
+
+@pytest.mark.parametrize("B,P,J,C,prec", [(64, 784, 4608, 512, "bf16"), (64, 196, 4608, 512, "bf16"),
+                                          (32, 3136, 576, 64, "f32"), (32, 196, 2304, 256, "f32")])
+def test_conv_statistic_sampled_outputs_at_config_shapes(dev, B, P, J, C, prec):
+    """3x3 convolution shapes of the VGG-16 (bf16, batch 64) and ResNet-50 (float32, batch 32) configs:
+    sampled outputs recomputed from the definition on the CPU, one per-sample gradient at a time."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    bf16 = prec == "bf16"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(B * 7 + P)
+    dt = torch.bfloat16 if bf16 else torch.float32
+    U = torch.randn((B, P, J), generator=gen, device=dev, dtype=torch.float32).to(dt)
+    D = (torch.randn((B, P, C), generator=gen, device=dev, dtype=torch.float32) * 3e-3).to(dt)
+    s = torch.empty(J, C, dtype=torch.float32, device=dev)
+    g = torch.empty(J, C, dtype=torch.float32, device=dev)
+    nb = vgc.sqgrad_workspace_bytes(vgc.CONV, vgc.BF16 if bf16 else vgc.F32, B, P, J, C)
+    ws = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
+    vgc.sqgrad(vgc.CONV, U, D, 1.0 / B, s, g, workspace=ws if nb else None)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(1)
+    jj = np.concatenate([rng.integers(0, J, 60), [0, J - 1, 0, J - 1]])
+    cc = np.concatenate([rng.integers(0, C, 60), [0, C - 1, C - 1, 0]])
+    tol = 1e-2 if bf16 else 1e-5
+    sh, gh = s.cpu().numpy(), g.cpu().numpy()
+    Uc = {int(j): U[:, :, int(j)].to(torch.float64).cpu().numpy() for j in set(jj.tolist())}
+    Dc = {int(c): D[:, :, int(c)].to(torch.float64).cpu().numpy() for c in set(cc.tolist())}
+    for j, c in zip(jj.tolist(), cc.tolist()):
+        terms = Uc[j] * Dc[c] / B                                # [B, P]
+        Gz = terms.sum(1)
+        s_ref, g_ref = (Gz ** 2).sum(), Gz.sum()
+        mag = np.abs(terms).sum(1)                               # what float32 accumulation error scales with
+        assert abs(sh[j, c] - s_ref) <= tol * (mag ** 2).sum()
+        assert abs(gh[j, c] - g_ref) <= tol * mag.sum()
+    assert np.isfinite(sh).all() and (sh >= 0).all()
