@@ -175,34 +175,50 @@ def measured_traffic(N):
 
 
 def bench_sqgrad(dev):
-    """Part (a) on two layer shapes of the VGG-16 configuration (bf16 inputs, batch 64)."""
+    """Part (a) on layer shapes of the VGG-16 (bf16, batch 64) and ResNet-50 (float32, batch 32)
+    configurations.  FC layers are bound by writing [J, C] floats (HBM roofline); conv layers by the
+    matrix cores (bf16 peak 2500 TFLOP/s, float32 peak 157.3 TFLOP/s).  s alone and g + s are timed."""
     import torch
     from paper_1802_06058_amd import vgc
     res = {}
-    shapes = [("fc6_25088x4096_B64_bf16", vgc.FC, 64, 1, 25088, 4096),
-              ("conv4_2_P784_4608x512_B64_bf16", vgc.CONV, 64, 784, 4608, 512)]
-    for name, kind, B, P, J, C in shapes:
+    shapes = [("vgg_fc6_25088x4096_B64_bf16", vgc.FC, torch.bfloat16, 64, 1, 25088, 4096),
+              ("vgg_conv4_2_P784_4608x512_B64_bf16", vgc.CONV, torch.bfloat16, 64, 784, 4608, 512),
+              ("vgg_conv3_2_P3136_2304x256_B64_bf16", vgc.CONV, torch.bfloat16, 64, 3136, 2304, 256),
+              ("resnet_s3_conv2_P196_2304x256_B32_f32", vgc.CONV, torch.float32, 32, 196, 2304, 256),
+              ("resnet_fc_2048x1000_B32_f32", vgc.FC, torch.float32, 32, 1, 2048, 1000)]
+    for name, kind, dt, B, P, J, C in shapes:
         gen = torch.Generator(device=dev); gen.manual_seed(1)
         shp_x = (B, J) if kind == vgc.FC else (B, P, J)
         shp_d = (B, C) if kind == vgc.FC else (B, P, C)
-        X = torch.randn(shp_x, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-        D = (torch.randn(shp_d, generator=gen, device=dev, dtype=torch.float32) * 1e-3).to(torch.bfloat16)
+        X = torch.randn(shp_x, generator=gen, device=dev, dtype=torch.float32).to(dt)
+        D = (torch.randn(shp_d, generator=gen, device=dev, dtype=torch.float32) * 1e-3).to(dt)
         g = torch.empty(J, C, dtype=torch.float32, device=dev)
         s = torch.empty(J, C, dtype=torch.float32, device=dev)
-        vgc.sqgrad(kind, X, D, 1.0 / B, s, g)
-        torch.cuda.synchronize()
-        reps = 3
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            vgc.sqgrad(kind, X, D, 1.0 / B, s, g)
-        e1.record(); torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
-        flops = (4.0 if kind == vgc.FC else 2.0) * B * P * J * C      # FC: two contractions; conv: one
-        byts = 8.0 * J * C + 2.0 * B * P * (J + C)
-        res[name] = {"ms": round(ms, 4), "TFLOPs": round(flops / (ms * 1e-3) / 1e12, 2),
-                     "GBs": round(byts / (ms * 1e-3) / 1e9, 1)}
-        del X, D, g, s
+        nb = vgc.sqgrad_workspace_bytes(kind, vgc.BF16 if dt == torch.bfloat16 else vgc.F32, B, P, J, C)
+        ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
+        peak = 2500.0 if dt == torch.bfloat16 else 157.3
+        entry = {}
+        for tag, gg in (("s_only", None), ("g_and_s", g)):
+            vgc.sqgrad(kind, X, D, 1.0 / B, s, gg, workspace=ws)
+            torch.cuda.synchronize()
+            reps = 5
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                vgc.sqgrad(kind, X, D, 1.0 / B, s, gg, workspace=ws)
+            e1.record(); torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            chains = 2.0 if (kind == vgc.FC and gg is not None) else 1.0      # FC: one contraction per output array
+            flops = chains * 2.0 * B * P * J * C
+            out_bytes = (8.0 if gg is not None else 4.0) * J * C
+            in_bytes = X.element_size() * B * P * (J + C)
+            tf = flops / (ms * 1e-3) / 1e12
+            entry[tag] = {"ms": round(ms, 4), "TFLOPs": round(tf, 1), "mfma_frac": round(tf / peak, 4),
+                          "algorithmic_GBs": round((out_bytes + in_bytes) / (ms * 1e-3) / 1e9, 1),
+                          "hbm_frac": round((out_bytes + in_bytes) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        entry["bound"] = "hbm" if kind == vgc.FC else "mfma"
+        res[name] = entry
+        del X, D, g, s, ws
     return res
 
 
