@@ -29,11 +29,7 @@ typedef __attribute__((address_space(3))) s4v* lds_s4v_ptr;
 #ifndef VGC_CONV_KC
 #define VGC_CONV_KC 32
 #endif
-#ifndef VGC_CONV_DEPTH
-#define VGC_CONV_DEPTH 3
-#endif
 constexpr int kKC = VGC_CONV_KC;         // positions per LDS stage
-constexpr int kDepthS = VGC_CONV_DEPTH;  // chunks in flight from global memory per thread (s alone; 2 when g is wanted too)
 
 // Row pitch (bf16 elements) of a staged tile of width W: W + 32, i.e. consecutive rows start 16 banks
 // apart, so the 4 rows x 2 column halves one half-wave reads with a transposing load fall on distinct banks.
@@ -126,80 +122,114 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             if (kWantG) g_acc[a][b] = (f16v){0};
         }
 
-    constexpr int kDepth = kWantG ? 2 : kDepthS;      // chunks in flight from global memory per thread
+    constexpr int kDepth = 2;                            // chunks in flight from global memory per thread
+    constexpr int kKS = kKC / 16;                        // MFMA k-steps per chunk
     ChunkRegs<BM, NT> ra[kDepth];
     ChunkRegs<BN, NT> rb[kDepth];
     uint32_t zl = z_begin, pcl = 0, issued = 0;          // cursor of the next chunk to request from global memory
     auto issue = [&](int slot_) {                       // past the last chunk the range is empty: zeros come back
         const bool live = issued < total;
-        const uint32_t zz = live ? zl : z_begin;
-        load_chunk<BM, NT>(ra[slot_], sample_rsrc(U + (size_t)zz * P * J, live ? P * J * 2u : 0u), J, pcl * kKC, j0, tid);
-        load_chunk<BN, NT>(rb[slot_], sample_rsrc(D + (size_t)zz * P * C, live ? P * C * 2u : 0u), C, pcl * kKC, c0, tid);
+        const uint32_t zz = live ? zl : z_begin, pq = pcl;
+        load_chunk<BM, NT>(ra[slot_], sample_rsrc(U + (size_t)zz * P * J, live ? P * J * 2u : 0u), J, pq * kKC, j0, tid);
+        load_chunk<BN, NT>(rb[slot_], sample_rsrc(D + (size_t)zz * P * C, live ? P * C * 2u : 0u), C, pq * kKC, c0, tid);
         if (++pcl == n_chunks) { pcl = 0; ++zl; }
         ++issued;
     };
-    // prologue: chunks 0 .. kDepth-1 requested, chunk 0 staged, its registers reused for chunk kDepth
+    auto sample_end = [&]() {                            // G_z is complete in acc: square into s, add into g, clear
 #pragma unroll
-    for (int d = 0; d < kDepth; ++d) issue(d);
-    store_chunk<BM, NT>(shA[0], ra[0], tid);
-    store_chunk<BN, NT>(shB[0], rb[0], tid);
-    issue(0);
-    __syncthreads();
-
-    // The loop body is free of branches around memory operations (the trip count is rounded up to a
-    // multiple of kDepth; the surplus chunks are all zeros and add nothing), which keeps the compiler's
-    // count of outstanding loads exact.
-    uint32_t pc = 0, zdone = z_begin;
-    for (uint32_t q0 = 0; q0 < total; q0 += kDepth) {
+        for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
-        for (int u = 0; u < kDepth; ++u) {
-            const uint32_t q = q0 + u;
-            const uint32_t buf = q & 1u;
-            // operand fragments of k-step ks+1 are fetched from LDS while the MFMAs of step ks run
-            bf8v fa[2][2], fb[2][2];
+            for (int nt = 0; nt < 2; ++nt) {
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                fa[0][t] = lds_frag_bf16<BM>(shA[buf], 0, wm * 64 + t * 32, lane);
-                fb[0][t] = lds_frag_bf16<BN>(shB[buf], 0, wn * 64 + t * 32, lane);
+                for (int i = 0; i < 16; ++i) {
+                    const float x = acc[mt][nt][i];
+                    s_acc[mt][nt][i] += x * x;
+                    if (kWantG) g_acc[mt][nt][i] += x;
+                }
+                acc[mt][nt] = (f16v){0};
             }
+    };
+    // The loop bodies are free of branches around memory operations (the trip count is rounded up to a
+    // multiple of the unroll factor; the surplus chunks are all zeros and add nothing), which keeps the
+    // compiler's count of outstanding loads exact.
+    uint32_t pc = 0, zdone = z_begin;
+
+    if constexpr (!kWantG) {
+        // Pipelined across the barrier: the operand fragments of chunk q+1 are read from LDS while the
+        // MFMAs of chunk q run from registers, and chunk q+2 is staged into the buffer chunk q came from.
+        bf8v F[2][kKS][2][2];                            // [ping-pong][k-step][A / B][32-wide tile]
+        auto read_frags = [&](int pp, uint32_t buf) {
 #pragma unroll
-            for (int ks = 0; ks < kKC / 16; ++ks) {
-                const int cur = ks & 1, nxt = cur ^ 1;
-                if (ks + 1 < kKC / 16) {        // (with g the register budget is tighter; the compiler may serialise these)
+            for (int ks = 0; ks < kKS; ++ks)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    F[pp][ks][0][t] = lds_frag_bf16<BM>(shA[buf], ks, wm * 64 + t * 32, lane);
+                    F[pp][ks][1][t] = lds_frag_bf16<BN>(shB[buf], ks, wn * 64 + t * 32, lane);
+                }
+        };
+        issue(0);
+        issue(1);
+        store_chunk<BM, NT>(shA[0], ra[0], tid);
+        store_chunk<BN, NT>(shB[0], rb[0], tid);
+        issue(0);
+        __syncthreads();
+        read_frags(0, 0);
+        store_chunk<BM, NT>(shA[1], ra[1], tid);
+        store_chunk<BN, NT>(shB[1], rb[1], tid);
+        issue(1);
+        __syncthreads();
+        for (uint32_t q0 = 0; q0 < total; q0 += 2) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {                // chunk q = q0 + u lives in fragment set u, LDS buffer u
+                read_frags(u ^ 1, (uint32_t)(u ^ 1));
+#pragma unroll
+                for (int ks = 0; ks < kKS; ++ks)
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[u][ks][0][mt], F[u][ks][1][nt], acc[mt][nt], 0, 0, 0);
+                // keep the MFMAs ahead of the wait for the global loads: they run in the matrix pipe while
+                // the wave waits, stages and issues the next loads
+                __builtin_amdgcn_sched_barrier(0);
+                store_chunk<BM, NT>(shA[u], ra[u], tid);  // chunk q+2, then its registers take chunk q+4
+                store_chunk<BN, NT>(shB[u], rb[u], tid);
+                issue(u);
+                if (++pc == n_chunks && zdone < z_end) { pc = 0; ++zdone; sample_end(); }
+                __syncthreads();
+            }
+        }
+    } else {
+        issue(0);
+        issue(1);
+        store_chunk<BM, NT>(shA[0], ra[0], tid);
+        store_chunk<BN, NT>(shB[0], rb[0], tid);
+        issue(0);
+        __syncthreads();
+        for (uint32_t q0 = 0; q0 < total; q0 += 2) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {                // chunk q = q0 + u is in LDS buffer u
+#pragma unroll
+                for (int ks = 0; ks < kKS; ++ks) {
+                    bf8v fa[2], fb[2];
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        fa[nxt][t] = lds_frag_bf16<BM>(shA[buf], ks + 1, wm * 64 + t * 32, lane);
-                        fb[nxt][t] = lds_frag_bf16<BN>(shB[buf], ks + 1, wn * 64 + t * 32, lane);
+                        fa[t] = lds_frag_bf16<BM>(shA[u], ks, wm * 64 + t * 32, lane);
+                        fb[t] = lds_frag_bf16<BN>(shB[u], ks, wn * 64 + t * 32, lane);
                     }
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
                 }
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[cur][mt], fb[cur][nt], acc[mt][nt], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);       // MFMAs issue before the wait for the global loads
+                store_chunk<BM, NT>(shA[u ^ 1], ra[u ^ 1], tid);   // chunk q+1, then its registers take chunk q+3
+                store_chunk<BN, NT>(shB[u ^ 1], rb[u ^ 1], tid);
+                issue(u ^ 1);
+                if (++pc == n_chunks && zdone < z_end) { pc = 0; ++zdone; sample_end(); }
+                __syncthreads();
             }
-            // chunk q+1 sits in register set (u+1) % kDepth: stage it, then reuse the set for chunk q+1+kDepth
-            const int ns = (u + 1) % kDepth;
-            store_chunk<BM, NT>(shA[buf ^ 1u], ra[ns], tid);
-            store_chunk<BN, NT>(shB[buf ^ 1u], rb[ns], tid);
-            issue(ns);
-            if (++pc == n_chunks && zdone < z_end) {   // sample finished: G_z is complete in acc
-                pc = 0;
-                ++zdone;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt) {
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            const float x = acc[mt][nt][i];
-                            s_acc[mt][nt][i] += x * x;
-                            if (kWantG) g_acc[mt][nt][i] += x;
-                        }
-                        acc[mt][nt] = (f16v){0};
-                    }
-            }
-            __syncthreads();
         }
     }
 
