@@ -297,3 +297,63 @@ def unpack_add(words, headers, groups, scale, out):
         contrib = (sc * val).astype(F32)
         out[off + idx] = out[off + idx] + contrib
     return out
+
+
+# --------------------------------------------------------------------------------------
+# Hybrid algorithm (Alg. 2, Section 4.5): variance criterion combined with Strom's threshold
+# --------------------------------------------------------------------------------------
+
+def accumulate_select_hybrid(g, s, r, v, alpha, zeta, tau, abs_r="before"):
+    """One step of Alg. 2 for every parameter, float32, one rounding per operation.
+
+        r += g;  v += s
+        if |r| > tau and r^2 > alpha v:   send Sign(r);  r -= Sign(r) tau;  v = max(v - 2|r|tau + tau^2, 0)
+        v *= zeta                                        (always, unlike Alg. 1)
+
+    The correction of v is Section 4.5's "modify a^2 to (a - b)^2" with b = S = +-tau the value sent and
+    a the accumulated gradient, so |r| in it is the value BEFORE tau is subtracted (abs_r="before");
+    Alg. 2 as printed updates r first, which would use the value after (abs_r="after").  The expression
+    is evaluated left to right: ((v - (2|r|) tau) + tau*tau).
+
+    Returns (r_out, v_out, send, sign) with sign = +1 / -1 where sent, 0 elsewhere.
+    """
+    g = np.asarray(g, dtype=F32)
+    s = np.asarray(s, dtype=F32)
+    r = np.asarray(r, dtype=F32)
+    v = np.asarray(v, dtype=F32)
+    a32, z32, t32 = F32(alpha), F32(zeta), F32(tau)
+    r_acc = r + g
+    v_acc = v + s
+    send = (np.abs(r_acc) > t32) & ((r_acc * r_acc) > (a32 * v_acc))
+    sgn = np.where(r_acc < 0, F32(-1), F32(1)).astype(F32)
+    r_sent = (r_acc - sgn * t32).astype(F32)
+    absr = np.abs(r_acc) if abs_r == "before" else np.abs(r_sent)
+    if abs_r not in ("before", "after"):
+        raise ValueError(abs_r)
+    two_r_tau = ((F32(2) * absr) * t32).astype(F32)
+    v_sent = np.maximum(((v_acc - two_r_tau) + (t32 * t32)).astype(F32), F32(0))
+    r_out = np.where(send, r_sent, r_acc).astype(F32)
+    v_out = (z32 * np.where(send, v_sent, v_acc)).astype(F32)
+    sign = np.where(send, sgn, F32(0)).astype(F32)
+    return r_out, v_out, send, sign
+
+
+def pack_hybrid(sign, send, groups):
+    """Encode(Sign(r)) of Alg. 2 in the word format of Section 4.2: one word per sent element with the
+    sign bit and the group-local index, exponent code d = 0.  The header's exponent field is 127
+    (2^0 = 1): a message is in units of tau, and the receiver decodes with scale = tau (times 1/p for
+    the mean), so the decoder of the basic algorithm serves unchanged."""
+    sign = np.asarray(sign, dtype=F32)
+    send = np.asarray(send, dtype=bool)
+    words, headers, word_offset = [], [], 0
+    for (off, size) in groups:
+        idx = np.flatnonzero(send[off:off + size])
+        if idx.size == 0:
+            headers.append((0, 0, word_offset))
+            continue
+        neg = (sign[off:off + size][idx] < 0).astype(np.uint64)
+        words.append(((neg << np.uint64(31)) | idx.astype(np.uint64)).astype(U32))
+        headers.append((127, int(idx.size), word_offset))
+        word_offset += int(idx.size)
+    words = np.concatenate(words) if words else np.zeros(0, dtype=U32)
+    return words, headers
