@@ -155,6 +155,25 @@ def main():
         "input_generation_s": round(gen_s, 1),
     }
 
+    # hybrid algorithm (Alg. 2) on worker 0's buffers: same kernels with the threshold rule, tau = 0.05
+    r[0].zero_(); v[0].zero_()
+    hy_ms, hy_words = [], []
+    for k in range(4):
+        g, s = pool[k % P]
+        e0, e1 = ev(), ev()
+        e0.record()
+        vgc.accumulate_select_hybrid(g, s, r[0], v[0], plan, 2.0, zeta, 0.05, scratch)
+        vgc.pack(plan, scratch, words[0], hdrs[0], status[0])
+        e1.record()
+        torch.cuda.synchronize()
+        if k:
+            hy_ms.append(e0.elapsed_time(e1)); hy_words.append(vgc.read_status(status[0])[0])
+    hy, hrho = float(np.mean(hy_ms)), float(np.mean(hy_words)) / N
+    out["stages"]["hybrid_select_plus_pack"] = {
+        "alpha": 2.0, "tau": 0.05, "ms": round(hy, 4), "sent_fraction": round(hrho, 5),
+        "algorithmic_GBs": round((24.0 + 4.0 * hrho) * N / (hy * 1e-3) / 1e9, 1),
+        "frac_of_peak": round((24.0 + 4.0 * hrho) * N / (hy * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+
     if not a.no_sqgrad:
         out["stages"]["sqgrad"] = bench_sqgrad(dev)
     if not a.no_cpu_baseline:

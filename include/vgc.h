@@ -152,6 +152,18 @@ int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, ui
                           const vgc_group* groups, uint32_t n_groups, const void* plan,
                           float alpha, float zeta, void* scratch, void* stream);
 
+/* Hybrid algorithm (Alg. 2, Section 4.5: the variance criterion combined with a threshold tau):
+ *     r' = r + g;  v' = v + s;  send = (|r'| > tau) and (r'*r' > alpha*v')
+ *     sent:   r = r' - sign(r')*tau;   v = max((v' - (2|r'|)*tau) + tau*tau, 0)      (|r'| before the subtraction)
+ *     always: v = zeta * v
+ * What is sent is Sign(r'), i.e. +-tau.  The staged result goes through the same vgc_pack: the message
+ * has exp_field = 127 (2^0) in the header of every non-empty group and d = 0 in every word, and
+ * vgc_unpack_add decodes it with scale = tau (times 1/p for the mean).  Same arguments as above, plus
+ * tau >= 0 finite. */
+int vgc_accumulate_select_hybrid(const float* g, const float* s, float* r, float* v, uint64_t n,
+                                 const vgc_group* groups, uint32_t n_groups, const void* plan,
+                                 float alpha, float zeta, float tau, void* scratch, void* stream);
+
 /* ---- (c) quantise, compact, pack ------------------------------------------------------------
  * Encode() of Alg. 1 (Sections 4.2 and 4.4): per group, M_k = the largest magnitude among the
  * elements being sent, header = floor(log2 M_k); each sent element becomes one word (layout

@@ -163,9 +163,9 @@ int vgc_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, ui
                          static_cast<hipStream_t>(stream));
 }
 
-int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, uint64_t n,
-                          const vgc_group* groups, uint32_t n_groups, const void* plan,
-                          float alpha, float zeta, void* scratch, void* stream) {
+static int accumulate_select_any(const float* g, const float* s, float* r, float* v, uint64_t n,
+                                 const vgc_group* groups, uint32_t n_groups, const void* plan,
+                                 float alpha, float zeta, float tau, bool hybrid, void* scratch, void* stream) {
     if (!g || !s || !r || !v || !plan || !scratch) { set_error("vgc_accumulate_select: NULL pointer"); return VGC_ERR_NULL; }
     uint64_t n_tiles = 0;
     int rc = check_groups(groups, n_groups, n, &n_tiles);
@@ -178,6 +178,10 @@ int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, ui
         set_error("vgc_accumulate_select: need alpha >= 0 finite and 0 < zeta <= 1 (got %g, %g)", alpha, zeta);
         return VGC_ERR_PARAM;
     }
+    if (hybrid && (!(tau >= 0.0f) || !std::isfinite(tau))) {
+        set_error("vgc_accumulate_select_hybrid: need tau >= 0 finite (got %g)", tau);
+        return VGC_ERR_PARAM;
+    }
     const ScratchLayout L = scratch_layout(n_tiles, n_groups);
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
     char* sc = static_cast<char*>(scratch);
@@ -186,7 +190,19 @@ int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, ui
                                     reinterpret_cast<TileHdr*>(sc + L.tile_hdr_off),
                                     reinterpret_cast<uint32_t*>(sc + L.bitmap_off),
                                     reinterpret_cast<uint16_t*>(sc + L.staging_off),
-                                    alpha, zeta, vec, static_cast<hipStream_t>(stream));
+                                    alpha, zeta, tau, hybrid, vec, static_cast<hipStream_t>(stream));
+}
+
+int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, uint64_t n,
+                          const vgc_group* groups, uint32_t n_groups, const void* plan,
+                          float alpha, float zeta, void* scratch, void* stream) {
+    return accumulate_select_any(g, s, r, v, n, groups, n_groups, plan, alpha, zeta, 0.0f, false, scratch, stream);
+}
+
+int vgc_accumulate_select_hybrid(const float* g, const float* s, float* r, float* v, uint64_t n,
+                                 const vgc_group* groups, uint32_t n_groups, const void* plan,
+                                 float alpha, float zeta, float tau, void* scratch, void* stream) {
+    return accumulate_select_any(g, s, r, v, n, groups, n_groups, plan, alpha, zeta, tau, true, scratch, stream);
 }
 
 int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void* plan, void* scratch,

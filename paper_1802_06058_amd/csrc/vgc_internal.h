@@ -98,7 +98,8 @@ int hip_check(hipError_t e, const char* what);
 int launch_accumulate_select(const float* g, const float* s, float* r, float* v,
                              const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles,
                              TileHdr* hdrs, uint32_t* bitmap, uint16_t* staging,
-                             float alpha, float zeta, bool ptrs_vec_aligned, hipStream_t stream);
+                             float alpha, float zeta, float tau, bool hybrid, bool ptrs_vec_aligned,
+                             hipStream_t stream);
 
 int launch_pack(const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles, uint32_t n_groups,
                 TileHdr* hdrs, GroupTmp* gtmp, const uint16_t* staging,

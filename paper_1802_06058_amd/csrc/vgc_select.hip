@@ -34,16 +34,43 @@ __device__ __forceinline__ bool alg1_step(float g, float s, float r, float v, fl
     return send;
 }
 
+// Alg. 2 loop body (hybrid with the threshold method, Section 4.5) for one element:
+//   send = |r'| > tau and r'^2 > alpha v';  sent: r = r' - sign(r') tau,  v = max((v' - (2|r'|) tau) + tau^2, 0);
+//   v *= zeta always.  What is staged for a sent element is +-1.0f: the message carries signs in units of
+//   tau, so the exponent machinery of the basic algorithm sees one constant magnitude (header 2^0, code 0).
+__device__ __forceinline__ bool alg2_step(float g, float s, float r, float v, float alpha, float zeta, float tau,
+                                          float& r_out, float& v_out, uint32_t& acc_bits) {
+    const float rp = r + g;
+    const float vp = v + s;
+    const float lhs = rp * rp;
+    const float rhs = alpha * vp;
+    const bool send = (fabsf(rp) > tau) && (lhs > rhs);
+    const float r_sent = rp - copysignf(tau, rp);
+    const float two_r_tau = (2.0f * fabsf(rp)) * tau;
+    const float v_sent = fmaxf((vp - two_r_tau) + (tau * tau), 0.0f);
+    r_out = send ? r_sent : rp;
+    v_out = zeta * (send ? v_sent : vp);
+    acc_bits = (__float_as_uint(rp) & 0x80000000u) | 0x3F800000u;
+    return send;
+}
+
+template <bool kHybrid>
+__device__ __forceinline__ bool step_any(float g, float s, float r, float v, float alpha, float zeta, float tau,
+                                         float& r_out, float& v_out, uint32_t& acc_bits) {
+    if (kHybrid) return alg2_step(g, s, r, v, alpha, zeta, tau, r_out, v_out, acc_bits);
+    return alg1_step(g, s, r, v, alpha, zeta, r_out, v_out, acc_bits);
+}
+
 // kVec: lane owns elements {u*1024 + 4*tid + c}, u < 2, c < 4 (16-byte accesses).
 // !kVec: lane owns elements {u*256 + tid}, u < 8 (4-byte accesses, any alignment, bounds-checked).
 // Element e of a thread is (u, c) = (e / 4, e % 4) resp. u = e.  In both layouts the elements of
 // segment (u, wave) are a contiguous index range and segments are ordered by u*4 + wave.
-template <bool kVec>
+template <bool kVec, bool kHybrid>
 __device__ __forceinline__ void tile_body(const float* __restrict__ g, const float* __restrict__ s,
                                           float* __restrict__ r, float* __restrict__ v,
                                           uint32_t m, TileHdr* __restrict__ hdr,
                                           uint32_t* __restrict__ bitmap, uint16_t* __restrict__ staging,
-                                          float alpha, float zeta) {
+                                          float alpha, float zeta, float tau) {
     __shared__ uint32_t sh_wmax[4];
     __shared__ uint32_t sh_seg[32];
     __shared__ uint32_t sh_hist[4][kRelBins];
@@ -77,7 +104,7 @@ __device__ __forceinline__ void tile_body(const float* __restrict__ g, const flo
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
                 float a, b;
-                const bool send = alg1_step(G[u][c], S[u][c], R[u][c], V[u][c], alpha, zeta, a, b, bits[u * 4 + c]);
+                const bool send = step_any<kHybrid>(G[u][c], S[u][c], R[u][c], V[u][c], alpha, zeta, tau, a, b, bits[u * 4 + c]);
                 ro[c] = a;
                 vo[c] = b;
                 sendmask |= (send ? 1u : 0u) << (u * 4 + c);
@@ -103,7 +130,7 @@ __device__ __forceinline__ void tile_body(const float* __restrict__ g, const flo
         for (int u = 0; u < E; ++u) {
             const uint32_t i = u * 256 + tid;
             float a, b;
-            const bool send = alg1_step(G[u], S[u], R[u], V[u], alpha, zeta, a, b, bits[u]) && (i < m);
+            const bool send = step_any<kHybrid>(G[u], S[u], R[u], V[u], alpha, zeta, tau, a, b, bits[u]) && (i < m);
             sendmask |= (send ? 1u : 0u) << u;
             if (i < m) {
                 __builtin_nontemporal_store(a, r + i);
@@ -232,11 +259,12 @@ __device__ __forceinline__ void tile_body(const float* __restrict__ g, const flo
     }
 }
 
+template <bool kHybrid>
 __global__ __launch_bounds__(256) void k_accumulate_select(
     const float* __restrict__ g, const float* __restrict__ s, float* __restrict__ r, float* __restrict__ v,
     const PlanGroup* __restrict__ groups, const PlanTile* __restrict__ tiles,
     TileHdr* __restrict__ hdrs, uint32_t* __restrict__ bitmap, uint16_t* __restrict__ staging,
-    float alpha, float zeta, int ptrs_vec_aligned) {
+    float alpha, float zeta, float tau, int ptrs_vec_aligned) {
     const uint64_t t = blockIdx.x;
     const PlanTile pt = tiles[t];
     const PlanGroup pg = groups[pt.group];
@@ -246,21 +274,26 @@ __global__ __launch_bounds__(256) void k_accumulate_select(
     uint32_t* bm = bitmap + t * (kTile / 32);
     uint16_t* st = staging + t * kTile;
     if (m == kTile && (base & 3u) == 0 && ptrs_vec_aligned)
-        tile_body<true>(g + base, s + base, r + base, v + base, m, hdr, bm, st, alpha, zeta);
+        tile_body<true, kHybrid>(g + base, s + base, r + base, v + base, m, hdr, bm, st, alpha, zeta, tau);
     else
-        tile_body<false>(g + base, s + base, r + base, v + base, m, hdr, bm, st, alpha, zeta);
+        tile_body<false, kHybrid>(g + base, s + base, r + base, v + base, m, hdr, bm, st, alpha, zeta, tau);
 }
 
 int launch_accumulate_select(const float* g, const float* s, float* r, float* v,
                              const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles,
                              TileHdr* hdrs, uint32_t* bitmap, uint16_t* staging,
-                             float alpha, float zeta, bool ptrs_vec_aligned, hipStream_t stream) {
+                             float alpha, float zeta, float tau, bool hybrid, bool ptrs_vec_aligned,
+                             hipStream_t stream) {
     if (n_tiles > 0x7FFFFFFFull) {
         set_error("vgc_accumulate_select: %llu tiles exceed the launch limit", (unsigned long long)n_tiles);
         return VGC_ERR_SIZE;
     }
-    hipLaunchKernelGGL(k_accumulate_select, dim3((uint32_t)n_tiles), dim3(kThreads), 0, stream,
-                       g, s, r, v, groups, tiles, hdrs, bitmap, staging, alpha, zeta, ptrs_vec_aligned ? 1 : 0);
+    if (hybrid)
+        hipLaunchKernelGGL(k_accumulate_select<true>, dim3((uint32_t)n_tiles), dim3(kThreads), 0, stream,
+                           g, s, r, v, groups, tiles, hdrs, bitmap, staging, alpha, zeta, tau, ptrs_vec_aligned ? 1 : 0);
+    else
+        hipLaunchKernelGGL(k_accumulate_select<false>, dim3((uint32_t)n_tiles), dim3(kThreads), 0, stream,
+                           g, s, r, v, groups, tiles, hdrs, bitmap, staging, alpha, zeta, 0.0f, ptrs_vec_aligned ? 1 : 0);
     return hip_check(hipGetLastError(), "launch k_accumulate_select");
 }
 

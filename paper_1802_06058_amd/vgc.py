@@ -50,6 +50,9 @@ EXPORTS = {
                              C.c_uint32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "vgc_accumulate_select": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
                                         C.c_uint32, C.c_void_p, C.c_float, C.c_float, C.c_void_p, C.c_void_p]),
+    "vgc_accumulate_select_hybrid": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
+                                               C.c_uint32, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p,
+                                               C.c_void_p]),
     "vgc_pack": (C.c_int, [C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
                            C.c_void_p, C.c_void_p, C.c_void_p]),
     "vgc_unpack_add": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
@@ -185,6 +188,12 @@ def sqgrad(kind, X, D, c, s_out, g_out=None, workspace=None):
 def accumulate_select(g, s, r, v, plan, alpha, zeta, scratch):
     _check(load().vgc_accumulate_select(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups, plan.n_groups,
                                         _ptr(plan.plan), float(alpha), float(zeta), _ptr(scratch), _stream()))
+
+
+def accumulate_select_hybrid(g, s, r, v, plan, alpha, zeta, tau, scratch):
+    _check(load().vgc_accumulate_select_hybrid(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups,
+                                               plan.n_groups, _ptr(plan.plan), float(alpha), float(zeta), float(tau),
+                                               _ptr(scratch), _stream()))
 
 
 def pack(plan, scratch, words, hdrs, status):

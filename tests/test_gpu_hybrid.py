@@ -1,0 +1,78 @@
+"""Parity of the hybrid path (Alg. 2) on the GPU against the oracle: mask, signs, state, headers, words
+bit for bit, decoded with scale = tau, several steps with state carry."""
+import numpy as np
+import pytest
+
+from oracle import vgc_oracle as O
+from paper_1802_06058_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+F32 = np.float32
+U32 = np.uint32
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+    from paper_1802_06058_amd import vgc
+    assert torch.cuda.is_available()
+    vgc.load()
+    return torch.device("cuda:0")
+
+
+def _bits(a):
+    return np.ascontiguousarray(a).view(U32)
+
+
+@pytest.mark.parametrize("sizes", [[2048 * 5], [1000, 1, 37, 5000, 64, 2048, 4099, 3, 6144, 10], [3, 2048 * 3, 5, 2048 * 2 + 1]])
+@pytest.mark.parametrize("alpha,tau", [(2.0, 0.01), (1.0, 0.002), (0.0, 0.02)])
+def test_hybrid_steps_match_oracle(dev, sizes, alpha, tau):
+    import torch
+    from paper_1802_06058_amd import vgc
+    groups = W.groups_from_sizes(sizes)
+    plan = vgc.Plan(groups, dev)
+    n = plan.n
+    r_ref, v_ref = np.zeros(n, F32), np.zeros(n, F32)
+    r = torch.zeros(n, dtype=torch.float32, device=dev)
+    v = torch.zeros(n, dtype=torch.float32, device=dev)
+    scratch = plan.new_scratch()
+    words = torch.full((n,), -1, dtype=torch.int32, device=dev)
+    hdrs, status = plan.new_headers(), plan.new_status()
+    dense = torch.zeros(n, dtype=torch.float32, device=dev)
+    d_ref = np.zeros(n, F32)
+    sent_total = 0
+    for step in range(4):
+        g, s = W.sample_stream(31, (len(sizes), step), n, 16, "student", sigma=0.02)
+        g += F32(0.004)                                         # a drift, so that residuals keep crossing tau
+        vgc.accumulate_select_hybrid(torch.from_numpy(g).to(dev), torch.from_numpy(s).to(dev), r, v, plan,
+                                     alpha, 0.999, tau, scratch)
+        mask = plan.send_mask(scratch)
+        vgc.pack(plan, scratch, words, hdrs, status)
+        torch.cuda.synchronize()
+        total, overflow = vgc.read_status(status)
+        vgc.unpack_add(words, total, hdrs, plan, tau / 4, dense)
+        r_ref, v_ref, send, sign = O.accumulate_select_hybrid(g, s, r_ref, v_ref, alpha, 0.999, tau)
+        w_ref, h_ref = O.pack_hybrid(sign, send, groups)
+        O.unpack_add(w_ref, h_ref, groups, tau / 4, d_ref)
+        assert np.array_equal(mask, send)
+        assert overflow == 0 and total == w_ref.size
+        assert vgc.read_headers(hdrs) == h_ref
+        assert np.array_equal(words[:total].cpu().numpy().view(U32), w_ref)
+        assert np.array_equal(_bits(r.cpu().numpy()), _bits(r_ref))
+        assert np.array_equal(_bits(v.cpu().numpy()), _bits(v_ref))
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(dense.cpu().numpy()), _bits(d_ref))
+        sent_total += int(send.sum())
+    assert sent_total > 0
+
+
+def test_hybrid_rejects_bad_tau(dev):
+    import torch
+    from paper_1802_06058_amd import vgc
+    plan = vgc.Plan(W.groups_from_sizes([100]), dev)
+    t = torch.zeros(100, dtype=torch.float32, device=dev)
+    with pytest.raises(vgc.VgcError):
+        vgc.accumulate_select_hybrid(t, t, t, t, plan, 1.0, 0.999, -0.1, plan.new_scratch())
+    with pytest.raises(vgc.VgcError):
+        vgc.accumulate_select_hybrid(t, t, t, t, plan, 1.0, 0.999, float("nan"), plan.new_scratch())
