@@ -174,6 +174,7 @@ def main():
         "algorithmic_GBs": round((24.0 + 4.0 * hrho) * N / (hy * 1e-3) / 1e9, 1),
         "frac_of_peak": round((24.0 + 4.0 * hrho) * N / (hy * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    out["stages"]["model_parameter_sets"] = bench_model_sets(dev, a.alpha, zeta)
     if not a.no_sqgrad:
         out["stages"]["sqgrad"] = bench_sqgrad(dev)
     if not a.no_cpu_baseline:
@@ -191,6 +192,47 @@ def measured_traffic(N):
         if line.startswith("k_accumulate_select_traffic_bytes_per_launch_n1e9:"):
             return float(line.split(":")[1])
     return None
+
+
+def bench_model_sets(dev, alpha, zeta):
+    """select + pack on the ResNet-50-shaped (161 groups, 25.6 M) and VGG-16-shaped (32 groups, 138 M)
+    parameter sets: many groups of very different sizes in one launch."""
+    import torch
+    from paper_1802_06058_amd import vgc, workloads as W
+    res = {}
+    for name in ("C3", "C4"):
+        cfg = W.CONFIGS[name]
+        layers = cfg["layers"]
+        plan = vgc.Plan(W.groups_from_sizes([L["size"] for L in layers]), dev)
+        n, B = plan.n, cfg["batch"]
+        sig = torch.from_numpy(np.repeat(W.layer_sigmas(cfg["seed"], len(layers)), [L["size"] for L in layers]).astype(np.float32)).to(dev)
+        gen = torch.Generator(device=dev); gen.manual_seed(3)
+        r = torch.zeros(n, dtype=torch.float32, device=dev); v = torch.zeros(n, dtype=torch.float32, device=dev)
+        scratch, hdrs, status = plan.new_scratch(), plan.new_headers(), plan.new_status()
+        words = torch.empty(n, dtype=torch.int32, device=dev)
+        ms, sent = [], []
+        for k in range(6):
+            z = torch.randn(n, generator=gen, device=dev)
+            chi = torch.zeros(n, device=dev)
+            for _ in range(B - 1):
+                w = torch.randn(n, generator=gen, device=dev); chi += w * w
+            g = sig * z / B ** 0.5
+            s = sig * sig * (chi + z * z) / (B * B)
+            del z, chi
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            vgc.accumulate_select(g, s, r, v, plan, alpha, zeta, scratch)
+            vgc.pack(plan, scratch, words, hdrs, status)
+            e1.record(); torch.cuda.synchronize()
+            if k:
+                ms.append(e0.elapsed_time(e1)); sent.append(vgc.read_status(status)[0])
+        t, rho = float(np.mean(ms)), float(np.mean(sent)) / n
+        res[name] = {"n_params": n, "n_groups": plan.n_groups, "select_plus_pack_ms": round(t, 4),
+                     "sent_fraction": round(rho, 4), "Gparams_per_s": round(n / (t * 1e-3) / 1e9, 1),
+                     "algorithmic_GBs": round((24 + 4 * rho) * n / (t * 1e-3) / 1e9, 1),
+                     "frac_of_peak": round((24 + 4 * rho) * n / (t * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    return res
 
 
 def bench_sqgrad(dev):

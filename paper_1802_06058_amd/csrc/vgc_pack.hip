@@ -47,9 +47,18 @@ __global__ __launch_bounds__(1024) void k_group_scan(const PlanGroup* __restrict
     TileHdr* H = hdrs + pg.first_tile;
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
 
-    // E_k: the largest exponent among all sent elements of the group
+    // E_k: the largest exponent among all sent elements of the group (eight independent loads in flight)
     uint32_t e = 0;
-    for (uint32_t i = tid; i < nt; i += 1024) e = max(e, H[i].w[4] >> 16);
+    for (uint32_t i0 = 0; i0 < nt; i0 += 8 * 1024) {
+        uint32_t w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t i = i0 + (uint32_t)j * 1024 + tid;
+            w[j] = (i < nt) ? H[i].w[4] : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) e = max(e, w[j] >> 16);
+    }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) e = max(e, (uint32_t)__shfl_xor((int)e, off));
     if (lane == 0) sh[wave] = e;
@@ -62,28 +71,48 @@ __global__ __launch_bounds__(1024) void k_group_scan(const PlanGroup* __restrict
     __syncthreads();
     const uint32_t E = sh_e;
 
+    // each thread owns 8 consecutive tiles per pass: their headers are loaded together, scanned in
+    // registers, and only the per-thread totals go through the workgroup scan
     uint32_t running = 0;
-    for (uint32_t base = 0; base < nt; base += 1024) {
-        const uint32_t i = base + tid;
-        uint32_t kept = 0, shift = 0;
-        if (i < nt) {
-            const uint4 lo = reinterpret_cast<const uint4*>(H + i)[0];
-            const uint32_t w4 = H[i].w[4];
-            shift = E - (w4 >> 16);
-            if (E != 0 && shift <= 8) {
-                const uint32_t h[9] = {lo.x & 0xFFFFu, lo.x >> 16, lo.y & 0xFFFFu, lo.y >> 16, lo.z & 0xFFFFu,
-                                       lo.z >> 16, lo.w & 0xFFFFu, lo.w >> 16, w4 & 0xFFFFu};
-                const uint32_t lim = 8 - shift;            // entries with rel <= lim are encoded
+    for (uint32_t base = 0; base < nt; base += 8 * 1024) {
+        uint4 lo[8];
+        uint32_t w4[8];
 #pragma unroll
-                for (int j = 0; j < 9; ++j) kept += ((uint32_t)j <= lim) ? h[j] : 0u;
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t i = base + tid * 8 + j;
+            lo[j] = make_uint4(0u, 0u, 0u, 0u);
+            w4[j] = 0u;
+            if (i < nt) {
+                lo[j] = reinterpret_cast<const uint4*>(H + i)[0];
+                w4[j] = H[i].w[4];
             }
         }
+        uint32_t kept[8], shift[8], mine = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            shift[j] = E - (w4[j] >> 16);
+            kept[j] = 0;
+            if (E != 0 && shift[j] <= 8) {
+                const uint32_t h[9] = {lo[j].x & 0xFFFFu, lo[j].x >> 16, lo[j].y & 0xFFFFu, lo[j].y >> 16, lo[j].z & 0xFFFFu,
+                                       lo[j].z >> 16, lo[j].w & 0xFFFFu, lo[j].w >> 16, w4[j] & 0xFFFFu};
+                const uint32_t lim = 8 - shift[j];          // entries with rel <= lim are encoded
+#pragma unroll
+                for (int q = 0; q < 9; ++q) kept[j] += ((uint32_t)q <= lim) ? h[q] : 0u;
+            }
+            mine += kept[j];
+        }
         uint32_t total;
-        const uint32_t incl = block_scan_1024(kept, sh, total);
-        if (i < nt) {
-            H[i].w[5] = running + incl - kept;
-            H[i].w[6] = shift;
-            H[i].w[7] = kept;
+        const uint32_t incl = block_scan_1024(mine, sh, total);
+        uint32_t prefix = running + incl - mine;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t i = base + tid * 8 + j;
+            if (i < nt) {
+                H[i].w[5] = prefix;
+                H[i].w[6] = shift[j];
+                H[i].w[7] = kept[j];
+            }
+            prefix += kept[j];
         }
         running += total;
     }
