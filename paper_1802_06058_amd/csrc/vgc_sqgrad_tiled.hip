@@ -178,23 +178,38 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         store_chunk<BN, NT>(shB[1], rb[1], tid);
         issue(1);
         __syncthreads();
+        // A wave issues in order, and the two waves of a SIMD run in lockstep between barriers: if the
+        // MFMAs sat in one block and the LDS traffic in another, the matrix pipe would idle during the
+        // LDS phase and vice versa.  So the instruction stream is interleaved by hand: after every MFMA
+        // one operand fragment (two transposing reads) of the next chunk is requested, and the staging
+        // writes and the next global loads go in the middle of the MFMA sequence.
+        static_assert(kKS == 2, "the interleaving below is written for two k-steps per chunk");
         for (uint32_t q0 = 0; q0 < total; q0 += 2) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {                // chunk q = q0 + u lives in fragment set u, LDS buffer u
-                read_frags(u ^ 1, (uint32_t)(u ^ 1));
+                const uint32_t nb = (uint32_t)(u ^ 1);
 #pragma unroll
-                for (int ks = 0; ks < kKS; ++ks)
+                for (int i = 0; i < 8; ++i) {            // MFMA i = (ks, mt, nt); fragment i = (ks, A/B, t) of chunk q+1
+                    const int ks = i >> 2, mt = (i >> 1) & 1, nt = i & 1;
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[u][ks][0][mt], F[u][ks][1][nt], acc[mt][nt], 0, 0, 0);
+                    const int fk = i >> 2, fo = (i >> 1) & 1, ft = i & 1;
+                    if (fo == 0) F[u ^ 1][fk][0][ft] = lds_frag_bf16<BM>(shA[nb], fk, wm * 64 + ft * 32, lane);
+                    else F[u ^ 1][fk][1][ft] = lds_frag_bf16<BN>(shB[nb], fk, wn * 64 + ft * 32, lane);
+                    if (i == 3) {
+                        store_chunk<BM, NT>(shA[u], ra[u], tid);  // chunk q+2, then its registers take chunk q+4
+                        store_chunk<BN, NT>(shB[u], rb[u], tid);
+                        issue(u);
+                    }
+                }
 #pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < 2; ++nt)
-                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[u][ks][0][mt], F[u][ks][1][nt], acc[mt][nt], 0, 0, 0);
-                // keep the MFMAs ahead of the wait for the global loads: they run in the matrix pipe while
-                // the wave waits, stages and issues the next loads
-                __builtin_amdgcn_sched_barrier(0);
-                store_chunk<BM, NT>(shA[u], ra[u], tid);  // chunk q+2, then its registers take chunk q+4
-                store_chunk<BN, NT>(shB[u], rb[u], tid);
-                issue(u);
+                for (int i = 0; i < 8; ++i) {            // pin the order above for the instruction scheduler
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);      // two LDS reads
+                    if (i == 3) {
+                        __builtin_amdgcn_sched_group_barrier(0x200, kKC * (BM + BN) / 8 / NT, 0);   // the LDS writes
+                        __builtin_amdgcn_sched_group_barrier(0x020, kKC * (BM + BN) / 8 / NT, 0);   // the global loads
+                    }
+                }
                 if (++pc == n_chunks && zdone < z_end) { pc = 0; ++zdone; sample_end(); }
                 __syncthreads();
             }
