@@ -84,6 +84,7 @@ __device__ __forceinline__ void store_chunk(uint16_t* tile, const ChunkRegs<TW, 
     }
 }
 
+
 // BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.
 template <int BM, int BN, bool kWantG>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
@@ -377,3 +378,4 @@ int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint3
 }
 
 }  // namespace vgc
+
