@@ -24,11 +24,14 @@ int hip_check(hipError_t e, const char* what) {
 }
 
 // Validates the group list and counts tiles.  Returns a vgc_status.
+struct GroupStats { uint64_t n_runs; uint32_t n_segs; bool multi_seg; };
+
 static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, uint64_t* n_tiles_out,
-                        uint64_t* n_runs_out = nullptr) {
+                        GroupStats* stats_out = nullptr) {
     if (!groups) { set_error("groups is NULL"); return VGC_ERR_NULL; }
     if (n == 0 || n_groups == 0) { set_error("n and n_groups must be positive"); return VGC_ERR_SIZE; }
-    uint64_t off = 0, tiles = 0, runs = 0;
+    uint64_t off = 0, tiles = 0, runs = 0, segs = 0;
+    bool multi = false;
     for (uint32_t k = 0; k < n_groups; ++k) {
         if (groups[k].size == 0) { set_error("group %u is empty", k); return VGC_ERR_SIZE; }
         if (groups[k].size > VGC_MAX_GROUP_SIZE) {
@@ -44,6 +47,8 @@ static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, 
         const uint64_t nt = (groups[k].size + kTile - 1) / kTile;
         tiles += nt;
         runs += (nt + kRunTiles - 1) / kRunTiles;
+        segs += (nt + kSegTiles - 1) / kSegTiles;
+        multi = multi || nt > kSegTiles;
     }
     if (off != n) {
         set_error("groups cover %llu elements, n = %llu", (unsigned long long)off, (unsigned long long)n);
@@ -51,14 +56,14 @@ static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, 
     }
     if (tiles > 0x7FFFFFFFull) { set_error("too many tiles (%llu)", (unsigned long long)tiles); return VGC_ERR_SIZE; }
     if (n_tiles_out) *n_tiles_out = tiles;
-    if (n_runs_out) *n_runs_out = runs;
+    if (stats_out) { stats_out->n_runs = runs; stats_out->n_segs = (uint32_t)segs; stats_out->multi_seg = multi; }
     return VGC_OK;
 }
 
-// The run table sits after the tile table; its size is bounded by the tile count, so the layout
-// reserves one PlanRun slot per tile and the offsets depend on (n_tiles, n_groups) only.
+// The run and segment tables sit after the tile table; their sizes are bounded through the tile and
+// group counts, so the layout reserves the bound and the offsets depend on (n_tiles, n_groups) only.
 static size_t plan_bytes_for(uint64_t n_tiles, uint32_t n_groups, size_t* groups_off, size_t* tiles_off,
-                             size_t* runs_off = nullptr) {
+                             size_t* runs_off = nullptr, size_t* segs_off = nullptr) {
     size_t off = sizeof(PlanHeader);
     if (groups_off) *groups_off = off;
     off = align_up(off + (size_t)n_groups * sizeof(PlanGroup), 256);
@@ -66,19 +71,21 @@ static size_t plan_bytes_for(uint64_t n_tiles, uint32_t n_groups, size_t* groups
     off = align_up(off + n_tiles * sizeof(PlanTile), 256);
     if (runs_off) *runs_off = off;
     off = align_up(off + (n_tiles / kRunTiles + n_groups) * sizeof(PlanRun), 256);
+    if (segs_off) *segs_off = off;
+    off = align_up(off + (n_tiles / kSegTiles + n_groups) * sizeof(PlanSeg), 256);
     return off;
 }
 
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-struct PlanView { const PlanGroup* groups; const PlanTile* tiles; const PlanRun* runs; };
+struct PlanView { const PlanGroup* groups; const PlanTile* tiles; const PlanRun* runs; const PlanSeg* segs; };
 
 static PlanView plan_view(const void* plan_dev, uint64_t n_tiles, uint32_t n_groups) {
-    size_t go, to, ro;
-    plan_bytes_for(n_tiles, n_groups, &go, &to, &ro);
+    size_t go, to, ro, so;
+    plan_bytes_for(n_tiles, n_groups, &go, &to, &ro, &so);
     const char* b = static_cast<const char*>(plan_dev);
     return PlanView{reinterpret_cast<const PlanGroup*>(b + go), reinterpret_cast<const PlanTile*>(b + to),
-                    reinterpret_cast<const PlanRun*>(b + ro)};
+                    reinterpret_cast<const PlanRun*>(b + ro), reinterpret_cast<const PlanSeg*>(b + so)};
 }
 
 }  // namespace vgc
@@ -115,27 +122,37 @@ size_t vgc_scratch_bitmap_offset(const vgc_group* groups, uint32_t n_groups, uin
 }
 
 int vgc_plan_build(const vgc_group* groups, uint32_t n_groups, uint64_t n, void* plan_host, size_t plan_bytes) {
-    uint64_t n_tiles = 0, n_runs = 0;
-    int rc = check_groups(groups, n_groups, n, &n_tiles, &n_runs);
+    uint64_t n_tiles = 0;
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
     if (rc != VGC_OK) return rc;
     if (!plan_host) { set_error("plan_host is NULL"); return VGC_ERR_NULL; }
-    size_t go, to, ro;
-    const size_t need = plan_bytes_for(n_tiles, n_groups, &go, &to, &ro);
+    size_t go, to, ro, so;
+    const size_t need = plan_bytes_for(n_tiles, n_groups, &go, &to, &ro, &so);
     if (plan_bytes < need) { set_error("plan buffer has %zu bytes, %zu needed", plan_bytes, need); return VGC_ERR_SIZE; }
     char* b = static_cast<char*>(plan_host);
     memset(b, 0, need);
     PlanHeader* h = reinterpret_cast<PlanHeader*>(b);
     h->magic = kPlanMagic; h->n = n; h->n_tiles = n_tiles; h->n_groups = n_groups; h->tile = kTile;
-    h->groups_off = go; h->tiles_off = to; h->runs_off = ro; h->n_runs = n_runs;
+    h->groups_off = go; h->tiles_off = to; h->runs_off = ro; h->n_runs = gs.n_runs;
+    h->segs_off = so; h->n_segs = gs.n_segs;
     PlanGroup* G = reinterpret_cast<PlanGroup*>(b + go);
     PlanTile* T = reinterpret_cast<PlanTile*>(b + to);
     PlanRun* R = reinterpret_cast<PlanRun*>(b + ro);
+    PlanSeg* S = reinterpret_cast<PlanSeg*>(b + so);
     uint64_t t = 0, rn = 0;
+    uint32_t sn = 0;
     for (uint32_t k = 0; k < n_groups; ++k) {
         G[k].offset = groups[k].offset; G[k].size = groups[k].size; G[k].first_tile = (uint32_t)t;
+        const uint32_t group_first_seg = sn;
         uint32_t in_group = 0;
         for (uint64_t start = 0; start < groups[k].size; start += kTile, ++t, ++in_group) {
-            T[t].group = k; T[t].start = (uint32_t)start;
+            if (in_group % kSegTiles == 0) {
+                S[sn].group = k; S[sn].first_tile = in_group; S[sn].seg_in_group = sn - group_first_seg;
+                S[sn].group_first_seg = group_first_seg;
+                ++sn;
+            }
+            T[t].group = k; T[t].start = (uint32_t)start; T[t].seg = sn - 1;
             if (in_group % kRunTiles == 0) { R[rn].group = k; R[rn].first_tile = in_group; ++rn; }
         }
     }
@@ -213,7 +230,8 @@ int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void*
         return VGC_ERR_NULL;
     }
     uint64_t n_tiles = 0;
-    int rc = check_groups(groups, n_groups, n, &n_tiles);
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
     if (rc != VGC_OK) return rc;
     if (!aligned(plan, 256) || !aligned(scratch, 256) || !aligned(words_out, 4) || !aligned(hdrs_out, 8) || !aligned(status_out, 8)) {
         set_error("vgc_pack: misaligned pointer");
@@ -222,9 +240,9 @@ int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void*
     const ScratchLayout L = scratch_layout(n_tiles, n_groups);
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
     char* sc = static_cast<char*>(scratch);
-    return launch_pack(pv.groups, pv.tiles, n_tiles, n_groups,
+    return launch_pack(pv.groups, pv.tiles, pv.segs, n_tiles, n_groups, gs.n_segs, gs.multi_seg,
                        reinterpret_cast<TileHdr*>(sc + L.tile_hdr_off),
-                       reinterpret_cast<GroupTmp*>(sc + L.group_tmp_off),
+                       reinterpret_cast<SegTmp*>(sc + L.seg_tmp_off),
                        reinterpret_cast<const uint16_t*>(sc + L.staging_off),
                        words_out, words_cap, hdrs_out, status_out, static_cast<hipStream_t>(stream));
 }
@@ -249,8 +267,9 @@ int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, 
                          uint32_t p, const vgc_group* groups, uint32_t n_groups, const void* plan,
                          float scale, int overwrite, float* dense_out, uint64_t n, void* stream) {
     if (!plan || !dense_out || (p && (!words || !n_words || !hdrs))) { set_error("vgc_unpack_add_batch: NULL pointer"); return VGC_ERR_NULL; }
-    uint64_t n_tiles = 0, n_runs = 0;
-    int rc = check_groups(groups, n_groups, n, &n_tiles, &n_runs);
+    uint64_t n_tiles = 0;
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
     if (rc != VGC_OK) return rc;
     for (uint32_t w = 0; w < p; ++w) {
         if (!hdrs[w] || (!words[w] && n_words[w])) { set_error("vgc_unpack_add_batch: message %u has a NULL pointer", w); return VGC_ERR_NULL; }
@@ -260,7 +279,7 @@ int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, 
     if (!std::isfinite(scale)) { set_error("vgc_unpack_add_batch: scale is not finite"); return VGC_ERR_PARAM; }
     if (p == 0 && !overwrite) return VGC_OK;
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
-    return launch_unpack_add_batch(words, n_words, hdrs, p, pv.groups, pv.runs, n_runs, scale, overwrite, dense_out,
+    return launch_unpack_add_batch(words, n_words, hdrs, p, pv.groups, pv.runs, gs.n_runs, scale, overwrite, dense_out,
                                    static_cast<hipStream_t>(stream));
 }
 

@@ -18,9 +18,9 @@ constexpr uint32_t kThreads = 256;
 constexpr uint32_t kElemsPerThread = kTile / kThreads;   // 8
 constexpr uint32_t kRelBins = 9;                          // staged exponent codes 0..8 (see StagedEntry)
 
-constexpr uint64_t kPlanMagic = 0x31304E414C504756ull;    // "VGPLAN01"
+constexpr uint64_t kPlanMagic = 0x32304E414C504756ull;    // "VGPLAN02"
 
-struct PlanHeader {            // 64 bytes at the start of the plan blob
+struct PlanHeader {            // 128 bytes at the start of the plan blob
     uint64_t magic;
     uint64_t n;
     uint64_t n_tiles;
@@ -30,6 +30,9 @@ struct PlanHeader {            // 64 bytes at the start of the plan blob
     uint64_t tiles_off;        // byte offset of PlanTile[n_tiles]
     uint64_t runs_off;         // byte offset of PlanRun[n_runs]
     uint64_t n_runs;
+    uint64_t segs_off;         // byte offset of PlanSeg[n_segs]
+    uint64_t n_segs;
+    uint64_t reserved[6];
 };
 
 struct PlanGroup {             // 16 bytes
@@ -38,9 +41,21 @@ struct PlanGroup {             // 16 bytes
     uint32_t first_tile;       // would overflow only beyond 2^43 parameters
 };
 
-struct PlanTile {              // 8 bytes
+struct PlanTile {              // 16 bytes
     uint32_t group;
     uint32_t start;            // element offset of the tile inside its group (multiple of kTile)
+    uint32_t seg;              // index of the tile's segment in the segment table
+    uint32_t reserved;
+};
+
+// A segment is up to kSegTiles consecutive tiles of one group: the unit one workgroup of the scan
+// kernel owns (8 tile records per thread, one pass).  A group of 2^28 elements has 16 of them.
+constexpr uint32_t kSegTiles = 8192;
+struct PlanSeg {               // 16 bytes
+    uint32_t group;
+    uint32_t first_tile;       // index of the segment's first tile inside its group
+    uint32_t seg_in_group;
+    uint32_t group_first_seg;  // index of the group's first segment in the table
 };
 
 // A run is up to kRunTiles consecutive tiles of one group: the unit one wave of the batched
@@ -55,7 +70,7 @@ struct PlanRun {               // 8 bytes
 // the first pack kernel (w[5..7]).
 //   w[0..3]  : hist[0..7], two 16-bit counters per word (low half = even bin)
 //   w[4]     : low half hist[8]; high half = largest truncated exponent field among the tile's sent elements
-//   w[5]     : number of words the group's earlier tiles produce (exclusive prefix inside the group)
+//   w[5]     : number of words the segment's earlier tiles produce (exclusive prefix inside the segment)
 //   w[6]     : shift = E_k - tile exponent
 //   w[7]     : words this tile produces
 struct TileHdr { uint32_t w[8]; };
@@ -65,12 +80,19 @@ struct TileHdr { uint32_t w[8]; };
 // With shift = E_k - tile exponent the final code is d = max(shift + rel - 1, 0)
 // and the element is encoded iff rel <= 8 - shift.
 
-struct GroupTmp { uint32_t exp_field; uint32_t count; };
+struct SegTmp {                // 32 bytes, one per segment
+    uint32_t max_e;            // largest tile exponent inside the segment (written only for groups of several segments)
+    uint32_t exp_field;        // E_k of the segment's group
+    uint32_t count;            // words the segment produces
+    uint32_t reserved;
+    uint64_t base;             // position of the segment's first word in the message
+    uint64_t reserved2;
+};
 
 struct ScratchLayout {
     uint64_t n_tiles;
     size_t tile_hdr_off;       // TileHdr[n_tiles]
-    size_t group_tmp_off;      // GroupTmp[n_groups]
+    size_t seg_tmp_off;        // SegTmp[n_segs], sized for the bound n_tiles / kSegTiles + n_groups
     size_t bitmap_off;         // uint32[n_tiles * kTile / 32]
     size_t staging_off;        // uint16[n_tiles * kTile]
     size_t total;
@@ -83,7 +105,7 @@ inline ScratchLayout scratch_layout(uint64_t n_tiles, uint32_t n_groups) {
     L.n_tiles = n_tiles;
     size_t off = 0;
     L.tile_hdr_off = off;  off = align_up(off + n_tiles * sizeof(TileHdr), 256);
-    L.group_tmp_off = off; off = align_up(off + (size_t)n_groups * sizeof(GroupTmp), 256);
+    L.seg_tmp_off = off;   off = align_up(off + (size_t)(n_tiles / kSegTiles + n_groups) * sizeof(SegTmp), 256);
     L.bitmap_off = off;    off = align_up(off + n_tiles * (kTile / 8), 256);
     L.staging_off = off;   off = align_up(off + n_tiles * (size_t)kTile * 2, 256);
     L.total = off;
@@ -101,8 +123,9 @@ int launch_accumulate_select(const float* g, const float* s, float* r, float* v,
                              float alpha, float zeta, float tau, bool hybrid, bool ptrs_vec_aligned,
                              hipStream_t stream);
 
-int launch_pack(const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles, uint32_t n_groups,
-                TileHdr* hdrs, GroupTmp* gtmp, const uint16_t* staging,
+int launch_pack(const PlanGroup* groups, const PlanTile* tiles, const PlanSeg* segs, uint64_t n_tiles,
+                uint32_t n_groups, uint32_t n_segs, bool multi_seg,
+                TileHdr* hdrs, SegTmp* stmp, const uint16_t* staging,
                 uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
                 vgc_pack_status* status_out, hipStream_t stream);
 

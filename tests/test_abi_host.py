@@ -41,7 +41,8 @@ def test_plan_build_tiles_never_span_groups():
     lib = vgc.load()
     T = lib.vgc_tile_size()
     assert T == 2048
-    sizes = [1, T, T + 1, 5 * T - 3, 10]
+    S = 8192                                   # tiles per scan segment
+    sizes = [1, T, T + 1, 5 * T - 3, 10, 2 * S * T + 7, S * T]
     arr, n = _groups(sizes)
     n_tiles = lib.vgc_tile_count(arr, len(sizes), n)
     assert n_tiles == sum((s + T - 1) // T for s in sizes)
@@ -52,7 +53,12 @@ def test_plan_build_tiles_never_span_groups():
     assert hdr[1] == n and hdr[2] == n_tiles
     groups_off, tiles_off = int(buf[32:40].view("<u8")[0]), int(buf[40:48].view("<u8")[0])
     G = buf[groups_off:groups_off + 16 * len(sizes)].view(np.dtype([("offset", "<u8"), ("size", "<u4"), ("first", "<u4")]))
-    Tt = buf[tiles_off:tiles_off + 8 * n_tiles].view(np.dtype([("group", "<u4"), ("start", "<u4")]))
+    Tt = buf[tiles_off:tiles_off + 16 * n_tiles].view(
+        np.dtype([("group", "<u4"), ("start", "<u4"), ("seg", "<u4"), ("reserved", "<u4")]))
+    segs_off, n_segs = int(buf[64:72].view("<u8")[0]), int(buf[72:80].view("<u8")[0])
+    assert n_segs == sum(((s + T - 1) // T + S - 1) // S for s in sizes) == len(sizes) + 2
+    Sg = buf[segs_off:segs_off + 16 * n_segs].view(
+        np.dtype([("group", "<u4"), ("first_tile", "<u4"), ("seg_in_group", "<u4"), ("group_first_seg", "<u4")]))
     covered = np.zeros(n, np.int32)
     for t in range(n_tiles):
         k, start = int(Tt[t]["group"]), int(Tt[t]["start"])
@@ -61,6 +67,11 @@ def test_plan_build_tiles_never_span_groups():
         covered[lo:lo + min(T, sizes[k] - start)] += 1
         if start == 0:
             assert int(G[k]["first"]) == t
+        sg = Sg[int(Tt[t]["seg"])]
+        in_group = start // T
+        assert int(sg["group"]) == k and int(sg["first_tile"]) == in_group // S * S
+        assert int(sg["seg_in_group"]) == in_group // S
+        assert int(sg["group_first_seg"]) == int(Tt[t]["seg"]) - in_group // S
     assert np.all(covered == 1)
     assert lib.vgc_plan_build(arr, len(sizes), n, buf.ctypes.data, nbytes - 1) == -2
     assert lib.vgc_scratch_bytes(arr, len(sizes), n) >= n_tiles * (32 + T // 8 + 2 * T)

@@ -118,6 +118,30 @@ def test_wide_dynamic_range_exercises_shift_and_drop(dev):
     assert set(np.unique(d).tolist()) == set(range(8))
 
 
+def test_group_of_several_scan_segments(dev):
+    """A group larger than one scan segment (8192 tiles): E_k comes from the last segment, the first
+    segment lies partly below 2^(E_k-7) and the middle one wholly, so segment totals of zero, the
+    segment bases and the shift all matter; a one-tile group before and after."""
+    S = 8192 * 2048
+    sizes = [700, 2 * S + 3 * 2048 + 5, 2048]
+    groups = W.groups_from_sizes(sizes)
+    n = sum(sizes)
+    rng = np.random.default_rng(21)
+    g = rng.standard_normal(n, dtype=F32)
+    scale = np.ones(n, F32)
+    scale[700:700 + S] = 2.0 ** -6
+    scale[700 + S:700 + 2 * S] = 2.0 ** -14
+    g *= scale
+    g[700 + 2 * S + 4000] = 3.0                                # group maximum in the short last segment
+    s = (g.astype(np.float64) ** 2 * rng.uniform(0.2, 3.0, n)).astype(F32)
+    del scale
+    z = np.zeros(n, F32)
+    gw = GpuWorker(groups, dev)
+    r_out, v_out, send, words, hdrs = _compare_step(gw, g, s, z, z, groups, 1.0, 0.999, dev)
+    idx = (words[hdrs[1][2]:hdrs[1][2] + hdrs[1][1]] & U32(0x0FFFFFFF)).astype(np.int64)
+    assert hdrs[1][1] > 0 and (idx < S).any() and not ((idx >= S) & (idx < 2 * S)).any() and (idx >= 2 * S).any()
+
+
 def test_alpha_extremes_and_ties(dev):
     sizes = [3000, 5000]
     groups = W.groups_from_sizes(sizes)
