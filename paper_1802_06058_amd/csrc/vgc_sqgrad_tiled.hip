@@ -1,20 +1,29 @@
 // LDS-tiled MFMA kernels for the per-parameter sums of Alg. 1 (g = c sum_z G_z, s = c^2 sum_z G_z.G_z,
 // G_z the gradient of sample z's loss, Section 4.1), shared-weight form: G_z = U_z^T D_z with K = P.
 //
-// A workgroup (4 waves, 2 x 2) owns a 128 x 128 tile of [J, C] and a range of samples.  For every
-// sample it runs the K loop over the P positions in chunks of 32 rows staged through LDS (double
-// buffered, one barrier per chunk), keeping the per-sample product in MFMA accumulators; when the
-// sample is finished the accumulators are squared into s (and added into g) and cleared, so a
-// per-sample gradient never leaves registers.  The sample range can be split over blockIdx.z to fill
-// the chip when [J, C] has few tiles; the partial sums then go to a workspace and are added in fixed
-// order by k_sqgrad_reduce.
+// A workgroup owns a BM x BN tile of [J, C] (one wave per 64 x 64 sub-tile) and a range of samples.
+// For every sample it runs the K loop over the P positions in chunks of 32 rows, keeping the
+// per-sample product in MFMA accumulators; when the sample is finished the accumulators are squared
+// into s (and added into g) and cleared, so a per-sample gradient never leaves registers.  The sample
+// range can be split over workgroups to fill the chip when [J, C] has few tiles; the partial sums then
+// go to a workspace and are added in fixed order by k_sqgrad_reduce.
 //
-// bf16 path: v_mfma_f32_32x32x16_bf16.  Lane l of that instruction holds, for row m = l % 32, the 8
+// Chunks travel from global memory straight into LDS (buffer loads with the LDS modifier: lane l of a
+// wave-wide load deposits its 16 bytes at M0 + 16 l), several chunks ahead of the one being multiplied,
+// in a ring of LDS buffers.  No staging registers, no LDS store instructions; the distance covers the
+// HBM latency of the lines a workgroup is the first in its L2 to touch.
+//
+// bf16 operands: v_mfma_f32_32x32x16_bf16.  Lane l of that instruction holds, for row m = l % 32, the 8
 // consecutive k = 8 * (l / 32) .. + 7.  Memory has the other order (k-major rows, m contiguous), so
 // the operands are fetched with the LDS transposing read ds_read_b64_tr_b16: within 16 lanes, lane r
 // supplies the address of 4 consecutive b16 and lane i receives element i % 4 from the addresses of
 // lanes i / 4 + 4 j, j = 0..3.  With lane r pointing at row k0 + r / 4, columns m0 + 4 (r % 4) .. + 3,
 // lane i receives k0 .. k0 + 3 for column m0 + i.
+//
+// A staged row is W * 2 bytes with no padding (a wave-wide load fills 1 KiB of consecutive LDS), so
+// rows k0 .. k0+3 of one 64-byte column unit would share banks.  The unit index is therefore XORed
+// with a function of the row (swizzle) on the way in, by choosing which global piece each lane
+// fetches, and on the way out in the fragment addresses.
 #include "vgc_internal.h"
 
 namespace vgc {
@@ -23,67 +32,59 @@ typedef short s4v __attribute__((ext_vector_type(4)));
 typedef short s8v __attribute__((ext_vector_type(8)));
 typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
-typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+typedef int i4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s4v* lds_s4v_ptr;
 
-#ifndef VGC_CONV_KC
-#define VGC_CONV_KC 32
-#endif
-constexpr int kKC = VGC_CONV_KC;         // positions per LDS stage
+constexpr int kKC = 32;                  // positions per LDS stage
 
-// Row pitch (bf16 elements) of a staged tile of width W: W + 32, i.e. consecutive rows start 16 banks
-// apart, so the 4 rows x 2 column halves one half-wave reads with a transposing load fall on distinct banks.
-template <int W> struct Pitch { static constexpr int value = W + 32; };
-
-template <int W>
-__device__ __forceinline__ bf8v lds_frag_bf16(const uint16_t* tile, int ks, int mbase, uint32_t lane) {
-    constexpr int kPitch = Pitch<W>::value;
-    const uint32_t r = lane & 15u, grp = lane >> 4;
-    const uint32_t mhalf = grp & 1u, khalf = grp >> 1;
-    const uint16_t* p = tile + (ks * 16 + khalf * 8 + (r >> 2)) * kPitch + mbase + mhalf * 16 + 4 * (r & 3u);
-    const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p));
-    const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p + 4 * kPitch));
-    s8v v;
-    v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
-    v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
-    return __builtin_bit_cast(bf8v, v);
+// XOR mask applied to the 64-byte unit index of row `row` in a staged tile W elements wide.  Four
+// consecutive rows (row % 4 = 0..3) of one unit then start 16 banks apart.
+template <int W> __device__ __forceinline__ uint32_t swizzle(uint32_t row) {
+    return W >= 128 ? (row & 3u) : ((row >> 1) & 1u);
 }
 
-// One staged chunk of an operand: rows p0 .. p0+31 of a [P, W] bf16 matrix, columns w0 .. w0+TW-1,
-// moved by NT threads in 16-byte pieces.
-template <int TW, int NT> struct ChunkRegs { u4v v[kKC * TW / 8 / NT]; };
-
-// Buffer loads with the sample's [P, W] matrix as the bounded range: rows past P fall outside the range
-// and read as zero in hardware, so there is no branch around a load and the compiler can count the
-// outstanding loads exactly (it waits only for the register set about to be staged).  Columns past W
-// wrap into the next row; they only feed outputs that are never stored.
-typedef __amdgpu_buffer_rsrc_t rsrc_t;
-
-__device__ __forceinline__ rsrc_t sample_rsrc(const uint16_t* base, uint32_t bytes) {
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(base), 0, (int)bytes, 0x00020000);
+// One 16-byte piece per lane from the bounded buffer `rsrc` (byte offset voff) to LDS byte address
+// lds_addr + 16 * lane.  Lanes outside the range deposit zeros.  Counted by vmcnt.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"          // m0 is named as clobbered on purpose
+__device__ __forceinline__ void load_to_lds(uint32_t lds_addr, uint32_t voff, i4v rsrc) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+template <int N> __device__ __forceinline__ void wait_loads_but() {
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-template <int TW, int NT>
-__device__ __forceinline__ void load_chunk(ChunkRegs<TW, NT>& R, rsrc_t rs, uint32_t W, uint32_t p0, uint32_t w0, uint32_t tid) {
-    constexpr int kPer = kKC * TW / 8 / NT, kCols = TW / 8;
-#pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-        const uint32_t idx = tid + (uint32_t)NT * i, row = idx / kCols, col = w0 + (idx % kCols) * 8u;
-        const uint32_t off = ((p0 + row) * W + col) * 2u;
-        R.v[i] = __builtin_bit_cast(u4v, __builtin_amdgcn_raw_buffer_load_b128(rs, (int)off, 0, 0));
+// Scalar cursor over the chunks of one operand ([B, P, W] bf16): the buffer descriptor covers the rest
+// of the current sample from the chunk's first row on, so rows past P read as zeros.
+struct ChunkStream {
+    uint64_t sample;        // address of the current sample's matrix
+    uint64_t cur;           // address of the chunk's first row
+    uint32_t rem;           // bytes from there to the end of the sample
+    uint32_t chunk_bytes, sample_bytes;
+    __device__ __forceinline__ void init(const uint16_t* base, uint32_t z, uint32_t P, uint32_t W) {
+        chunk_bytes = kKC * W * 2u;
+        sample_bytes = P * W * 2u;
+        sample = reinterpret_cast<uint64_t>(base) + (uint64_t)z * sample_bytes;
+        cur = sample;
+        rem = sample_bytes;
     }
-}
-
-template <int TW, int NT>
-__device__ __forceinline__ void store_chunk(uint16_t* tile, const ChunkRegs<TW, NT>& R, uint32_t tid) {
-    constexpr int kPer = kKC * TW / 8 / NT, kCols = TW / 8, kPitch = Pitch<TW>::value;
-#pragma unroll
-    for (int i = 0; i < kPer; ++i) {
-        const uint32_t idx = tid + (uint32_t)NT * i, row = idx / kCols, col = (idx % kCols) * 8u;
-        *reinterpret_cast<u4v*>(tile + row * kPitch + col) = R.v[i];
+    __device__ __forceinline__ i4v rsrc(bool live) const {
+        i4v r;
+        r[0] = (int)(uint32_t)cur;
+        r[1] = (int)((uint32_t)(cur >> 32) & 0xFFFFu);
+        r[2] = live ? (int)rem : 0;
+        r[3] = 0x00020000;
+        return r;
     }
-}
-
+    __device__ __forceinline__ void next(bool new_sample) {
+        const uint64_t following = sample + sample_bytes;    // selects, not branches: the loop body stays one block
+        sample = new_sample ? following : sample;
+        cur = new_sample ? following : cur + chunk_bytes;
+        rem = new_sample ? sample_bytes : rem - chunk_bytes;
+    }
+};
 
 // BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.
 template <int BM, int BN, bool kWantG>
@@ -92,12 +93,21 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                  uint32_t B, uint32_t P, uint32_t J, uint32_t C,
                  uint32_t z_per_split, uint32_t splits, float cg, float cs,
                  float* __restrict__ g_out, float* __restrict__ s_out, float* __restrict__ ws) {
-    constexpr int NT = (BM / 64) * (BN / 64) * 64;
-    constexpr int kPA = Pitch<BM>::value, kPB = Pitch<BN>::value;
-    __shared__ __attribute__((aligned(16))) uint16_t shA[2][kKC * kPA];
-    __shared__ __attribute__((aligned(16))) uint16_t shB[2][kKC * kPB];
+    constexpr int NW = (BM / 64) * (BN / 64);
+    constexpr int kABytes = kKC * BM * 2, kBBytes = kKC * BN * 2, kBufBytes = kABytes + kBBytes;
+    // ring of staged chunks = chunks in flight: as many as fit beside the other workgroups of the CU (at
+    // most 6), the CU holding 8 waves of this kernel
+    constexpr int kLdsBudget = 160 * 1024 / (8 / NW) - 1024;
+    constexpr int kNB = kLdsBudget / kBufBytes < 6 ? kLdsBudget / kBufBytes : 6;
+    static_assert(kNB >= 3, "the ring needs three buffers");
+    constexpr int kInstrA = kABytes / 1024, kInstrB = kBBytes / 1024;          // wave-wide loads per chunk
+    static_assert(kInstrA % NW == 0 && kInstrB % NW == 0, "every wave issues the same number of loads per chunk");
+    constexpr int kPerA = kInstrA / NW, kPerB = kInstrB / NW, kPer = kPerA + kPerB;
+    constexpr int kRingBytes = kNB * kBufBytes;
+    __shared__ __attribute__((aligned(1024))) uint8_t sh[kRingBytes + 1024];
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const uint32_t wm = wave / (BN / 64), wn = wave % (BN / 64);
     // Workgroups are dealt to the 8 XCDs round-robin by linear id.  Give every XCD a contiguous range
     // of (split, row tile, column tile) so that the workgroups sharing a sample range and a row tile
@@ -113,6 +123,54 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     const uint32_t n_chunks = (P + kKC - 1) / kKC;
     const uint32_t total = (z_end - z_begin) * n_chunks;
 
+    // the compiler must see a store to the array: everything else arrives behind its back
+    reinterpret_cast<uint32_t*>(sh + kRingBytes)[tid & 255u] = 0u;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)sh;
+
+    // ---- global side: which piece each lane fetches, per wave-wide load ----
+    // Load ii of an operand covers rows ii * rpi .. + rpi - 1 of the chunk (1 KiB of the staged tile);
+    // lane l lands on row ii * rpi + l / npr, physical piece l % npr.
+    uint32_t voffA[kPerA], voffB[kPerB];
+#pragma unroll
+    for (int j = 0; j < kPerA; ++j) {
+        constexpr uint32_t npr = BM / 8, rpi = 64 / npr;
+        const uint32_t ii = wave + (uint32_t)NW * j, row = ii * rpi + lane / npr, p = lane % npr;
+        const uint32_t piece = (((p >> 2) ^ swizzle<BM>(row)) << 2) | (p & 3u);
+        voffA[j] = (row * J + j0 + piece * 8u) * 2u;
+    }
+#pragma unroll
+    for (int j = 0; j < kPerB; ++j) {
+        constexpr uint32_t npr = BN / 8, rpi = 64 / npr;
+        const uint32_t ii = wave + (uint32_t)NW * j, row = ii * rpi + lane / npr, p = lane % npr;
+        const uint32_t piece = (((p >> 2) ^ swizzle<BN>(row)) << 2) | (p & 3u);
+        voffB[j] = (row * C + c0 + piece * 8u) * 2u;
+    }
+
+    // ---- LDS side: fragment addresses (bytes inside a buffer) for the two 32-wide tiles of each operand ----
+    const uint32_t r = lane & 15u, grp = lane >> 4, mhalf = grp & 1u, khalf = grp >> 1;
+    const uint32_t frow = khalf * 8u + (r >> 2);
+    uint32_t fA[2], fB[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        fA[t] = frow * (BM * 2u) + (((wm * 2u + t) ^ swizzle<BM>(frow)) * 64u) + mhalf * 32u + (r & 3u) * 8u;
+        fB[t] = kABytes + frow * (BN * 2u) + (((wn * 2u + t) ^ swizzle<BN>(frow)) * 64u) + mhalf * 32u + (r & 3u) * 8u;
+    }
+    // fragment (ks, t) of the chunk staged at byte offset `bo`: rows ks * 16 + {0, 4} keep row % 4 and (row / 2) % 2
+    auto frag_a = [&](uint32_t bo, int ks, int t) -> bf8v {
+        const uint8_t* p = sh + bo + fA[t] + ks * 16 * BM * 2;
+        const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p));
+        const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p + 4 * BM * 2));
+        s8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf8v, v);
+    };
+    auto frag_b = [&](uint32_t bo, int ks, int t) -> bf8v {
+        const uint8_t* p = sh + bo + fB[t] + ks * 16 * BN * 2;
+        const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p));
+        const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p + 4 * BN * 2));
+        s8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf8v, v);
+    };
+
     f16v acc[2][2], s_acc[2][2], g_acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
@@ -123,18 +181,25 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             if (kWantG) g_acc[a][b] = (f16v){0};
         }
 
-    constexpr int kDepth = 2;                            // chunks in flight from global memory per thread
-    constexpr int kKS = kKC / 16;                        // MFMA k-steps per chunk
-    ChunkRegs<BM, NT> ra[kDepth];
-    ChunkRegs<BN, NT> rb[kDepth];
-    uint32_t zl = z_begin, pcl = 0, issued = 0;          // cursor of the next chunk to request from global memory
-    auto issue = [&](int slot_) {                       // past the last chunk the range is empty: zeros come back
-        const bool live = issued < total;
-        const uint32_t zz = live ? zl : z_begin, pq = pcl;
-        load_chunk<BM, NT>(ra[slot_], sample_rsrc(U + (size_t)zz * P * J, live ? P * J * 2u : 0u), J, pq * kKC, j0, tid);
-        load_chunk<BN, NT>(rb[slot_], sample_rsrc(D + (size_t)zz * P * C, live ? P * C * 2u : 0u), C, pq * kKC, c0, tid);
-        if (++pcl == n_chunks) { pcl = 0; ++zl; }
+    // ---- the stream of chunk requests ----
+    ChunkStream sa, sb;
+    sa.init(U, z_begin, P, J);
+    sb.init(D, z_begin, P, C);
+    uint32_t pcl = 0, issued = 0, bo_fill = 0;           // position in the sample, chunks requested, ring buffer (byte offset)
+    auto next_buf = [&](uint32_t bo) -> uint32_t { return bo + kBufBytes == (uint32_t)kRingBytes ? 0u : bo + kBufBytes; };
+    auto issue = [&]() {                                 // request the next chunk into the next ring buffer
+        const bool live = issued < total;                // past the last chunk the range is empty: zeros arrive
+        const i4v ra = sa.rsrc(live), rb = sb.rsrc(live);
+#pragma unroll
+        for (int j = 0; j < kPerA; ++j) load_to_lds(lds0 + bo_fill + (wave + (uint32_t)NW * j) * 1024u, voffA[j], ra);
+#pragma unroll
+        for (int j = 0; j < kPerB; ++j) load_to_lds(lds0 + bo_fill + kABytes + (wave + (uint32_t)NW * j) * 1024u, voffB[j], rb);
         ++issued;
+        const bool wrap = (++pcl == n_chunks);
+        if (wrap) pcl = 0;
+        sa.next(wrap);
+        sb.next(wrap);
+        bo_fill = next_buf(bo_fill);
     };
     auto sample_end = [&]() {                            // G_z is complete in acc: square into s, add into g, clear
 #pragma unroll
@@ -144,110 +209,89 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const float x = acc[mt][nt][i];
-                    s_acc[mt][nt][i] += x * x;
+                    s_acc[mt][nt][i] = __builtin_fmaf(x, x, s_acc[mt][nt][i]);
                     if (kWantG) g_acc[mt][nt][i] += x;
                 }
                 acc[mt][nt] = (f16v){0};
             }
     };
-    // The loop bodies are free of branches around memory operations (the trip count is rounded up to a
-    // multiple of the unroll factor; the surplus chunks are all zeros and add nothing), which keeps the
-    // compiler's count of outstanding loads exact.
+    // Ring: chunk c lives in buffer c % kNB; kNB chunks are requested up front and one more per iteration,
+    // into the buffer of the chunk just consumed.  A wave's loads complete in order, so once all but the
+    // loads of its last kNB - 2 requests are back, its pieces of the chunk needed next are in LDS.  The trip
+    // count of the pipelined loop is rounded up to a multiple of its unroll factor; the surplus chunks are
+    // all zeros and add nothing.
+    constexpr int kInFlight = (kNB - 2) * kPer;
     uint32_t pc = 0, zdone = z_begin;
-
+#pragma unroll 1
+    for (int i = 0; i < kNB; ++i) issue();
+    wait_loads_but<kInFlight>();                         // chunks 0 and 1 have landed
+    __syncthreads();
     if constexpr (!kWantG) {
         // Pipelined across the barrier: the operand fragments of chunk q+1 are read from LDS while the
-        // MFMAs of chunk q run from registers, and chunk q+2 is staged into the buffer chunk q came from.
-        bf8v F[2][kKS][2][2];                            // [ping-pong][k-step][A / B][32-wide tile]
-        auto read_frags = [&](int pp, uint32_t buf) {
+        // MFMAs of chunk q run from registers.
+        bf8v F[2][2][2][2];                              // [ping-pong][k-step][A / B][32-wide tile]
 #pragma unroll
-            for (int ks = 0; ks < kKS; ++ks)
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    F[pp][ks][0][t] = lds_frag_bf16<BM>(shA[buf], ks, wm * 64 + t * 32, lane);
-                    F[pp][ks][1][t] = lds_frag_bf16<BN>(shB[buf], ks, wn * 64 + t * 32, lane);
-                }
-        };
-        issue(0);
-        issue(1);
-        store_chunk<BM, NT>(shA[0], ra[0], tid);
-        store_chunk<BN, NT>(shB[0], rb[0], tid);
-        issue(0);
-        __syncthreads();
-        read_frags(0, 0);
-        store_chunk<BM, NT>(shA[1], ra[1], tid);
-        store_chunk<BN, NT>(shB[1], rb[1], tid);
-        issue(1);
-        __syncthreads();
+            for (int t = 0; t < 2; ++t) {
+                F[0][ks][0][t] = frag_a(0, ks, t);
+                F[0][ks][1][t] = frag_b(0, ks, t);
+            }
+        __syncthreads();                                 // buffer 0 is free
+        uint32_t bo_next = kBufBytes;                    // buffer of chunk q+1
         // A wave issues in order, and the two waves of a SIMD run in lockstep between barriers: if the
         // MFMAs sat in one block and the LDS traffic in another, the matrix pipe would idle during the
         // LDS phase and vice versa.  So the instruction stream is interleaved by hand: after every MFMA
-        // one operand fragment (two transposing reads) of the next chunk is requested, and the staging
-        // writes and the next global loads go in the middle of the MFMA sequence.
-        static_assert(kKS == 2, "the interleaving below is written for two k-steps per chunk");
+        // one operand fragment (two transposing reads) of the next chunk is requested, and the request
+        // for chunk q+kNB goes in the middle of the MFMA sequence.
         for (uint32_t q0 = 0; q0 < total; q0 += 2) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {                // chunk q = q0 + u lives in fragment set u, LDS buffer u
-                const uint32_t nb = (uint32_t)(u ^ 1);
+            for (int u = 0; u < 2; ++u) {                // chunk q = q0 + u lives in fragment set u
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {            // MFMA i = (ks, mt, nt); fragment i = (ks, A/B, t) of chunk q+1
                     const int ks = i >> 2, mt = (i >> 1) & 1, nt = i & 1;
                     acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[u][ks][0][mt], F[u][ks][1][nt], acc[mt][nt], 0, 0, 0);
                     const int fk = i >> 2, fo = (i >> 1) & 1, ft = i & 1;
-                    if (fo == 0) F[u ^ 1][fk][0][ft] = lds_frag_bf16<BM>(shA[nb], fk, wm * 64 + ft * 32, lane);
-                    else F[u ^ 1][fk][1][ft] = lds_frag_bf16<BN>(shB[nb], fk, wn * 64 + ft * 32, lane);
-                    if (i == 3) {
-                        store_chunk<BM, NT>(shA[u], ra[u], tid);  // chunk q+2, then its registers take chunk q+4
-                        store_chunk<BN, NT>(shB[u], rb[u], tid);
-                        issue(u);
-                    }
+                    if (fo == 0) F[u ^ 1][fk][0][ft] = frag_a(bo_next, fk, ft);
+                    else F[u ^ 1][fk][1][ft] = frag_b(bo_next, fk, ft);
+                    if (i == 3) issue();                 // chunk q + kNB into chunk q's buffer
                 }
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {            // pin the order above for the instruction scheduler
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);      // two LDS reads
-                    if (i == 3) {
-                        __builtin_amdgcn_sched_group_barrier(0x200, kKC * (BM + BN) / 8 / NT, 0);   // the LDS writes
-                        __builtin_amdgcn_sched_group_barrier(0x020, kKC * (BM + BN) / 8 / NT, 0);   // the global loads
-                    }
                 }
+                bo_next = next_buf(bo_next);
                 if (++pc == n_chunks && zdone < z_end) { pc = 0; ++zdone; sample_end(); }
+                wait_loads_but<kInFlight>();             // chunk q+2 has landed (this wave's pieces)
                 __syncthreads();
             }
         }
     } else {
-        issue(0);
-        issue(1);
-        store_chunk<BM, NT>(shA[0], ra[0], tid);
-        store_chunk<BN, NT>(shB[0], rb[0], tid);
-        issue(0);
-        __syncthreads();
-        for (uint32_t q0 = 0; q0 < total; q0 += 2) {
+        uint32_t bo_cur = 0;
+        for (uint32_t q = 0; q < total; ++q) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {                // chunk q = q0 + u is in LDS buffer u
+            for (int ks = 0; ks < 2; ++ks) {
+                bf8v fa[2], fb[2];
 #pragma unroll
-                for (int ks = 0; ks < kKS; ++ks) {
-                    bf8v fa[2], fb[2];
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        fa[t] = lds_frag_bf16<BM>(shA[u], ks, wm * 64 + t * 32, lane);
-                        fb[t] = lds_frag_bf16<BN>(shB[u], ks, wn * 64 + t * 32, lane);
-                    }
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                        for (int nt = 0; nt < 2; ++nt)
-                            acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
+                for (int t = 0; t < 2; ++t) {
+                    fa[t] = frag_a(bo_cur, ks, t);
+                    fb[t] = frag_b(bo_cur, ks, t);
                 }
-                __builtin_amdgcn_sched_barrier(0);       // MFMAs issue before the wait for the global loads
-                store_chunk<BM, NT>(shA[u ^ 1], ra[u ^ 1], tid);   // chunk q+1, then its registers take chunk q+3
-                store_chunk<BN, NT>(shB[u ^ 1], rb[u ^ 1], tid);
-                issue(u ^ 1);
-                if (++pc == n_chunks && zdone < z_end) { pc = 0; ++zdone; sample_end(); }
-                __syncthreads();
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int nt = 0; nt < 2; ++nt)
+                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
             }
+            if (++pc == n_chunks) { pc = 0; sample_end(); }
+            bo_cur = next_buf(bo_cur);
+            wait_loads_but<kInFlight>();                 // chunk q+1 has landed (this wave's pieces)
+            __syncthreads();                             // ... everybody's, and chunk q's buffer is free
+            issue();                                     // chunk q + kNB into chunk q's buffer
         }
     }
+    wait_loads_but<0>();                                 // nothing may still be landing when the workgroup ends
 
     // ---- epilogue: scaled result, or unscaled partial sums for the fixed-order reduction ----
     const bool direct = (splits == 1);
