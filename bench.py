@@ -39,6 +39,9 @@ def parse():
                     help="batch: all messages in one pass over the dense buffer; per-message: one launch each")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sqgrad", action="store_true")
+    ap.add_argument("--core-only", action="store_true",
+                    help="only the timed steps of the flat workload (what the kernel-trace summary under profiles/ is taken with: "
+                         "every launch then has the benchmark's size)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 27, help="upper bound on the parameters of the oracle-timed sample")
     return ap.parse_args()
 
@@ -154,6 +157,10 @@ def main():
         },
         "input_generation_s": round(gen_s, 1),
     }
+
+    if a.core_only:
+        print(json.dumps(out))
+        return
 
     # hybrid algorithm (Alg. 2) on worker 0's buffers: same kernels with the threshold rule, tau = 0.05
     r[0].zero_(); v[0].zero_()
