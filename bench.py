@@ -181,6 +181,9 @@ def main():
         "algorithmic_GBs": round((24.0 + 4.0 * hrho) * N / (hy * 1e-3) / 1e9, 1),
         "frac_of_peak": round((24.0 + 4.0 * hrho) * N / (hy * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # the sparse regime, one worker of the flat workload on a fresh state
+    out["stages"]["sparse_regime_fresh_state"] = alpha_sweep(vgc, plan, pool[0][0], pool[0][1], r[0], v[0], zeta, scratch,
+                                                             words[0], hdrs[0], status[0], (8.0, 16.0))
     out["stages"]["model_parameter_sets"] = bench_model_sets(dev, a.alpha, zeta)
     if not a.no_sqgrad:
         out["stages"]["sqgrad"] = bench_sqgrad(dev)
@@ -239,6 +242,31 @@ def bench_model_sets(dev, alpha, zeta):
                      "sent_fraction": round(rho, 4), "Gparams_per_s": round(n / (t * 1e-3) / 1e9, 1),
                      "algorithmic_GBs": round((24 + 4 * rho) * n / (t * 1e-3) / 1e9, 1),
                      "frac_of_peak": round((24 + 4 * rho) * n / (t * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if name == "C4":
+            # the last (g, s) on a fresh state, across alpha: from half of the elements sent down to the
+            # sparse regime the method is meant for
+            res[name]["alpha_sweep_fresh_state"] = alpha_sweep(vgc, plan, g, s, r, v, zeta, scratch, words, hdrs, status,
+                                                               (0.5, 1.0, 2.0, 4.0, 8.0, 16.0))
+    return res
+
+
+def alpha_sweep(vgc, plan, g, s, r, v, zeta, scratch, words, hdrs, status, alphas):
+    """select + pack on state (r, v) = 0 for each alpha (three repetitions, state cleared before each)."""
+    import torch
+    n, res = plan.n, {}
+    for alpha in alphas:
+        ms = []
+        for _ in range(3):
+            r.zero_(); v.zero_()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            vgc.accumulate_select(g, s, r, v, plan, alpha, zeta, scratch)
+            vgc.pack(plan, scratch, words, hdrs, status)
+            e1.record(); torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        t, rho = min(ms[1:]), vgc.read_status(status)[0] / n
+        res[str(alpha)] = {"ms": round(t, 4), "sent_fraction": float(f"{rho:.3g}"),
+                           "frac_of_peak": round((24 + 4 * rho) * n / (t * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     return res
 
 

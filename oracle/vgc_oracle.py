@@ -20,6 +20,9 @@ What is implemented, in the paper's order and notation:
   pack                Encode() of Alg. 1: per weight-matrix group, floor(log2 M_k),
                       4-bit value code and 28-bit index in one 32-bit word (Section 4.2).
   unpack_add          the decode-and-sum half of CommunicateAndUpdate() (Section 4.3).
+  momentum_sgd_step,  the parameter update that follows it (Sections 4.1, 4.3), with the
+  adam_step,          elements nobody sent entering as zero; unpack_apply = decode + one step.
+  unpack_apply
 
 Readings taken where the paper is silent are stated at the function that needs them.
 Every function here is pinned by tests that do not go through this module's own
@@ -357,3 +360,64 @@ def pack_hybrid(sign, send, groups):
         word_offset += int(idx.size)
     words = np.concatenate(words) if words else np.zeros(0, dtype=U32)
     return words, headers
+
+
+# --------------------------------------------------------------------------------------
+# Parameter update after the exchange (Sections 4.1 and 4.3): the decoded, summed gradient
+# feeds the optimizer directly; an element no worker sent enters as zero
+# --------------------------------------------------------------------------------------
+
+def momentum_sgd_step(ghat, w, m, lr, mu):
+    """One Momentum SGD step on the decoded gradient `ghat` (Section 4.1: elements not sent are
+    taken to be zero, i.e. ghat holds 0 there and the momentum simply decays).
+
+    The paper names the optimizer but prints no formula.  Reading taken: the classical form
+        m <- mu m - lr ghat;   w <- w + m
+    in float32, one rounding per operation: t1 = mu*m, t2 = lr*ghat, m = t1 - t2, w = w + m.
+    Returns (w, m).
+    """
+    assert ghat.dtype == F32 and w.dtype == F32 and m.dtype == F32
+    lr32, mu32 = F32(lr), F32(mu)
+    t1 = (mu32 * m).astype(F32)
+    t2 = (lr32 * ghat).astype(F32)
+    m_new = (t1 - t2).astype(F32)
+    w_new = (w + m_new).astype(F32)
+    return w_new, m_new
+
+
+def adam_step(ghat, w, m, v, lr, beta1, beta2, eps, t):
+    """One Adam step (the method Section 4.3 says is computed locally after the exchange; the
+    experiments use its default hyperparameters), step count t >= 1, on the decoded gradient:
+        m <- b1 m + (1 - b1) ghat;  v <- b2 v + (1 - b2) ghat^2
+        w <- w - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
+    float32, one rounding per operation, in exactly this order; 1 - b1, 1 - b2, 1 - b1^t and
+    1 - b2^t are formed in float64 and rounded to float32 once.  Returns (w, m, v).
+    """
+    assert ghat.dtype == F32 and w.dtype == F32 and m.dtype == F32 and v.dtype == F32 and t >= 1
+    b1, b2 = F32(beta1), F32(beta2)
+    omb1, omb2 = F32(1.0 - float(b1)), F32(1.0 - float(b2))
+    bias1, bias2 = F32(1.0 - float(b1) ** t), F32(1.0 - float(b2) ** t)
+    m_new = ((b1 * m).astype(F32) + (omb1 * ghat).astype(F32)).astype(F32)
+    g2 = (ghat * ghat).astype(F32)
+    v_new = ((b2 * v).astype(F32) + (omb2 * g2).astype(F32)).astype(F32)
+    mhat = (m_new / bias1).astype(F32)
+    vhat = (v_new / bias2).astype(F32)
+    denom = (np.sqrt(vhat).astype(F32) + F32(eps)).astype(F32)
+    step = ((F32(lr) * mhat).astype(F32) / denom).astype(F32)
+    w_new = (w - step).astype(F32)
+    return w_new, m_new, v_new
+
+
+def unpack_apply(messages, groups, scale, n, optimizer, w, state1, state2=None, **hyper):
+    """CommunicateAndUpdate() after the allgatherv (Section 4.3) with the update folded in: the
+    messages [(words, headers)] are decoded and summed in worker order into a zero gradient,
+    then one optimizer step is taken.  optimizer: "momentum_sgd" (hyper: lr, mu) or "adam"
+    (hyper: lr, beta1, beta2, eps, t).  Returns the new (w, state1[, state2])."""
+    ghat = np.zeros(n, F32)
+    for words, headers in messages:
+        unpack_add(words, headers, groups, scale, ghat)
+    if optimizer == "momentum_sgd":
+        return momentum_sgd_step(ghat, w, state1, hyper["lr"], hyper["mu"])
+    if optimizer == "adam":
+        return adam_step(ghat, w, state1, state2, hyper["lr"], hyper["beta1"], hyper["beta2"], hyper["eps"], hyper["t"])
+    raise ValueError(optimizer)
