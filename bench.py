@@ -181,6 +181,9 @@ def main():
         "algorithmic_GBs": round((24.0 + 4.0 * hrho) * N / (hy * 1e-3) / 1e9, 1),
         "frac_of_peak": round((24.0 + 4.0 * hrho) * N / (hy * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
 
+    # decode fused with the parameter update: the last step's 8 messages, one Momentum SGD / Adam step on N parameters
+    out["stages"]["decode_plus_update"] = bench_update(vgc, plan, words, hdrs, status, dense, N, P, scale)
+
     # the sparse regime, one worker of the flat workload on a fresh state
     out["stages"]["sparse_regime_fresh_state"] = alpha_sweep(vgc, plan, pool[0][0], pool[0][1], r[0], v[0], zeta, scratch,
                                                              words[0], hdrs[0], status[0], (8.0, 16.0))
@@ -190,6 +193,33 @@ def main():
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(pool[0], a, cfg, min(a.cpu_sample, N))
     print(json.dumps(out))
+
+
+def bench_update(vgc, plan, words, hdrs, status, param, N, P, scale):
+    """vgc_unpack_apply on the messages left by the last timed step.  Algorithmic bytes: parameters and optimizer
+    state read and written once (16 B per parameter for Momentum SGD, 24 for Adam) + 4 B per word."""
+    import torch
+    counts = [vgc.read_status(status[w])[0] for w in range(P)]
+    n_words = float(sum(counts))
+    res = {}
+    m = torch.zeros_like(param)
+    v = torch.zeros_like(param)
+    for name, kind, per_param in (("momentum_sgd", vgc.MOMENTUM_SGD, 16.0), ("adam", vgc.ADAM, 24.0)):
+        ms = []
+        for k in range(4):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            vgc.unpack_apply(words, counts, hdrs, plan, scale, param, m, v if kind == vgc.ADAM else None, kind=kind,
+                             lr=1e-3, momentum=0.9, step=k + 1)
+            e1.record(); torch.cuda.synchronize()
+            if k:
+                ms.append(e0.elapsed_time(e1))
+        t = float(np.mean(ms))
+        gbs = (per_param * N + 4.0 * n_words) / (t * 1e-3) / 1e9
+        res[name] = {"ms": round(t, 4), "algorithmic_GBs": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+                     "bytes_per_param": per_param, "messages": P}
+    del m, v
+    return res
 
 
 def measured_traffic(N):

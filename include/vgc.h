@@ -208,6 +208,40 @@ int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words,
                          const vgc_group* groups, uint32_t n_groups, const void* plan,
                          float scale, int overwrite, float* dense_out, uint64_t n, void* stream);
 
+/* ---- decode fused with the parameter update --------------------------------------------------
+ * CommunicateAndUpdate() of Alg. 1 in one pass (Section 4.3; with Momentum SGD and the like,
+ * elements that no worker sent enter the update as zero, Section 4.1): the p messages are decoded
+ * and summed in message order into a zero gradient ghat, exactly as vgc_unpack_add_batch with
+ * overwrite does, and instead of writing ghat out the optimizer step is applied to every parameter:
+ *   VGC_OPT_MOMENTUM_SGD   m <- momentum m - lr ghat;   w <- w + m                  (state1 = m)
+ *   VGC_OPT_ADAM           m <- beta1 m + (1 - beta1) ghat;  v <- beta2 v + (1 - beta2) ghat^2;
+ *                          w <- w - lr (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ *                                                                               (state1 = m, state2 = v)
+ * float32, one rounding per operation in the order written; 1 - beta and 1 - beta^step are formed in
+ * double and rounded to float once.  The paper names the optimizers without printing them; these are
+ * the classical forms.
+ *
+ * words, hdrs, n_words: HOST arrays as for vgc_unpack_add_batch, p <= VGC_MAX_UPDATE_MESSAGES.
+ * opt: HOST.  param, state1, state2: DEVICE float[n], updated in place (state2 may be NULL for
+ * Momentum SGD).  Moves 16 (Momentum SGD) or 24 (Adam) bytes per parameter plus 4 per word; no
+ * dense gradient buffer exists.
+ */
+#define VGC_MAX_UPDATE_MESSAGES 64
+enum { VGC_OPT_MOMENTUM_SGD = 0, VGC_OPT_ADAM = 1 };
+typedef struct {
+    int32_t kind;        /* VGC_OPT_* */
+    float lr;
+    float momentum;      /* Momentum SGD */
+    float beta1, beta2, eps;   /* Adam */
+    uint32_t step;       /* Adam: number of this step, >= 1 */
+} vgc_optimizer;
+
+int vgc_unpack_apply(const uint32_t* const* words, const uint64_t* n_words,
+                     const vgc_group_hdr* const* hdrs, uint32_t p,
+                     const vgc_group* groups, uint32_t n_groups, const void* plan, float scale,
+                     const vgc_optimizer* opt, float* param, float* state1, float* state2,
+                     uint64_t n, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -283,4 +283,42 @@ int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, 
                                    static_cast<hipStream_t>(stream));
 }
 
+int vgc_unpack_apply(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+                     uint32_t p, const vgc_group* groups, uint32_t n_groups, const void* plan, float scale,
+                     const vgc_optimizer* opt, float* param, float* state1, float* state2, uint64_t n, void* stream) {
+    if (!plan || !opt || !param || !state1 || (p && (!words || !n_words || !hdrs))) { set_error("vgc_unpack_apply: NULL pointer"); return VGC_ERR_NULL; }
+    if (opt->kind != VGC_OPT_MOMENTUM_SGD && opt->kind != VGC_OPT_ADAM) { set_error("vgc_unpack_apply: unknown optimizer %d", opt->kind); return VGC_ERR_PARAM; }
+    if (opt->kind == VGC_OPT_ADAM && !state2) { set_error("vgc_unpack_apply: Adam needs state2"); return VGC_ERR_NULL; }
+    if (p > VGC_MAX_UPDATE_MESSAGES) { set_error("vgc_unpack_apply: %u messages, at most %d", p, VGC_MAX_UPDATE_MESSAGES); return VGC_ERR_SIZE; }
+    uint64_t n_tiles = 0;
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
+    if (rc != VGC_OK) return rc;
+    for (uint32_t w = 0; w < p; ++w) {
+        if (!hdrs[w] || (!words[w] && n_words[w])) { set_error("vgc_unpack_apply: message %u has a NULL pointer", w); return VGC_ERR_NULL; }
+        if (!aligned(words[w], 4) || !aligned(hdrs[w], 8)) { set_error("vgc_unpack_apply: message %u is misaligned", w); return VGC_ERR_ALIGN; }
+    }
+    if (!aligned(plan, 256) || !aligned(param, 4) || !aligned(state1, 4) || !aligned(state2, 4)) { set_error("vgc_unpack_apply: misaligned pointer"); return VGC_ERR_ALIGN; }
+    if (!std::isfinite(scale) || !std::isfinite(opt->lr)) { set_error("vgc_unpack_apply: scale or lr is not finite"); return VGC_ERR_PARAM; }
+    float mu = 0.f, b1 = 0.f, b2 = 0.f, omb1 = 0.f, omb2 = 0.f, bias1 = 1.f, bias2 = 1.f, eps = 0.f;
+    if (opt->kind == VGC_OPT_MOMENTUM_SGD) {
+        if (!(opt->momentum >= 0.0f) || !(opt->momentum < 1.0f)) { set_error("vgc_unpack_apply: need 0 <= momentum < 1 (got %g)", opt->momentum); return VGC_ERR_PARAM; }
+        mu = opt->momentum;
+    } else {
+        if (!(opt->beta1 >= 0.0f) || !(opt->beta1 < 1.0f) || !(opt->beta2 >= 0.0f) || !(opt->beta2 < 1.0f) || !(opt->eps >= 0.0f) ||
+            !std::isfinite(opt->eps) || opt->step < 1) {
+            set_error("vgc_unpack_apply: need 0 <= beta1, beta2 < 1, eps >= 0, step >= 1");
+            return VGC_ERR_PARAM;
+        }
+        b1 = opt->beta1; b2 = opt->beta2; eps = opt->eps;
+        omb1 = (float)(1.0 - (double)b1);
+        omb2 = (float)(1.0 - (double)b2);
+        bias1 = (float)(1.0 - std::pow((double)b1, (double)opt->step));
+        bias2 = (float)(1.0 - std::pow((double)b2, (double)opt->step));
+    }
+    const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    return launch_unpack_apply(words, n_words, hdrs, p, pv.groups, pv.runs, gs.n_runs, scale, opt->kind, opt->lr, mu, b1, b2,
+                               omb1, omb2, bias1, bias2, eps, param, state1, state2, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -134,9 +134,15 @@ int launch_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_h
                       hipStream_t stream);
 
 constexpr int kBatchMax = 8;   // messages one launch of the batched decoder takes
+constexpr int kApplyMax = 64;  // messages the decoder fused with the parameter update takes (one launch; a lane per message)
 int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
                             uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs,
                             float scale, int overwrite, float* dense, hipStream_t stream);
+
+int launch_unpack_apply(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+                        uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs, float scale,
+                        int kind, float lr, float mu, float b1, float b2, float omb1, float omb2, float bias1, float bias2,
+                        float eps, float* param, float* state1, float* state2, hipStream_t stream);
 
 int launch_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P,
                   uint32_t J, uint32_t C, float c, float* g_out, float* s_out,

@@ -63,12 +63,50 @@ namespace vgc {
 
 constexpr int kRounds = 4;          // words per lane loaded ahead per message
 
+template <int kMax>
 struct BatchArgs {
-    const uint32_t* words[kBatchMax];
-    const vgc_group_hdr* hdrs[kBatchMax];
-    uint64_t n_words[kBatchMax];
+    const uint32_t* words[kMax];
+    const vgc_group_hdr* hdrs[kMax];
+    uint64_t n_words[kMax];
     uint32_t p;
 };
+
+// What happens to a tile once every message has been added into it.
+//   kToDense       it is the tile of the dense gradient buffer: written back.
+//   kMomentumSgd   it is the decoded gradient ghat (elements nobody sent are zero, Section 4.1):
+//                  m <- mu m - lr ghat;  w <- w + m.
+//   kAdam          m <- b1 m + (1 - b1) ghat;  v <- b2 v + (1 - b2) ghat^2;
+//                  w <- w - lr (m / bias1) / (sqrt(v / bias2) + eps),  bias_i = 1 - b_i^t.
+// One float32 rounding per operation, in the order written (no contraction).
+enum { kToDense = 0, kMomentumSgd = 1, kAdam = 2 };
+
+struct UpdateArgs {
+    float* w;
+    float* s1;
+    float* s2;
+    float lr, mu, b1, b2, omb1, omb2, bias1, bias2, eps;
+};
+
+template <int kMode>
+__device__ __forceinline__ void update_element(const UpdateArgs& O, float ghat, float& w, float& s1, float& s2) {
+    if (kMode == kMomentumSgd) {
+        const float t1 = O.mu * s1;
+        const float t2 = O.lr * ghat;
+        s1 = t1 - t2;
+        w = w + s1;
+    } else {
+        const float a = O.b1 * s1, b = O.omb1 * ghat;
+        s1 = a + b;
+        const float g2 = ghat * ghat;
+        const float c = O.b2 * s2, d = O.omb2 * g2;
+        s2 = c + d;
+        const float mhat = s1 / O.bias1;
+        const float vhat = s2 / O.bias2;
+        const float denom = sqrtf(vhat) + O.eps;
+        const float step = (O.lr * mhat) / denom;
+        w = w - step;
+    }
+}
 
 typedef float f4u __attribute__((ext_vector_type(4)));
 
@@ -78,9 +116,11 @@ __device__ __forceinline__ uint64_t shfl64(uint64_t x, int src) {
     return ((uint64_t)hi << 32) | lo;
 }
 
-__global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs A, const PlanGroup* __restrict__ groups,
+template <int kMax, int kMode>
+__global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs<kMax> A, const PlanGroup* __restrict__ groups,
                                                           const PlanRun* __restrict__ runs, uint32_t n_runs,
-                                                          float scale, float* __restrict__ dense, int overwrite) {
+                                                          float scale, float* __restrict__ dense, int overwrite,
+                                                          UpdateArgs O) {
     __shared__ __attribute__((aligned(16))) float sh_tile[4][kTile];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     const uint32_t run = blockIdx.x * 4 + wave;
@@ -114,10 +154,25 @@ __global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs A, const Pla
     for (uint32_t t = t0; t < t1; ++t) {
         const uint32_t start = t * kTile;
         const uint32_t m = min(kTile, pg.size - start);
-        float* base = dense + pg.offset + start;
-        const bool vec = (m == kTile) && ((reinterpret_cast<uintptr_t>(base) & 15u) == 0);
+        const uint64_t e0 = pg.offset + start;
+        float* base = (kMode == kToDense) ? dense + e0 : O.w + e0;
+        bool vec = (m == kTile) && ((reinterpret_cast<uintptr_t>(base) & 15u) == 0);
+        // the optimizer's arrays are requested now and arrive while the messages are decoded
+        f4u W4[kMode == kToDense ? 1 : 8], S1[kMode == kToDense ? 1 : 8], S2[kMode == kAdam ? 8 : 1];
+        if (kMode != kToDense) {
+            vec = vec && ((reinterpret_cast<uintptr_t>(O.s1 + e0) & 15u) == 0) &&
+                  (kMode != kAdam || (reinterpret_cast<uintptr_t>(O.s2 + e0) & 15u) == 0);
+            if (vec) {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    W4[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(O.w + e0) + q * 64 + lane);
+                    S1[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(O.s1 + e0) + q * 64 + lane);
+                    if (kMode == kAdam) S2[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(O.s2 + e0) + q * 64 + lane);
+                }
+            }
+        }
         // ---- tile -> LDS ----
-        if (overwrite) {
+        if (overwrite || kMode != kToDense) {
 #pragma unroll
             for (int q = 0; q < 8; ++q) reinterpret_cast<f4u*>(T)[q * 64 + lane] = (f4u){0.f, 0.f, 0.f, 0.f};
         } else if (vec) {
@@ -171,15 +226,54 @@ __global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs A, const Pla
         }
 
         // ---- LDS -> tile ----
-        if (vec) {
+        if (kMode == kToDense) {
+            if (vec) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q)
-                __builtin_nontemporal_store(reinterpret_cast<f4u*>(T)[q * 64 + lane], reinterpret_cast<f4u*>(base) + q * 64 + lane);
+                for (int q = 0; q < 8; ++q)
+                    __builtin_nontemporal_store(reinterpret_cast<f4u*>(T)[q * 64 + lane], reinterpret_cast<f4u*>(base) + q * 64 + lane);
+            } else {
+                for (uint32_t i = lane; i < m; i += 64) base[i] = T[i];
+            }
+        } else if (vec) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const f4u G = reinterpret_cast<f4u*>(T)[q * 64 + lane];
+                f4u w4 = W4[q], a4 = S1[q], b4 = S2[kMode == kAdam ? q : 0];
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    float w = w4[c], a = a4[c], b = b4[c];
+                    update_element<kMode>(O, G[c], w, a, b);
+                    w4[c] = w; a4[c] = a; b4[c] = b;
+                }
+                __builtin_nontemporal_store(w4, reinterpret_cast<f4u*>(O.w + e0) + q * 64 + lane);
+                __builtin_nontemporal_store(a4, reinterpret_cast<f4u*>(O.s1 + e0) + q * 64 + lane);
+                if (kMode == kAdam) __builtin_nontemporal_store(b4, reinterpret_cast<f4u*>(O.s2 + e0) + q * 64 + lane);
+            }
         } else {
-            for (uint32_t i = lane; i < m; i += 64) base[i] = T[i];
+            for (uint32_t i = lane; i < m; i += 64) {
+                float w = O.w[e0 + i], a = O.s1[e0 + i], b = (kMode == kAdam) ? O.s2[e0 + i] : 0.f;
+                update_element<kMode>(O, T[i], w, a, b);
+                O.w[e0 + i] = w;
+                O.s1[e0 + i] = a;
+                if (kMode == kAdam) O.s2[e0 + i] = b;
+            }
         }
         __builtin_amdgcn_wave_barrier();
     }
+}
+
+template <int kMax>
+static BatchArgs<kMax> batch_args(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+                                  uint32_t first, uint32_t p) {
+    BatchArgs<kMax> A;
+    A.p = p - first < (uint32_t)kMax ? p - first : (uint32_t)kMax;
+    for (uint32_t w = 0; w < (uint32_t)kMax; ++w) {
+        const bool on = w < A.p;
+        A.words[w] = on ? words[first + w] : nullptr;
+        A.hdrs[w] = on ? hdrs[first + w] : nullptr;
+        A.n_words[w] = on ? n_words[first + w] : 0;
+    }
+    return A;
 }
 
 int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
@@ -188,19 +282,29 @@ int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_word
     const uint32_t blocks = (uint32_t)((n_runs + 3) / 4);
     const uint32_t chunks = p ? (p + kBatchMax - 1) / kBatchMax : 1;     // p == 0: only the optional clear
     for (uint32_t ch = 0; ch < chunks; ++ch) {
-        const uint32_t first = ch * kBatchMax;
-        BatchArgs A;
-        A.p = p - first < (uint32_t)kBatchMax ? p - first : (uint32_t)kBatchMax;
-        for (uint32_t w = 0; w < (uint32_t)kBatchMax; ++w) {
-            const bool on = w < A.p;
-            A.words[w] = on ? words[first + w] : nullptr;
-            A.hdrs[w] = on ? hdrs[first + w] : nullptr;
-            A.n_words[w] = on ? n_words[first + w] : 0;
-        }
-        hipLaunchKernelGGL(k_unpack_add_batch, dim3(blocks), dim3(256), 0, stream, A, groups, runs, (uint32_t)n_runs,
-                           scale, dense, (overwrite && ch == 0) ? 1 : 0);
+        const BatchArgs<kBatchMax> A = batch_args<kBatchMax>(words, n_words, hdrs, ch * kBatchMax, p);
+        hipLaunchKernelGGL((k_unpack_add_batch<kBatchMax, kToDense>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
+                           (uint32_t)n_runs, scale, dense, (overwrite && ch == 0) ? 1 : 0, UpdateArgs{});
     }
     return hip_check(hipGetLastError(), "launch k_unpack_add_batch");
+}
+
+int launch_unpack_apply(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+                        uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs, float scale,
+                        int kind, float lr, float mu, float b1, float b2, float omb1, float omb2, float bias1, float bias2,
+                        float eps, float* param, float* state1, float* state2, hipStream_t stream) {
+    const uint32_t blocks = (uint32_t)((n_runs + 3) / 4);
+    const BatchArgs<kApplyMax> A = batch_args<kApplyMax>(words, n_words, hdrs, 0, p);
+    UpdateArgs O;
+    O.w = param; O.s1 = state1; O.s2 = state2;
+    O.lr = lr; O.mu = mu; O.b1 = b1; O.b2 = b2; O.omb1 = omb1; O.omb2 = omb2; O.bias1 = bias1; O.bias2 = bias2; O.eps = eps;
+    if (kind == VGC_OPT_ADAM)
+        hipLaunchKernelGGL((k_unpack_add_batch<kApplyMax, kAdam>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
+                           (uint32_t)n_runs, scale, static_cast<float*>(nullptr), 1, O);
+    else
+        hipLaunchKernelGGL((k_unpack_add_batch<kApplyMax, kMomentumSgd>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
+                           (uint32_t)n_runs, scale, static_cast<float*>(nullptr), 1, O);
+    return hip_check(hipGetLastError(), "launch k_unpack_add_batch (update)");
 }
 
 }  // namespace vgc

@@ -34,6 +34,13 @@ class PackStatus(C.Structure):
     _fields_ = [("total_words", C.c_uint64), ("overflow", C.c_uint32), ("reserved", C.c_uint32)]
 
 
+class Optimizer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("momentum", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("eps", C.c_float), ("step", C.c_uint32)]
+
+
+MOMENTUM_SGD, ADAM = 0, 1
+
 HDR_DTYPE = np.dtype([("exp_field", "<u4"), ("count", "<u4"), ("word_offset", "<u8")])
 
 EXPORTS = {
@@ -59,6 +66,9 @@ EXPORTS = {
                                  C.c_float, C.c_void_p, C.c_uint64, C.c_void_p]),
     "vgc_unpack_add_batch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
                                        C.c_void_p, C.c_float, C.c_int, C.c_void_p, C.c_uint64, C.c_void_p]),
+    "vgc_unpack_apply": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
+                                   C.c_void_p, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
+                                   C.c_void_p]),
 }
 
 _lib = None
@@ -214,3 +224,15 @@ def unpack_add_batch(words, n_words, hdrs, plan, scale, dense, overwrite=False):
     nw = (C.c_uint64 * max(p, 1))(*[int(x) for x in n_words])
     _check(load().vgc_unpack_add_batch(wp, nw, hp, p, plan.c_groups, plan.n_groups, _ptr(plan.plan), float(scale),
                                        1 if overwrite else 0, _ptr(dense), plan.n, _stream()))
+
+
+def unpack_apply(words, n_words, hdrs, plan, scale, param, state1, state2=None, *, kind=MOMENTUM_SGD, lr=0.0,
+                 momentum=0.0, beta1=0.9, beta2=0.999, eps=1e-8, step=1):
+    """vgc_unpack_apply: decode the messages and take one optimizer step on (param, state1[, state2]) in place."""
+    p = len(words)
+    wp = (C.c_void_p * max(p, 1))(*[w.data_ptr() for w in words])
+    hp = (C.c_void_p * max(p, 1))(*[h.data_ptr() for h in hdrs])
+    nw = (C.c_uint64 * max(p, 1))(*[int(x) for x in n_words])
+    opt = Optimizer(kind, lr, momentum, beta1, beta2, eps, step)
+    _check(load().vgc_unpack_apply(wp, nw, hp, p, plan.c_groups, plan.n_groups, _ptr(plan.plan), float(scale),
+                                   C.byref(opt), _ptr(param), _ptr(state1), _ptr(state2), plan.n, _stream()))

@@ -1,0 +1,138 @@
+"""Decode fused with the parameter update (vgc_unpack_apply) against the oracle: the messages of p
+workers, built by the oracle's encoder, are decoded and one Momentum SGD or Adam step is taken.  Every
+output is compared bit for bit: both sides do the same float32 operations in the same order."""
+import numpy as np
+import pytest
+
+from oracle import vgc_oracle as O
+from paper_1802_06058_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+F32, U32 = np.float32, np.uint32
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+    from paper_1802_06058_amd import vgc
+    vgc.load()
+    assert torch.cuda.is_available()
+    return torch.device("cuda:0")
+
+
+def _bits(a):
+    return np.ascontiguousarray(a).view(U32)
+
+
+def _dev(a, dev):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
+def _messages(seed, p, n, groups, dev, sigma=1e-2):
+    msgs, d_words, d_hdrs, counts = [], [], [], []
+    rng = np.random.default_rng(seed)
+    for w in range(p):
+        g, s = W.sample_stream(31, (seed, w), n, 16, "student", sigma=sigma * 10.0 ** rng.uniform(-1, 1))
+        z = np.zeros(n, F32)
+        alpha = [1.0, 0.0, 4.0, 12.0][w % 4]
+        r_acc, _, _, send = O.accumulate_select(g, s, z, z, alpha, 0.999)
+        words, hdrs, _ = O.pack(r_acc, send, groups)
+        msgs.append((words, hdrs))
+        pad = np.full(words.size + 64, 0x12345678, U32)            # junk past the message; counts are upper bounds
+        pad[:words.size] = words
+        d_words.append(_dev(pad.view(np.int32), dev))
+        harr = np.array([(e, c, o) for e, c, o in hdrs], dtype=[("exp_field", "<u4"), ("count", "<u4"), ("word_offset", "<u8")])
+        d_hdrs.append(_dev(harr.view(np.uint8), dev))
+        counts.append(words.size + (7 if w % 2 else 0))
+    return msgs, d_words, d_hdrs, counts
+
+
+SIZES = [2048 * 70 + 5, 3, 5000, 2048 * 130, 1, 2048 * 3]
+
+
+@pytest.mark.parametrize("p", [0, 1, 3, 9, 64])
+def test_momentum_sgd_steps_match_oracle(dev, p):
+    import torch
+    from paper_1802_06058_amd import vgc
+    groups = W.groups_from_sizes(SIZES)
+    n = sum(SIZES)
+    plan = vgc.Plan(groups, dev)
+    rng = np.random.default_rng(100 + p)
+    w = rng.standard_normal(n).astype(F32)
+    m = (rng.standard_normal(n) * 1e-2).astype(F32)
+    dw, dm = _dev(w, dev), _dev(m, dev)
+    scale = 1.0 / max(p, 1) if p != 3 else 1.0 / 3.0
+    for step in range(2 if p <= 9 else 1):
+        msgs, d_words, d_hdrs, counts = _messages(1000 * p + step, p, n, groups, dev)
+        w, m = O.unpack_apply(msgs, groups, scale, n, "momentum_sgd", w, m, lr=0.05, mu=0.9)
+        vgc.unpack_apply(d_words, counts, d_hdrs, plan, scale, dw, dm, kind=vgc.MOMENTUM_SGD, lr=0.05, momentum=0.9)
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(dm.cpu().numpy()), _bits(m)), f"momentum differs at step {step}"
+        assert np.array_equal(_bits(dw.cpu().numpy()), _bits(w)), f"parameters differ at step {step}"
+
+
+@pytest.mark.parametrize("p", [1, 8, 17])
+def test_adam_steps_match_oracle(dev, p):
+    import torch
+    from paper_1802_06058_amd import vgc
+    groups = W.groups_from_sizes(SIZES)
+    n = sum(SIZES)
+    plan = vgc.Plan(groups, dev)
+    rng = np.random.default_rng(200 + p)
+    w = rng.standard_normal(n).astype(F32)
+    m, v = np.zeros(n, F32), np.zeros(n, F32)
+    dw, dm, dv = _dev(w, dev), _dev(m, dev), _dev(v, dev)
+    for t in (1, 2, 3):
+        msgs, d_words, d_hdrs, counts = _messages(2000 * p + t, p, n, groups, dev)
+        w, m, v = O.unpack_apply(msgs, groups, 1.0 / p, n, "adam", w, m, v, lr=1e-3, beta1=0.9, beta2=0.999, eps=1e-8, t=t)
+        vgc.unpack_apply(d_words, counts, d_hdrs, plan, 1.0 / p, dw, dm, dv, kind=vgc.ADAM, lr=1e-3, beta1=0.9, beta2=0.999,
+                         eps=1e-8, step=t)
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(dm.cpu().numpy()), _bits(m)), f"first moment differs at step {t}"
+        assert np.array_equal(_bits(dv.cpu().numpy()), _bits(v)), f"second moment differs at step {t}"
+        assert np.array_equal(_bits(dw.cpu().numpy()), _bits(w)), f"parameters differ at step {t}"
+
+
+def test_update_on_unaligned_views(dev):
+    """param / state pointers that are only 4-byte aligned take the element-wise path."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    sizes = [2048 * 5, 777]
+    groups = W.groups_from_sizes(sizes)
+    n = sum(sizes)
+    plan = vgc.Plan(groups, dev)
+    rng = np.random.default_rng(5)
+    w = rng.standard_normal(n).astype(F32)
+    m = (rng.standard_normal(n) * 1e-2).astype(F32)
+    bw = torch.zeros(n + 3, dtype=torch.float32, device=dev); bm = torch.zeros(n + 3, dtype=torch.float32, device=dev)
+    dw, dm = bw[1:n + 1], bm[3:n + 3]
+    dw.copy_(_dev(w, dev)); dm.copy_(_dev(m, dev))
+    msgs, d_words, d_hdrs, counts = _messages(77, 2, n, groups, dev)
+    w, m = O.unpack_apply(msgs, groups, 0.5, n, "momentum_sgd", w, m, lr=0.1, mu=0.5)
+    vgc.unpack_apply(d_words, counts, d_hdrs, plan, 0.5, dw, dm, kind=vgc.MOMENTUM_SGD, lr=0.1, momentum=0.5)
+    torch.cuda.synchronize()
+    assert np.array_equal(_bits(dm.cpu().numpy()), _bits(m)) and np.array_equal(_bits(dw.cpu().numpy()), _bits(w))
+    assert float(bw[0]) == 0.0 and float(bw[n + 1:].abs().sum()) == 0.0 and float(bm[:3].abs().sum()) == 0.0
+
+
+def test_update_rejects_bad_arguments(dev):
+    import torch
+    from paper_1802_06058_amd import vgc
+    groups = W.groups_from_sizes([100, 200])
+    plan = vgc.Plan(groups, dev)
+    t = torch.ones(300, dtype=torch.float32, device=dev)
+    h = plan.new_headers()
+    wd = torch.zeros(8, dtype=torch.int32, device=dev)
+    with pytest.raises(vgc.VgcError):
+        vgc.unpack_apply([wd] * 65, [0] * 65, [h] * 65, plan, 1.0, t, t, kind=vgc.MOMENTUM_SGD, lr=0.1, momentum=0.9)
+    with pytest.raises(vgc.VgcError):
+        vgc.unpack_apply([wd], [0], [h], plan, 1.0, t, t, kind=vgc.ADAM, lr=0.1)               # Adam without state2
+    with pytest.raises(vgc.VgcError):
+        vgc.unpack_apply([wd], [0], [h], plan, 1.0, t, t, kind=7, lr=0.1)
+    with pytest.raises(vgc.VgcError):
+        vgc.unpack_apply([wd], [0], [h], plan, 1.0, t, t, kind=vgc.MOMENTUM_SGD, lr=0.1, momentum=1.0)
+    with pytest.raises(vgc.VgcError):
+        vgc.unpack_apply([wd], [0], [h], plan, 1.0, t, t, t, kind=vgc.ADAM, lr=0.1, step=0)
+    torch.cuda.synchronize()
+    assert float((t - 1).abs().sum()) == 0.0
