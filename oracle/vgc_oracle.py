@@ -10,7 +10,8 @@ What is implemented, in the paper's order and notation:
   sqgrad_*            the two per-parameter sums of Alg. 1,
                       g_i = sum_z (grad_i f_z / B) and s_i = sum_z (grad_i f_z / B)^2,
                       from the definition of a per-sample gradient (Section 4.1).
-                      float64 throughout.
+                      float64 throughout.  sqgrad_conv_nhwc*: the same for a convolution
+                      given by its input and output-gradient tensors (no im2col matrix).
   accumulate_select   the body of the `foreach parameters` loop of Alg. 1 with the
                       criterion of Eq. 2 and the decay of Section 4.4; float32, one
                       rounding per operation.
@@ -120,6 +121,77 @@ def sqgrad_conv(U, D, c):
         G = (U[z].astype(np.float64).T @ D[z].astype(np.float64)) * c
         g += G
         s += G * G
+    return g, s
+
+
+def conv_out_size(n_in, k, stride, pad):
+    """Output extent of a convolution along one axis (no dilation)."""
+    return (n_in + 2 * pad - k) // stride + 1
+
+
+def sqgrad_conv_nhwc_bruteforce(act, D, kh, kw, stride, pad, c):
+    """The same sums for a 2-d convolution given as it is stored, without an im2col matrix.
+
+    act [B, H, W, Cin] is the layer's input, D [B, Ho, Wo, Cout] the gradient of each sample's loss
+    w.r.t. the layer's output.  Sample z's gradient w.r.t. the weight W[ky, kx, i, o] is
+        sum_{y, x} act[z, y*stride + ky - pad, x*stride + kx - pad, i] * D[z, y, x, o]
+    with positions outside the input contributing zero (zero padding).  The result is indexed
+    [(ky*kw + kx)*Cin + i, o].  Pure loops, float64; tiny inputs only.
+    """
+    act = np.asarray(act, dtype=np.float64)
+    D = np.asarray(D, dtype=np.float64)
+    B, H, W, Cin = act.shape
+    _, Ho, Wo, Cout = D.shape
+    sh, sw = stride
+    ph, pw = pad
+    assert Ho == conv_out_size(H, kh, sh, ph) and Wo == conv_out_size(W, kw, sw, pw)
+    g = np.zeros((kh * kw * Cin, Cout))
+    s = np.zeros((kh * kw * Cin, Cout))
+    for z in range(B):
+        for ky in range(kh):
+            for kx in range(kw):
+                for i in range(Cin):
+                    for o in range(Cout):
+                        grad = 0.0
+                        for y in range(Ho):
+                            iy = y * sh + ky - ph
+                            if iy < 0 or iy >= H:
+                                continue
+                            for x in range(Wo):
+                                ix = x * sw + kx - pw
+                                if ix < 0 or ix >= W:
+                                    continue
+                                grad += act[z, iy, ix, i] * D[z, y, x, o]
+                        grad *= c
+                        g[(ky * kw + kx) * Cin + i, o] += grad
+                        s[(ky * kw + kx) * Cin + i, o] += grad * grad
+    return g, s
+
+
+def sqgrad_conv_nhwc(act, D, kh, kw, stride, pad, c):
+    """Convolution at config sizes: per sample and per filter tap (ky, kx) the gradient block
+    G_z[ky, kx] = A^T D_z, A the input window that tap sees (a strided slice of the zero-padded
+    input), accumulated and square-accumulated over the samples.  float64."""
+    act = np.asarray(act)
+    D = np.asarray(D)
+    B, H, W, Cin = act.shape
+    _, Ho, Wo, Cout = D.shape
+    sh, sw = stride
+    ph, pw = pad
+    assert Ho == conv_out_size(H, kh, sh, ph) and Wo == conv_out_size(W, kw, sw, pw)
+    g = np.zeros((kh * kw * Cin, Cout))
+    s = np.zeros((kh * kw * Cin, Cout))
+    for z in range(B):
+        a = np.zeros((H + 2 * ph, W + 2 * pw, Cin))
+        a[ph:ph + H, pw:pw + W] = act[z].astype(np.float64)
+        d = D[z].astype(np.float64).reshape(Ho * Wo, Cout)
+        for ky in range(kh):
+            for kx in range(kw):
+                win = a[ky:ky + sh * (Ho - 1) + 1:sh, kx:kx + sw * (Wo - 1) + 1:sw]     # [Ho, Wo, Cin]
+                G = (win.reshape(Ho * Wo, Cin).T @ d) * c
+                j0 = (ky * kw + kx) * Cin
+                g[j0:j0 + Cin] += G
+                s[j0:j0 + Cin] += G * G
     return g, s
 
 
