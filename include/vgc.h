@@ -133,6 +133,27 @@ int vgc_sqgrad(int kind, int dtype, const void* X, const void* D,
                uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
                float* g_out, float* s_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same sums for a 2-d convolution given as the layer stores it, without a patch matrix:
+ *   act [B, H, W, Cin] (NHWC) the layer's input, D [B, Ho, Wo, C] (NHWC) the gradient of each sample's
+ *   loss w.r.t. the layer's output, Ho = (H + 2 pad_h - kh) / stride_h + 1, Wo likewise.
+ * Sample z's gradient of the weight W[ky, kx, i, o] is
+ *   sum_{y, x} act[z, y stride_h + ky - pad_h, x stride_w + kx - pad_w, i] * D[z, y, x, o]
+ * (positions outside the input count as zero); g and s come out as [kh * kw * Cin, C] row-major with
+ * row (ky * kw + kx) * Cin + i, i.e. the weight in [kh, kw, Cin, C] layout.  It is VGC_CONV applied to
+ * the im2col matrix of act, which is never materialised: the input is read directly, 1 / (kh kw) of
+ * the bytes, and neighbouring filter taps find each other's lines in the cache.
+ * dtype: VGC_BF16 only, Cin and C multiples of 8; anything else returns VGC_ERR_DTYPE / VGC_ERR_SIZE
+ * (build the patch matrix and call vgc_sqgrad).  Pointers, workspace and errors as for vgc_sqgrad.
+ */
+size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
+                                         uint32_t kh, uint32_t kw, uint32_t stride_h, uint32_t stride_w,
+                                         uint32_t pad_h, uint32_t pad_w);
+
+int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin,
+                      uint32_t C, uint32_t kh, uint32_t kw, uint32_t stride_h, uint32_t stride_w,
+                      uint32_t pad_h, uint32_t pad_w, float c, float* g_out, float* s_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- (b) accumulate, test, reset or decay ---------------------------------------------------
  * The body of Alg. 1's parameter loop with the criterion of Eq. 2 and the decay of Section 4.4,
  * for all n parameters in one launch, in float32 with one rounding per operation:

@@ -180,6 +180,55 @@ int vgc_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, ui
                          static_cast<hipStream_t>(stream));
 }
 
+// Validates a convolution's geometry; on success the output extent.
+static int conv2d_geometry(int dtype, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t kh, uint32_t kw,
+                           uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw, uint32_t* Ho, uint32_t* Wo) {
+    if (dtype != VGC_F32 && dtype != VGC_BF16) { set_error("vgc_sqgrad_conv2d: unknown dtype %d", dtype); return VGC_ERR_DTYPE; }
+    if (B == 0 || H == 0 || W == 0 || Cin == 0 || C == 0 || kh == 0 || kw == 0 || sh == 0 || sw == 0) {
+        set_error("vgc_sqgrad_conv2d: zero dimension");
+        return VGC_ERR_SIZE;
+    }
+    if (ph >= kh || pw >= kw || (uint64_t)H + 2 * ph < kh || (uint64_t)W + 2 * pw < kw) {
+        set_error("vgc_sqgrad_conv2d: need pad < kernel <= input + 2 pad");
+        return VGC_ERR_SIZE;
+    }
+    if ((uint64_t)kh * kw * Cin > 0x7FFFFFFFull || (uint64_t)H * W > 0x7FFFFFFFull) { set_error("vgc_sqgrad_conv2d: shape too large"); return VGC_ERR_SIZE; }
+    *Ho = (H + 2 * ph - kh) / sh + 1;
+    *Wo = (W + 2 * pw - kw) / sw + 1;
+    if (dtype != VGC_BF16) { set_error("vgc_sqgrad_conv2d: bf16 inputs only; build the patch matrix and call vgc_sqgrad"); return VGC_ERR_DTYPE; }
+    if (!conv2d_supported(dtype, H, W, Cin, C, *Ho * *Wo)) {
+        set_error("vgc_sqgrad_conv2d: needs Cin and C multiples of 8 and per-sample tensors below 2 GiB");
+        return VGC_ERR_SIZE;
+    }
+    return VGC_OK;
+}
+
+size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
+                                         uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw) {
+    uint32_t Ho, Wo;
+    if (conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, &Ho, &Wo) != VGC_OK) return 0;
+    const uint32_t J = kh * kw * Cin;
+    const uint32_t splits = conv_splits(B, J, C);
+    return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
+}
+
+int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin,
+                      uint32_t C, uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw,
+                      float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!act || !D || !s_out) { set_error("vgc_sqgrad_conv2d: act, D and s_out are required"); return VGC_ERR_NULL; }
+    uint32_t Ho, Wo;
+    int rc = conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, &Ho, &Wo);
+    if (rc != VGC_OK) return rc;
+    if (!aligned(act, 16) || !aligned(D, 16) || !aligned(s_out, 16) || (g_out && !aligned(g_out, 16)) ||
+        (workspace && !aligned(workspace, 16))) {
+        set_error("vgc_sqgrad_conv2d: pointers must be 16-byte aligned");
+        return VGC_ERR_ALIGN;
+    }
+    if (!std::isfinite(c)) { set_error("vgc_sqgrad_conv2d: c is not finite"); return VGC_ERR_PARAM; }
+    return launch_conv2d(act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, Ho, Wo, c, g_out, s_out, workspace, workspace_bytes,
+                         static_cast<hipStream_t>(stream));
+}
+
 static int accumulate_select_any(const float* g, const float* s, float* r, float* v, uint64_t n,
                                  const vgc_group* groups, uint32_t n_groups, const void* plan,
                                  float alpha, float zeta, float tau, bool hybrid, void* scratch, void* stream) {

@@ -86,13 +86,21 @@ struct ChunkStream {
     }
 };
 
-// BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.
-template <int BM, int BN, bool kWantG>
+// Geometry of a 2-d convolution whose patch matrix is never built: U[z, p, j] with p = y Wo + x and
+// j = (ky kw + kx) Cin + i is the input element [z, y sh + ky - ph, x sw + kx - pw, i], or zero outside.
+struct ConvGeom {
+    uint32_t H, W, Cin, kw, sh, sw, ph, pw, Ho, Wo;
+    uint32_t step_y, step_x; // one chunk of kKC positions further: kKC = step_y * Wo + step_x
+};
+
+// BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.  kImplicit: U is the layer's NHWC input seen
+// through the geometry G (J = kh kw Cin), otherwise a [B, P, J] matrix.
+template <int BM, int BN, bool kWantG, bool kImplicit>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
 void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                  uint32_t B, uint32_t P, uint32_t J, uint32_t C,
                  uint32_t z_per_split, uint32_t splits, float cg, float cs,
-                 float* __restrict__ g_out, float* __restrict__ s_out, float* __restrict__ ws) {
+                 float* __restrict__ g_out, float* __restrict__ s_out, float* __restrict__ ws, ConvGeom G) {
     constexpr int NW = (BM / 64) * (BN / 64);
     constexpr int kABytes = kKC * BM * 2, kBBytes = kKC * BN * 2, kBufBytes = kABytes + kBBytes;
     // ring of staged chunks = chunks in flight: as many as fit beside the other workgroups of the CU (at
@@ -130,13 +138,29 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     // ---- global side: which piece each lane fetches, per wave-wide load ----
     // Load ii of an operand covers rows ii * rpi .. + rpi - 1 of the chunk (1 KiB of the staged tile);
     // lane l lands on row ii * rpi + l / npr, physical piece l % npr.
+    // In the implicit form the lane's piece of 8 columns lies inside one filter tap (Cin is a multiple
+    // of 8); what is kept per load is the tap's offset in the input and the lane's row in the chunk, and
+    // the byte offset is formed per chunk from the row's output position.
     uint32_t voffA[kPerA], voffB[kPerB];
+    uint32_t y0A[kPerA], x0A[kPerA], yA[kPerA], xA[kPerA];       // output position of the lane's row: chunk 0, current chunk
+    int32_t tapY[kPerA], tapX[kPerA], tapOff[kPerA];
 #pragma unroll
     for (int j = 0; j < kPerA; ++j) {
         constexpr uint32_t npr = BM / 8, rpi = 64 / npr;
         const uint32_t ii = wave + (uint32_t)NW * j, row = ii * rpi + lane / npr, p = lane % npr;
         const uint32_t piece = (((p >> 2) ^ swizzle<BM>(row)) << 2) | (p & 3u);
-        voffA[j] = (row * J + j0 + piece * 8u) * 2u;
+        if (kImplicit) {
+            const uint32_t col = j0 + piece * 8u, tap = col / G.Cin, ky = tap / G.kw;
+            y0A[j] = yA[j] = row / G.Wo;
+            x0A[j] = xA[j] = row - y0A[j] * G.Wo;
+            tapY[j] = (int32_t)ky - (int32_t)G.ph;
+            tapX[j] = (int32_t)(tap - ky * G.kw) - (int32_t)G.pw;
+            // input offset (elements) of the tap relative to the row's own (y sh, x sw), plus the channel
+            tapOff[j] = (tapY[j] * (int32_t)G.W + tapX[j]) * (int32_t)G.Cin + (int32_t)(col - tap * G.Cin);
+            if (col >= J) tapY[j] = -0x400000;           // a column past J: never inside the input
+        } else {
+            voffA[j] = (row * J + j0 + piece * 8u) * 2u;
+        }
     }
 #pragma unroll
     for (int j = 0; j < kPerB; ++j) {
@@ -183,7 +207,12 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
 
     // ---- the stream of chunk requests ----
     ChunkStream sa, sb;
-    sa.init(U, z_begin, P, J);
+    if (kImplicit) {
+        sa.init(U, z_begin, G.H * G.W, G.Cin);           // the descriptor covers the whole input of the sample
+        sa.chunk_bytes = 0;
+    } else {
+        sa.init(U, z_begin, P, J);
+    }
     sb.init(D, z_begin, P, C);
     uint32_t pcl = 0, issued = 0, bo_fill = 0;           // position in the sample, chunks requested, ring buffer (byte offset)
     auto next_buf = [&](uint32_t bo) -> uint32_t { return bo + kBufBytes == (uint32_t)kRingBytes ? 0u : bo + kBufBytes; };
@@ -191,12 +220,39 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         const bool live = issued < total;                // past the last chunk the range is empty: zeros arrive
         const i4v ra = sa.rsrc(live), rb = sb.rsrc(live);
 #pragma unroll
-        for (int j = 0; j < kPerA; ++j) load_to_lds(lds0 + bo_fill + (wave + (uint32_t)NW * j) * 1024u, voffA[j], ra);
+        for (int j = 0; j < kPerA; ++j) {
+            uint32_t voff;
+            if (kImplicit) {
+                // All factors are below 2^23 (checked on the host): 24-bit multiplies, full rate.  Rows of the
+                // input above or below the image need no test: their offset is negative or past the sample's
+                // range, which the buffer load answers with zeros; a column outside would alias into the
+                // neighbouring row, and a position past P into a valid one, so those two are masked.
+                const int32_t ys = __mul24((int32_t)yA[j], (int32_t)G.sh);
+                const int32_t xs = __mul24((int32_t)xA[j], (int32_t)G.sw);
+                const bool inside = ((uint32_t)(xs + tapX[j]) < G.W) & (yA[j] < G.Ho);
+                const int32_t lin = __mul24(ys, (int32_t)G.W) + xs;
+                const int32_t off = __mul24(lin, (int32_t)G.Cin) + tapOff[j];
+                voff = ((uint32_t)off << 1) | (inside ? 0u : 0xFFFFFFFFu);
+            } else {
+                voff = voffA[j];
+            }
+            load_to_lds(lds0 + bo_fill + (wave + (uint32_t)NW * j) * 1024u, voff, ra);
+        }
 #pragma unroll
         for (int j = 0; j < kPerB; ++j) load_to_lds(lds0 + bo_fill + kABytes + (wave + (uint32_t)NW * j) * 1024u, voffB[j], rb);
         ++issued;
         const bool wrap = (++pcl == n_chunks);
         if (wrap) pcl = 0;
+        if (kImplicit) {
+#pragma unroll
+            for (int j = 0; j < kPerA; ++j) {            // the lane's row of the next chunk: kKC positions further
+                const uint32_t x = xA[j] + G.step_x, xw = x - G.Wo;
+                const uint32_t carry = x >= G.Wo ? 1u : 0u;
+                const uint32_t keep = wrap ? 0u : 0xFFFFFFFFu;           // bit select, not a branch on the uniform flag
+                xA[j] = (min(x, xw) & keep) | (x0A[j] & ~keep);
+                yA[j] = ((yA[j] + G.step_y + carry) & keep) | (y0A[j] & ~keep);
+            }
+        }
         sa.next(wrap);
         sb.next(wrap);
         bo_fill = next_buf(bo_fill);
@@ -388,22 +444,23 @@ void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg,
                        g_out, s_out);
 }
 
-template <int BM, int BN>
+template <int BM, int BN, bool kImplicit>
 static void launch_conv_bf16(uint32_t nblk, hipStream_t stream, const void* X, const void* D, uint32_t B, uint32_t P,
                              uint32_t J, uint32_t C, uint32_t zper, uint32_t splits, float cg, float cs,
-                             float* g_out, float* s_out, float* ws) {
+                             float* g_out, float* s_out, float* ws, const ConvGeom& G) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
     if (g_out)
-        hipLaunchKernelGGL((k_conv_bf16<BM, BN, true>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
-                           (const uint16_t*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+        hipLaunchKernelGGL((k_conv_bf16<BM, BN, true, kImplicit>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
+                           (const uint16_t*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
     else
-        hipLaunchKernelGGL((k_conv_bf16<BM, BN, false>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
-                           (const uint16_t*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+        hipLaunchKernelGGL((k_conv_bf16<BM, BN, false, kImplicit>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
+                           (const uint16_t*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
 }
 
-int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
-                      float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
-    (void)dtype;
+template <bool kImplicit>
+static int launch_conv_any(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+                           float* g_out, float* s_out, void* workspace, size_t workspace_bytes, const ConvGeom& G,
+                           hipStream_t stream) {
     const ConvTile t = conv_tile(J, C);
     uint32_t splits = conv_splits(B, J, C);
     if (splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * J * C * sizeof(float))) splits = 1;
@@ -413,12 +470,36 @@ int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint3
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
-    if (t.bm == 256 && t.bn == 128) launch_conv_bf16<256, 128>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
-    else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
-    else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
-    else launch_conv_bf16<128, 64>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+    if (t.bm == 256 && t.bn == 128) launch_conv_bf16<256, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
+    else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
+    else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
+    else launch_conv_bf16<128, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
     if (splits > 1) launch_sqgrad_reduce(ws, splits, (size_t)J * C, cg, cs, g_out, s_out, stream);
     return hip_check(hipGetLastError(), "launch k_conv_bf16");
+}
+
+int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
+                      float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    (void)dtype;
+    return launch_conv_any<false>(X, D, B, P, J, C, c, g_out, s_out, workspace, workspace_bytes, ConvGeom{}, stream);
+}
+
+bool conv2d_supported(int dtype, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t P) {
+    const uint64_t limit = 0x7FFFFFFFull;               // buffer ranges and offsets are 32-bit
+    // the kernel's address arithmetic multiplies (y sh W + x sw) by Cin with 24-bit multiplies
+    const uint64_t m24 = 1u << 23;
+    return dtype == VGC_BF16 && (Cin % 8 == 0) && (C % 8 == 0) && (uint64_t)H * W * Cin * 2 < limit &&
+           (uint64_t)(P + 64) * C * 2 < limit && (uint64_t)(H + 64) * (W + 64) < m24 && Cin < m24;
+}
+
+int launch_conv2d(const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
+                  uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw, uint32_t Ho, uint32_t Wo,
+                  float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    ConvGeom G;
+    G.H = H; G.W = W; G.Cin = Cin; G.kw = kw; G.sh = sh; G.sw = sw; G.ph = ph; G.pw = pw; G.Ho = Ho; G.Wo = Wo;
+    G.step_y = kKC / Wo;
+    G.step_x = kKC % Wo;
+    return launch_conv_any<true>(act, D, B, Ho * Wo, kh * kw * Cin, C, c, g_out, s_out, workspace, workspace_bytes, G, stream);
 }
 
 }  // namespace vgc

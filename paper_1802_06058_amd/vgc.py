@@ -55,6 +55,9 @@ EXPORTS = {
     "vgc_sqgrad_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]),
     "vgc_sqgrad": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
                              C.c_uint32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "vgc_sqgrad_conv2d_workspace_bytes": (C.c_size_t, [C.c_int] + [C.c_uint32] * 11),
+    "vgc_sqgrad_conv2d": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p] + [C.c_uint32] * 11 +
+                          [C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
     "vgc_accumulate_select": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
                                         C.c_uint32, C.c_void_p, C.c_float, C.c_float, C.c_void_p, C.c_void_p]),
     "vgc_accumulate_select_hybrid": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
@@ -193,6 +196,22 @@ def sqgrad(kind, X, D, c, s_out, g_out=None, workspace=None):
         Cc = D.shape[2]
     _check(load().vgc_sqgrad(kind, dtype, _ptr(X), _ptr(D), B, P, J, Cc, float(c), _ptr(g_out), _ptr(s_out),
                              _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()))
+
+
+def sqgrad_conv2d_workspace_bytes(dtype, B, H, W, Cin, Cc, kh, kw, stride, pad):
+    return int(load().vgc_sqgrad_conv2d_workspace_bytes(dtype, B, H, W, Cin, Cc, kh, kw, stride[0], stride[1], pad[0], pad[1]))
+
+
+def sqgrad_conv2d(act, D, kh, kw, stride, pad, c, s_out, g_out=None, workspace=None):
+    """vgc_sqgrad_conv2d.  act [B, H, W, Cin], D [B, Ho, Wo, C] (NHWC, bfloat16); s_out, g_out [kh*kw*Cin, C]."""
+    import torch
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(act.dtype)
+    if dtype is None or D.dtype != act.dtype:
+        raise VgcError(f"unsupported dtypes {act.dtype}, {D.dtype}")
+    B, H, W, Cin = act.shape
+    _check(load().vgc_sqgrad_conv2d(dtype, _ptr(act), _ptr(D), B, H, W, Cin, D.shape[3], kh, kw, stride[0], stride[1],
+                                    pad[0], pad[1], float(c), _ptr(g_out), _ptr(s_out), _ptr(workspace),
+                                    0 if workspace is None else workspace.numel(), _stream()))
 
 
 def accumulate_select(g, s, r, v, plan, alpha, zeta, scratch):

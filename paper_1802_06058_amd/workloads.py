@@ -140,6 +140,16 @@ def conv_inputs(seed, path, B, P, J, C, d_sigma=1.0, bf16=False):
     return U, D
 
 
+def conv2d_inputs(seed, path, B, H, W, Cin, Ho, Wo, C, d_sigma=1.0, bf16=False):
+    """Layer input [B, H, W, Cin] ~ N(0,1) and output gradient [B, Ho, Wo, C] ~ N(0, d_sigma^2), NHWC."""
+    ra, rd = stream(seed, *path, 0), stream(seed, *path, 2)
+    A = ra.standard_normal((B, H, W, Cin), dtype=np.float32)
+    D = rd.standard_normal((B, Ho, Wo, C), dtype=np.float32) * np.float32(d_sigma)
+    if bf16:
+        return f32_to_bf16_bits(A), f32_to_bf16_bits(D)
+    return A, D
+
+
 def layer_sigmas(seed, n_layers, lo=1e-5, hi=1e-2):
     """Per-layer gradient scale, log-uniform in [lo, hi], drawn once per layer."""
     u = stream(seed, 9001).random(n_layers)

@@ -1,0 +1,143 @@
+"""vgc_sqgrad_conv2d (the convolution statistic read from the NHWC input, no patch matrix) against the
+float64 oracle, and against vgc_sqgrad on the materialised patch matrix.  Tolerance for bfloat16
+inputs: 1e-2, measured like the conv form's (against the magnitudes summed)."""
+import numpy as np
+import pytest
+
+from oracle import vgc_oracle as O
+from paper_1802_06058_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-2
+
+
+@pytest.fixture(scope="module")
+def dev():
+    import torch
+    from paper_1802_06058_amd import vgc
+    assert torch.cuda.is_available()
+    vgc.load()
+    return torch.device("cuda:0")
+
+
+def _bf(a, dev):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a)).to(dev).view(torch.bfloat16)
+
+
+def _run(A, D, kh, kw, stride, pad, c, dev, want_g=True, use_workspace=True):
+    import torch
+    from paper_1802_06058_amd import vgc
+    B, H, Wd, Cin = A.shape
+    C = D.shape[3]
+    J = kh * kw * Cin
+    s = torch.full((J, C), float("nan"), dtype=torch.float32, device=dev)
+    g = torch.full((J, C), float("nan"), dtype=torch.float32, device=dev) if want_g else None
+    ws = None
+    if use_workspace:
+        nb = vgc.sqgrad_conv2d_workspace_bytes(vgc.BF16, B, H, Wd, Cin, C, kh, kw, stride, pad)
+        if nb:
+            ws = torch.full((nb,), 0xFF, dtype=torch.uint8, device=dev)
+    vgc.sqgrad_conv2d(_bf(A, dev), _bf(D, dev), kh, kw, stride, pad, c, s, g, workspace=ws)
+    torch.cuda.synchronize()
+    return (g.cpu().numpy() if want_g else None), s.cpu().numpy()
+
+
+def _patches(a, kh, kw, stride, pad, Ho, Wo):
+    """[B, Ho*Wo, kh*kw*Cin] patch matrix of a float array, zero padded (test-side helper)."""
+    B, H, Wd, Cin = a.shape
+    ap = np.zeros((B, H + 2 * pad[0], Wd + 2 * pad[1], Cin), a.dtype)
+    ap[:, pad[0]:pad[0] + H, pad[1]:pad[1] + Wd] = a
+    cols = [ap[:, ky:ky + stride[0] * (Ho - 1) + 1:stride[0], kx:kx + stride[1] * (Wo - 1) + 1:stride[1]]
+            for ky in range(kh) for kx in range(kw)]
+    return np.concatenate(cols, axis=3).reshape(B, Ho * Wo, kh * kw * Cin)
+
+
+GEOMS = [  # B, H, W, Cin, C, kh, kw, stride, pad
+    (3, 8, 8, 8, 16, 3, 3, (1, 1), (1, 1)),        # one tile, taps narrower than the 16-byte pieces' tile
+    (2, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)),     # VGG-like, small
+    (4, 9, 7, 16, 24, 3, 3, (2, 2), (1, 1)),       # stride 2, ragged everything
+    (2, 12, 10, 32, 40, 1, 1, (1, 1), (0, 0)),     # 1x1
+    (3, 11, 13, 8, 8, 5, 3, (2, 1), (2, 0)),       # rectangular kernel, mixed stride and padding
+    (2, 6, 1, 24, 16, 3, 1, (1, 1), (1, 0)),       # output one column wide
+    (5, 28, 28, 128, 136, 3, 3, (1, 1), (1, 1)),   # several row tiles and a ragged column tile, samples split
+    (2, 16, 16, 256, 128, 3, 3, (1, 1), (1, 1)),   # a 256-column tile inside one tap
+]
+
+
+@pytest.mark.parametrize("geom", GEOMS)
+def test_conv2d_matches_oracle(dev, geom):
+    B, H, Wd, Cin, C, kh, kw, stride, pad = geom
+    Ho, Wo = O.conv_out_size(H, kh, stride[0], pad[0]), O.conv_out_size(Wd, kw, stride[1], pad[1])
+    A, D = W.conv2d_inputs(41, geom[:7], B, H, Wd, Cin, Ho, Wo, C, d_sigma=0.02, bf16=True)
+    Aw, Dw = W.bf16_bits_to_f32(A).astype(np.float64), W.bf16_bits_to_f32(D).astype(np.float64)
+    c = 1.0 / B
+    g64, s64 = O.sqgrad_conv_nhwc(Aw, Dw, kh, kw, stride, pad, c)
+    Uabs = _patches(np.abs(Aw), kh, kw, stride, pad, Ho, Wo)
+    per_sample_abs = np.einsum("zpj,zpc->zjc", Uabs, np.abs(Dw).reshape(B, Ho * Wo, C))
+    absG = per_sample_abs.sum(0) * c
+    sabs = (per_sample_abs ** 2).sum(0) * c * c
+    g, s = _run(A, D, kh, kw, stride, pad, c, dev)
+    assert np.isfinite(g).all() and np.isfinite(s).all()
+    assert (np.abs(g - g64) / np.maximum(absG, 1e-300)).max() <= TOL
+    assert (np.abs(s - s64) / np.maximum(sabs, 1e-300)).max() <= TOL
+    assert np.all(s[sabs == 0] == 0)
+    # no workspace (no sample split), and s alone: same bounds; s alone equals s with g bit for bit
+    g1, s1 = _run(A, D, kh, kw, stride, pad, c, dev, use_workspace=False)
+    assert (np.abs(g1 - g64) / np.maximum(absG, 1e-300)).max() <= TOL and (np.abs(s1 - s64) / np.maximum(sabs, 1e-300)).max() <= TOL
+    _, s2 = _run(A, D, kh, kw, stride, pad, c, dev, want_g=False)
+    assert (np.abs(s2 - s64) / np.maximum(sabs, 1e-300)).max() <= TOL
+
+
+def test_conv2d_equals_patch_matrix_path(dev):
+    """Same inputs through vgc_sqgrad on the materialised patch matrix: the two kernels multiply the same
+    bfloat16 numbers and add them in float32 in the same order per output, so they agree to rounding noise."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    B, H, Wd, Cin, C, kh, kw, stride, pad = 4, 14, 14, 128, 128, 3, 3, (1, 1), (1, 1)
+    Ho, Wo = 14, 14
+    A, D = W.conv2d_inputs(42, (0,), B, H, Wd, Cin, Ho, Wo, C, d_sigma=0.02, bf16=True)
+    g, s = _run(A, D, kh, kw, stride, pad, 1.0 / B, dev)
+    U = _patches(A, kh, kw, stride, pad, Ho, Wo)
+    J = kh * kw * Cin
+    s_ref = torch.empty(J, C, dtype=torch.float32, device=dev); g_ref = torch.empty(J, C, dtype=torch.float32, device=dev)
+    nb = vgc.sqgrad_workspace_bytes(vgc.CONV, vgc.BF16, B, Ho * Wo, J, C)
+    ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
+    vgc.sqgrad(vgc.CONV, _bf(U, dev), _bf(D.reshape(B, Ho * Wo, C), dev), 1.0 / B, s_ref, g_ref, workspace=ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(s, s_ref.cpu().numpy()) and np.array_equal(g, g_ref.cpu().numpy())
+
+
+def test_conv2d_sampled_outputs_at_vgg_conv4_shape(dev):
+    """VGG-16 conv4_2 (28x28x512 -> 512, 3x3, batch 64): sampled outputs recomputed from the definition."""
+    B, H, Wd, Cin, C, kh, kw, stride, pad = 64, 28, 28, 512, 512, 3, 3, (1, 1), (1, 1)
+    A, D = W.conv2d_inputs(43, (0,), B, H, Wd, Cin, 28, 28, C, d_sigma=1e-3, bf16=True)
+    g, s = _run(A, D, kh, kw, stride, pad, 1.0 / B, dev)
+    Aw = W.bf16_bits_to_f32(A).astype(np.float64); Dw = W.bf16_bits_to_f32(D).astype(np.float64)
+    Ap = np.zeros((B, 30, 30, Cin)); Ap[:, 1:29, 1:29] = Aw
+    rng = np.random.default_rng(1)
+    for _ in range(60):
+        ky, kx, i, o = rng.integers(0, 3), rng.integers(0, 3), rng.integers(0, Cin), rng.integers(0, C)
+        win = Ap[:, ky:ky + 28, kx:kx + 28, i]                     # [B, 28, 28]
+        terms = win * Dw[:, :, :, o]
+        per_sample = terms.sum(axis=(1, 2)) / B
+        mag = np.abs(terms).sum(axis=(1, 2)) / B
+        j = (ky * 3 + kx) * Cin + i
+        assert abs(g[j, o] - per_sample.sum()) <= TOL * mag.sum()
+        assert abs(s[j, o] - (per_sample ** 2).sum()) <= TOL * (mag ** 2).sum()
+
+
+def test_conv2d_rejects_what_it_cannot_do(dev):
+    import torch
+    from paper_1802_06058_amd import vgc
+    lib = vgc.load()
+    a = torch.zeros(2, 8, 8, 8, dtype=torch.bfloat16, device=dev)
+    d = torch.zeros(2, 8, 8, 8, dtype=torch.bfloat16, device=dev)
+    s = torch.zeros(72, 8, device=dev)
+    args = lambda dtype, Cin, C, kh, ph: (dtype, a.data_ptr(), d.data_ptr(), 2, 8, 8, Cin, C, kh, 3, 1, 1, ph, 1, 1.0, None,
+                                          s.data_ptr(), None, 0, None)
+    assert lib.vgc_sqgrad_conv2d(*args(vgc.F32, 8, 8, 3, 1)) == -4          # float32 inputs: not in this form
+    assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 3, 8, 3, 1)) == -2         # Cin not a multiple of 8
+    assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 8, 8, 3, 3)) == -2         # padding as large as the kernel
+    assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 8, 8, 0, 0)) == -2         # empty kernel
+    assert float(s.abs().sum()) == 0.0
