@@ -345,6 +345,36 @@ def bench_sqgrad(dev):
         entry["bound"] = "hbm" if kind == vgc.FC else "mfma"
         res[name] = entry
         del X, D, g, s, ws
+
+    # the same two VGG convolutions from their NHWC inputs (no patch matrix): 1/9 of the input bytes
+    for name, B, H, Cin, C in (("vgg_conv4_2_nhwc_28x28x512_to_512_B64_bf16", 64, 28, 512, 512),
+                               ("vgg_conv3_2_nhwc_56x56x256_to_256_B64_bf16", 64, 56, 256, 256)):
+        gen = torch.Generator(device=dev); gen.manual_seed(1)
+        A = torch.randn((B, H, H, Cin), generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        D = (torch.randn((B, H, H, C), generator=gen, device=dev, dtype=torch.float32) * 1e-3).to(torch.bfloat16)
+        J = 9 * Cin
+        g = torch.empty(J, C, dtype=torch.float32, device=dev)
+        s = torch.empty(J, C, dtype=torch.float32, device=dev)
+        nb = vgc.sqgrad_conv2d_workspace_bytes(vgc.BF16, B, H, H, Cin, C, 3, 3, (1, 1), (1, 1))
+        ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
+        entry = {}
+        for tag, gg in (("s_only", None), ("g_and_s", g)):
+            vgc.sqgrad_conv2d(A, D, 3, 3, (1, 1), (1, 1), 1.0 / B, s, gg, workspace=ws)
+            torch.cuda.synchronize()
+            reps = 5
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                vgc.sqgrad_conv2d(A, D, 3, 3, (1, 1), (1, 1), 1.0 / B, s, gg, workspace=ws)
+            e1.record(); torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            tf = 2.0 * B * H * H * J * C / (ms * 1e-3) / 1e12
+            io = 2.0 * B * H * H * (Cin + C) + (8.0 if gg is not None else 4.0) * J * C
+            entry[tag] = {"ms": round(ms, 4), "TFLOPs": round(tf, 1), "mfma_frac": round(tf / 2500.0, 4),
+                          "algorithmic_GBs": round(io / (ms * 1e-3) / 1e9, 1)}
+        entry["bound"] = "mfma"
+        res[name] = entry
+        del A, D, g, s, ws
     return res
 
 

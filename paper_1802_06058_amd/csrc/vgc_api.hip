@@ -195,9 +195,8 @@ static int conv2d_geometry(int dtype, uint32_t B, uint32_t H, uint32_t W, uint32
     if ((uint64_t)kh * kw * Cin > 0x7FFFFFFFull || (uint64_t)H * W > 0x7FFFFFFFull) { set_error("vgc_sqgrad_conv2d: shape too large"); return VGC_ERR_SIZE; }
     *Ho = (H + 2 * ph - kh) / sh + 1;
     *Wo = (W + 2 * pw - kw) / sw + 1;
-    if (dtype != VGC_BF16) { set_error("vgc_sqgrad_conv2d: bf16 inputs only; build the patch matrix and call vgc_sqgrad"); return VGC_ERR_DTYPE; }
     if (!conv2d_supported(dtype, H, W, Cin, C, *Ho * *Wo)) {
-        set_error("vgc_sqgrad_conv2d: needs Cin and C multiples of 8 and per-sample tensors below 2 GiB");
+        set_error("vgc_sqgrad_conv2d: needs Cin and C multiples of 16 bytes and per-sample tensors below 2 GiB");
         return VGC_ERR_SIZE;
     }
     return VGC_OK;
@@ -208,7 +207,7 @@ size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint
     uint32_t Ho, Wo;
     if (conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, &Ho, &Wo) != VGC_OK) return 0;
     const uint32_t J = kh * kw * Cin;
-    const uint32_t splits = conv_splits(B, J, C);
+    const uint32_t splits = dtype == VGC_BF16 ? conv_splits(B, J, C) : conv_f32_splits(B, J, C);
     return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
 }
 
@@ -225,7 +224,7 @@ int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uin
         return VGC_ERR_ALIGN;
     }
     if (!std::isfinite(c)) { set_error("vgc_sqgrad_conv2d: c is not finite"); return VGC_ERR_PARAM; }
-    return launch_conv2d(act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, Ho, Wo, c, g_out, s_out, workspace, workspace_bytes,
+    return launch_conv2d(dtype, act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, Ho, Wo, c, g_out, s_out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
 }
 

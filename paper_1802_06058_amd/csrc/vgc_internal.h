@@ -163,8 +163,17 @@ int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_
 int launch_conv_f32_tiled(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
                           float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream);
 size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C);
+// Geometry of a 2-d convolution whose patch matrix is never built: U[z, p, j] with p = y Wo + x and
+// j = (ky kw + kx) Cin + i is the input element [z, y sh + ky - ph, x sw + kx - pw, i], or zero outside.
+struct ConvGeom {
+    uint32_t H, W, Cin, kw, sh, sw, ph, pw, Ho, Wo;
+    uint32_t step_y, step_x; // one chunk of kKC positions further: kKC = step_y * Wo + step_x
+};
+
 bool conv2d_supported(int dtype, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t P);
-int launch_conv2d(const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
+int launch_conv2d_f32(const void* act, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+                      float* g_out, float* s_out, void* workspace, size_t workspace_bytes, ConvGeom G, hipStream_t stream);
+int launch_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
                   uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw, uint32_t Ho, uint32_t Wo,
                   float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream);
 int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,

@@ -174,12 +174,15 @@ __device__ __forceinline__ void stage32(float* A, float* Bm, const Chunk32& R, u
 // kConv: X is [B, P, J], D is [B, P, C], samples z_begin .. z_end-1 of this workgroup's split.
 // !kConv: X is [B, J], D is [B, C]; treated as one "sample" with P = B rows and no per-sample square
 //         (the two chains run on the values and on their squares instead).
-template <bool kConv, bool kWantG>
+// kImplicit (with kConv): X is the layer's NHWC input [B, H, W, Cin] seen through the geometry G, J = kh kw Cin; the
+//         lane's piece of 4 columns lies inside one filter tap (Cin is a multiple of 4) and its offset in the input
+//         is formed per chunk from the output position of its row, which is kept incrementally.
+template <bool kConv, bool kWantG, bool kImplicit>
 __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
                                                       uint32_t B, uint32_t P, uint32_t J, uint32_t C,
                                                       uint32_t z_per_split, uint32_t splits, float cg, float cs,
                                                       float* __restrict__ g_out, float* __restrict__ s_out,
-                                                      float* __restrict__ ws) {
+                                                      float* __restrict__ ws, ConvGeom G) {
     __shared__ __attribute__((aligned(16))) float shA[2][kR32 * kPitch32];
     __shared__ __attribute__((aligned(16))) float shB[2][kR32 * kPitch32];
     const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, wm = wave >> 1, wn = wave & 1u;
@@ -201,15 +204,59 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
 #pragma unroll
         for (int b = 0; b < 2; ++b) { acc[a][b] = (f16v){0}; s_acc[a][b] = (f16v){0}; g_acc[a][b] = (f16v){0}; }
 
+    // implicit form: per load, the tap of the lane's columns and the output position of its row
+    uint32_t y0A[2], x0A[2], yA[2], xA[2];
+    int32_t tapX[2], tapOff[2];
+    if (kImplicit) {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const uint32_t idx = tid + 256u * i, row = idx >> 5, colj = j0 + (idx & 31u) * 4u;
+            const uint32_t tap = colj / G.Cin, ky = tap / G.kw;
+            y0A[i] = yA[i] = row / G.Wo;
+            x0A[i] = xA[i] = row - y0A[i] * G.Wo;
+            const int32_t ty = (int32_t)ky - (int32_t)G.ph;
+            tapX[i] = (int32_t)(tap - ky * G.kw) - (int32_t)G.pw;
+            tapOff[i] = (ty * (int32_t)G.W + tapX[i]) * (int32_t)G.Cin + (int32_t)(colj - tap * G.Cin);
+            if (colj >= J) tapX[i] = -0x400000;              // a column past J: never inside the input
+        }
+    }
     Chunk32 R[2];
     uint32_t zl = z_begin, pcl = 0, issued = 0;
     auto issue = [&](int slot_) {
         const bool live = issued < total;
         const uint32_t zz = live ? zl : z_begin;
-        const rsrc_t ra = make_rsrc(X + (size_t)zz * rowsP * J, live ? rowsP * J * 4u : 0u);
         const rsrc_t rb = make_rsrc(D + (size_t)zz * rowsP * C, live ? rowsP * C * 4u : 0u);
-        load32(R[slot_], ra, rb, J, C, pcl * kR32, j0, c0, tid);
-        if (++pcl == n_chunks) { pcl = 0; ++zl; }
+        if (kImplicit) {
+            const uint32_t sample = G.H * G.W * G.Cin;
+            const rsrc_t ra = make_rsrc(X + (size_t)zz * sample, live ? sample * 4u : 0u);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                // rows of the input outside the image give an offset that is negative or past the sample: the load
+                // answers with zeros; columns outside and positions past P are masked
+                const int32_t ys = __mul24((int32_t)yA[i], (int32_t)G.sh), xs = __mul24((int32_t)xA[i], (int32_t)G.sw);
+                const bool inside = ((uint32_t)(xs + tapX[i]) < G.W) & (yA[i] < G.Ho);
+                const int32_t off = __mul24(__mul24(ys, (int32_t)G.W) + xs, (int32_t)G.Cin) + tapOff[i];
+                const uint32_t voff = ((uint32_t)off << 2) | (inside ? 0u : 0xFFFFFFFFu);
+                R[slot_].a[i] = __builtin_bit_cast(f4v, __builtin_amdgcn_raw_buffer_load_b128(ra, (int)voff, 0, 0));
+                const uint32_t idx = tid + 256u * i, row = idx >> 5, col = (idx & 31u) * 4u;
+                R[slot_].b[i] = __builtin_bit_cast(f4v, __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(((pcl * kR32 + row) * C + c0 + col) * 4u), 0, 0));
+            }
+        } else {
+            const rsrc_t ra = make_rsrc(X + (size_t)zz * rowsP * J, live ? rowsP * J * 4u : 0u);
+            load32(R[slot_], ra, rb, J, C, pcl * kR32, j0, c0, tid);
+        }
+        const bool wrap = (++pcl == n_chunks);
+        if (wrap) { pcl = 0; ++zl; }
+        if (kImplicit) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {                     // the lane's row of the next chunk: kR32 positions further
+                const uint32_t x = xA[i] + G.step_x, xw = x - G.Wo;
+                const uint32_t carry = x >= G.Wo ? 1u : 0u;
+                const uint32_t keep = wrap ? 0u : 0xFFFFFFFFu;
+                xA[i] = (min(x, xw) & keep) | (x0A[i] & ~keep);
+                yA[i] = ((yA[i] + G.step_y + carry) & keep) | (y0A[i] & ~keep);
+            }
+        }
         ++issued;
     };
     issue(0);
@@ -314,14 +361,16 @@ int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_
         if (g_out) hipLaunchKernelGGL(k_fc_bf16<true>, dim3((uint32_t)nblk), dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, J, C, cg, cs, g_out, s_out);
         else hipLaunchKernelGGL(k_fc_bf16<false>, dim3((uint32_t)nblk), dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, J, C, cg, cs, g_out, s_out);
     } else {
-        if (g_out) hipLaunchKernelGGL((k_tiled_f32<false, true>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, cg, cs, g_out, s_out, (float*)nullptr);
-        else hipLaunchKernelGGL((k_tiled_f32<false, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, cg, cs, g_out, s_out, (float*)nullptr);
+        if (g_out) hipLaunchKernelGGL((k_tiled_f32<false, true, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
+        else hipLaunchKernelGGL((k_tiled_f32<false, false, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
     }
     return hip_check(hipGetLastError(), "launch fc tiled");
 }
 
-int launch_conv_f32_tiled(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
-                          float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+template <bool kImplicit>
+static int launch_conv_f32_any(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+                               float* g_out, float* s_out, void* workspace, size_t workspace_bytes, const ConvGeom& G,
+                               hipStream_t stream) {
     uint32_t splits = conv_f32_splits(B, J, C);
     if (splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * J * C * sizeof(float))) splits = 1;
     const uint32_t zper = (B + splits - 1) / splits;
@@ -330,10 +379,22 @@ int launch_conv_f32_tiled(const void* X, const void* D, uint32_t B, uint32_t P, 
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
-    if (g_out) hipLaunchKernelGGL((k_tiled_f32<true, true>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
-    else hipLaunchKernelGGL((k_tiled_f32<true, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws);
+    if (g_out) hipLaunchKernelGGL((k_tiled_f32<true, true, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
+    else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
     if (splits > 1) launch_sqgrad_reduce(ws, splits, (size_t)J * C, cg, cs, g_out, s_out, stream);
     return hip_check(hipGetLastError(), "launch k_tiled_f32");
+}
+
+int launch_conv_f32_tiled(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+                          float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    return launch_conv_f32_any<false>(X, D, B, P, J, C, c, g_out, s_out, workspace, workspace_bytes, ConvGeom{}, stream);
+}
+
+int launch_conv2d_f32(const void* act, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+                      float* g_out, float* s_out, void* workspace, size_t workspace_bytes, ConvGeom G, hipStream_t stream) {
+    G.step_y = kR32 / G.Wo;
+    G.step_x = kR32 % G.Wo;
+    return launch_conv_f32_any<true>(act, D, B, P, J, C, c, g_out, s_out, workspace, workspace_bytes, G, stream);
 }
 
 }  // namespace vgc

@@ -86,13 +86,6 @@ struct ChunkStream {
     }
 };
 
-// Geometry of a 2-d convolution whose patch matrix is never built: U[z, p, j] with p = y Wo + x and
-// j = (ky kw + kx) Cin + i is the input element [z, y sh + ky - ph, x sw + kx - pw, i], or zero outside.
-struct ConvGeom {
-    uint32_t H, W, Cin, kw, sh, sw, ph, pw, Ho, Wo;
-    uint32_t step_y, step_x; // one chunk of kKC positions further: kKC = step_y * Wo + step_x
-};
-
 // BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.  kImplicit: U is the layer's NHWC input seen
 // through the geometry G (J = kh kw Cin), otherwise a [B, P, J] matrix.
 template <int BM, int BN, bool kWantG, bool kImplicit>
@@ -486,17 +479,20 @@ int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint3
 
 bool conv2d_supported(int dtype, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t P) {
     const uint64_t limit = 0x7FFFFFFFull;               // buffer ranges and offsets are 32-bit
-    // the kernel's address arithmetic multiplies (y sh W + x sw) by Cin with 24-bit multiplies
+    // the kernels' address arithmetic multiplies (y sh W + x sw) by Cin with 24-bit multiplies
     const uint64_t m24 = 1u << 23;
-    return dtype == VGC_BF16 && (Cin % 8 == 0) && (C % 8 == 0) && (uint64_t)H * W * Cin * 2 < limit &&
-           (uint64_t)(P + 64) * C * 2 < limit && (uint64_t)(H + 64) * (W + 64) < m24 && Cin < m24;
+    const uint64_t es = dtype == VGC_BF16 ? 2 : 4, piece = 16 / es;
+    return (dtype == VGC_BF16 || dtype == VGC_F32) && (Cin % piece == 0) && (C % piece == 0) &&
+           (uint64_t)H * W * Cin * es < limit && (uint64_t)(P + 64) * C * es < limit &&
+           (uint64_t)(H + 64) * (W + 64) < m24 && Cin < m24;
 }
 
-int launch_conv2d(const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
+int launch_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
                   uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw, uint32_t Ho, uint32_t Wo,
                   float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
     ConvGeom G;
     G.H = H; G.W = W; G.Cin = Cin; G.kw = kw; G.sh = sh; G.sw = sw; G.ph = ph; G.pw = pw; G.Ho = Ho; G.Wo = Wo;
+    if (dtype == VGC_F32) return launch_conv2d_f32(act, D, B, Ho * Wo, kh * kw * Cin, C, c, g_out, s_out, workspace, workspace_bytes, G, stream);
     G.step_y = kKC / Wo;
     G.step_x = kKC % Wo;
     return launch_conv_any<true>(act, D, B, Ho * Wo, kh * kw * Cin, C, c, g_out, s_out, workspace, workspace_bytes, G, stream);

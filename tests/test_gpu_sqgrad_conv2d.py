@@ -1,6 +1,6 @@
 """vgc_sqgrad_conv2d (the convolution statistic read from the NHWC input, no patch matrix) against the
 float64 oracle, and against vgc_sqgrad on the materialised patch matrix.  Tolerance for bfloat16
-inputs: 1e-2, measured like the conv form's (against the magnitudes summed)."""
+inputs: 1e-2, for float32 inputs 1e-5, measured like the conv form's (against the magnitudes summed)."""
 import numpy as np
 import pytest
 
@@ -9,6 +9,7 @@ from paper_1802_06058_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 TOL = 1e-2
+RTOL = {"bf16": 1e-2, "f32": 1e-5}
 
 
 @pytest.fixture(scope="module")
@@ -25,9 +26,15 @@ def _bf(a, dev):
     return torch.from_numpy(np.ascontiguousarray(a)).to(dev).view(torch.bfloat16)
 
 
+def _in(a, dev):
+    import torch
+    return _bf(a, dev) if a.dtype == np.uint16 else torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+
 def _run(A, D, kh, kw, stride, pad, c, dev, want_g=True, use_workspace=True):
     import torch
     from paper_1802_06058_amd import vgc
+    dtype = vgc.BF16 if A.dtype == np.uint16 else vgc.F32
     B, H, Wd, Cin = A.shape
     C = D.shape[3]
     J = kh * kw * Cin
@@ -35,10 +42,10 @@ def _run(A, D, kh, kw, stride, pad, c, dev, want_g=True, use_workspace=True):
     g = torch.full((J, C), float("nan"), dtype=torch.float32, device=dev) if want_g else None
     ws = None
     if use_workspace:
-        nb = vgc.sqgrad_conv2d_workspace_bytes(vgc.BF16, B, H, Wd, Cin, C, kh, kw, stride, pad)
+        nb = vgc.sqgrad_conv2d_workspace_bytes(dtype, B, H, Wd, Cin, C, kh, kw, stride, pad)
         if nb:
             ws = torch.full((nb,), 0xFF, dtype=torch.uint8, device=dev)
-    vgc.sqgrad_conv2d(_bf(A, dev), _bf(D, dev), kh, kw, stride, pad, c, s, g, workspace=ws)
+    vgc.sqgrad_conv2d(_in(A, dev), _in(D, dev), kh, kw, stride, pad, c, s, g, workspace=ws)
     torch.cuda.synchronize()
     return (g.cpu().numpy() if want_g else None), s.cpu().numpy()
 
@@ -65,12 +72,17 @@ GEOMS = [  # B, H, W, Cin, C, kh, kw, stride, pad
 ]
 
 
+@pytest.mark.parametrize("prec", ["bf16", "f32"])
 @pytest.mark.parametrize("geom", GEOMS)
-def test_conv2d_matches_oracle(dev, geom):
+def test_conv2d_matches_oracle(dev, geom, prec):
     B, H, Wd, Cin, C, kh, kw, stride, pad = geom
+    TOL = RTOL[prec]
     Ho, Wo = O.conv_out_size(H, kh, stride[0], pad[0]), O.conv_out_size(Wd, kw, stride[1], pad[1])
-    A, D = W.conv2d_inputs(41, geom[:7], B, H, Wd, Cin, Ho, Wo, C, d_sigma=0.02, bf16=True)
-    Aw, Dw = W.bf16_bits_to_f32(A).astype(np.float64), W.bf16_bits_to_f32(D).astype(np.float64)
+    A, D = W.conv2d_inputs(41, geom[:7], B, H, Wd, Cin, Ho, Wo, C, d_sigma=0.02, bf16=prec == "bf16")
+    if prec == "bf16":
+        Aw, Dw = W.bf16_bits_to_f32(A).astype(np.float64), W.bf16_bits_to_f32(D).astype(np.float64)
+    else:
+        Aw, Dw = A.astype(np.float64), D.astype(np.float64)
     c = 1.0 / B
     g64, s64 = O.sqgrad_conv_nhwc(Aw, Dw, kh, kw, stride, pad, c)
     Uabs = _patches(np.abs(Aw), kh, kw, stride, pad, Ho, Wo)
@@ -136,8 +148,9 @@ def test_conv2d_rejects_what_it_cannot_do(dev):
     s = torch.zeros(72, 8, device=dev)
     args = lambda dtype, Cin, C, kh, ph: (dtype, a.data_ptr(), d.data_ptr(), 2, 8, 8, Cin, C, kh, 3, 1, 1, ph, 1, 1.0, None,
                                           s.data_ptr(), None, 0, None)
-    assert lib.vgc_sqgrad_conv2d(*args(vgc.F32, 8, 8, 3, 1)) == -4          # float32 inputs: not in this form
-    assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 3, 8, 3, 1)) == -2         # Cin not a multiple of 8
+    assert lib.vgc_sqgrad_conv2d(*args(7, 8, 8, 3, 1)) == -4                # unknown dtype
+    assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 4, 8, 3, 1)) == -2         # Cin not a multiple of 8 bfloat16
+    assert lib.vgc_sqgrad_conv2d(*args(vgc.F32, 6, 8, 3, 1)) == -2          # Cin not a multiple of 4 floats
     assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 8, 8, 3, 3)) == -2         # padding as large as the kernel
     assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 8, 8, 0, 0)) == -2         # empty kernel
     assert float(s.abs().sum()) == 0.0
