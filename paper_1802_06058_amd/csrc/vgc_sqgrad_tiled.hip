@@ -59,30 +59,37 @@ template <int N> __device__ __forceinline__ void wait_loads_but() {
 // Scalar cursor over the chunks of one operand ([B, P, W] bf16): the buffer descriptor covers the rest
 // of the current sample from the chunk's first row on, so rows past P read as zeros.
 struct ChunkStream {
-    uint64_t sample;        // address of the current sample's matrix
-    uint64_t cur;           // address of the chunk's first row
-    uint32_t rem;           // bytes from there to the end of the sample
-    uint32_t chunk_bytes, sample_bytes;
-    __device__ __forceinline__ void init(const uint16_t* base, uint32_t z, uint32_t P, uint32_t W) {
-        chunk_bytes = kKC * W * 2u;
+    uint32_t lo, hi, rem;   // the current chunk: address of its first row (48 bits), bytes from there to the end of the sample
+    uint32_t chunk_bytes;   // from one chunk to the next inside a sample
+    uint32_t wrap_bytes;    // from the last chunk of a sample to the first of the next
+    uint32_t sample_bytes;
+    // rows_per_chunk = 0: the descriptor stays on the sample's first row (the implicit form addresses through offsets)
+    __device__ __forceinline__ void init(const uint16_t* base, uint32_t z, uint32_t P, uint32_t W, uint32_t rows_per_chunk,
+                                         uint32_t n_chunks) {
+        chunk_bytes = rows_per_chunk * W * 2u;
         sample_bytes = P * W * 2u;
-        sample = reinterpret_cast<uint64_t>(base) + (uint64_t)z * sample_bytes;
-        cur = sample;
+        wrap_bytes = sample_bytes - (n_chunks - 1u) * chunk_bytes;
+        const uint64_t addr = reinterpret_cast<uint64_t>(base) + (uint64_t)z * sample_bytes;
+        lo = (uint32_t)addr;
+        hi = (uint32_t)(addr >> 32) & 0xFFFFu;
         rem = sample_bytes;
     }
-    __device__ __forceinline__ i4v rsrc(bool live) const {
+    __device__ __forceinline__ i4v rsrc() const {
         i4v r;
-        r[0] = (int)(uint32_t)cur;
-        r[1] = (int)((uint32_t)(cur >> 32) & 0xFFFFu);
-        r[2] = live ? (int)rem : 0;
+        r[0] = (int)lo;
+        r[1] = (int)hi;
+        r[2] = (int)rem;
         r[3] = 0x00020000;
         return r;
     }
-    __device__ __forceinline__ void next(bool new_sample) {
-        const uint64_t following = sample + sample_bytes;    // selects, not branches: the loop body stays one block
-        sample = new_sample ? following : sample;
-        cur = new_sample ? following : cur + chunk_bytes;
-        rem = new_sample ? sample_bytes : rem - chunk_bytes;
+    // Moves on one chunk (into the next sample if new_sample).  Past the last chunk (!live) the range becomes and
+    // stays empty.  Scalar adds and selects only: the loop body stays one block.
+    __device__ __forceinline__ void next(bool new_sample, bool live) {
+        const uint32_t inc = new_sample ? wrap_bytes : chunk_bytes;
+        lo += inc;
+        hi += (lo < inc) ? 1u : 0u;
+        const uint32_t r = new_sample ? sample_bytes : rem - chunk_bytes;
+        rem = live ? r : 0u;
     }
 };
 
@@ -201,17 +208,15 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     // ---- the stream of chunk requests ----
     ChunkStream sa, sb;
     if (kImplicit) {
-        sa.init(U, z_begin, G.H * G.W, G.Cin);           // the descriptor covers the whole input of the sample
-        sa.chunk_bytes = 0;
+        sa.init(U, z_begin, G.H * G.W, G.Cin, 0, n_chunks);   // the descriptor covers the whole input of the sample
     } else {
-        sa.init(U, z_begin, P, J);
+        sa.init(U, z_begin, P, J, kKC, n_chunks);
     }
-    sb.init(D, z_begin, P, C);
+    sb.init(D, z_begin, P, C, kKC, n_chunks);
     uint32_t pcl = 0, issued = 0, bo_fill = 0;           // position in the sample, chunks requested, ring buffer (byte offset)
     auto next_buf = [&](uint32_t bo) -> uint32_t { return bo + kBufBytes == (uint32_t)kRingBytes ? 0u : bo + kBufBytes; };
     auto issue = [&]() {                                 // request the next chunk into the next ring buffer
-        const bool live = issued < total;                // past the last chunk the range is empty: zeros arrive
-        const i4v ra = sa.rsrc(live), rb = sb.rsrc(live);
+        const i4v ra = sa.rsrc(), rb = sb.rsrc();        // past the last chunk the ranges are empty: zeros arrive
 #pragma unroll
         for (int j = 0; j < kPerA; ++j) {
             uint32_t voff;
@@ -246,8 +251,9 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                 yA[j] = ((yA[j] + G.step_y + carry) & keep) | (y0A[j] & ~keep);
             }
         }
-        sa.next(wrap);
-        sb.next(wrap);
+        const bool live = issued < total;
+        sa.next(wrap, live);
+        sb.next(wrap, live);
         bo_fill = next_buf(bo_fill);
     };
     auto sample_end = [&]() {                            // G_z is complete in acc: square into s, add into g, clear
@@ -270,7 +276,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     // count of the pipelined loop is rounded up to a multiple of its unroll factor; the surplus chunks are
     // all zeros and add nothing.
     constexpr int kInFlight = (kNB - 2) * kPer;
-    uint32_t pc = 0, zdone = z_begin;
+    uint32_t left = n_chunks;                            // chunks until the current sample's product is complete
 #pragma unroll 1
     for (int i = 0; i < kNB; ++i) issue();
     wait_loads_but<kInFlight>();                         // chunks 0 and 1 have landed
@@ -311,7 +317,8 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);      // two LDS reads
                 }
                 bo_next = next_buf(bo_next);
-                if (++pc == n_chunks && zdone < z_end) { pc = 0; ++zdone; sample_end(); }
+                // (a surplus chunk may complete a "sample" of zeros when P fits one chunk: it adds nothing)
+                if (--left == 0) { left = n_chunks; sample_end(); }
                 wait_loads_but<kInFlight>();             // chunk q+2 has landed (this wave's pieces)
                 __syncthreads();
             }
@@ -333,7 +340,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                     for (int nt = 0; nt < 2; ++nt)
                         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
             }
-            if (++pc == n_chunks) { pc = 0; sample_end(); }
+            if (--left == 0) { left = n_chunks; sample_end(); }
             bo_cur = next_buf(bo_cur);
             wait_loads_but<kInFlight>();                 // chunk q+1 has landed (this wave's pieces)
             __syncthreads();                             // ... everybody's, and chunk q's buffer is free
