@@ -190,6 +190,7 @@ def main():
     out["stages"]["model_parameter_sets"] = bench_model_sets(dev, a.alpha, zeta)
     if not a.no_sqgrad:
         out["stages"]["sqgrad"] = bench_sqgrad(dev)
+        out["stages"]["vgg16_iteration"] = bench_vgg_iteration(dev, zeta)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(pool[0], a, cfg, min(a.cpu_sample, N))
     print(json.dumps(out))
@@ -376,6 +377,92 @@ def bench_sqgrad(dev):
         res[name] = entry
         del A, D, g, s, ws
     return res
+
+
+def bench_vgg_iteration(dev, zeta):
+    """One worker's whole compression step on the VGG-16-shaped configuration (C4: batch 64, bfloat16 activations):
+    the statistic s of every layer (convolutions from their NHWC inputs, the 3-channel first layer through its patch
+    matrix, FC layers in the FC form; g comes from the framework's own backward pass and is synthetic here),
+    then select + pack over the 138 M parameters, then the decode of 8 such messages fused with a Momentum SGD step."""
+    import torch
+    from paper_1802_06058_amd import vgc, workloads as W
+    B = 64
+    convs = [(3, 64, 224), (64, 64, 224), (64, 128, 112), (128, 128, 112), (128, 256, 56), (256, 256, 56), (256, 256, 56),
+             (256, 512, 28), (512, 512, 28), (512, 512, 28), (512, 512, 14), (512, 512, 14), (512, 512, 14)]
+    fcs = [(25088, 4096), (4096, 4096), (4096, 1000)]
+    gen = torch.Generator(device=dev); gen.manual_seed(5)
+    rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
+
+    def timed(fn, reps=3):
+        fn(); torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record(); torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    layers, t_stat, flops = [], 0.0, 0.0
+    for cin, cout, sp in convs:
+        D = rnd(B, sp, sp, cout) * 1e-3
+        J = 9 * cin
+        s = torch.empty(J, cout, dtype=torch.float32, device=dev)
+        if cin % 8 == 0:
+            A = rnd(B, sp, sp, cin)
+            nb = vgc.sqgrad_conv2d_workspace_bytes(vgc.BF16, B, sp, sp, cin, cout, 3, 3, (1, 1), (1, 1))
+            ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
+            ms = timed(lambda: vgc.sqgrad_conv2d(A, D, 3, 3, (1, 1), (1, 1), 1.0 / B, s, None, workspace=ws))
+            form = "nhwc"
+        else:                                             # 3 input channels: patch matrix [B, P, 27] (padded to 32 columns)
+            A = rnd(B, sp * sp, 32)
+            A[:, :, 27:] = 0
+            J = 32
+            s = torch.empty(J, cout, dtype=torch.float32, device=dev)
+            nb = vgc.sqgrad_workspace_bytes(vgc.CONV, vgc.BF16, B, sp * sp, J, cout)
+            ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
+            ms = timed(lambda: vgc.sqgrad(vgc.CONV, A, D.view(B, sp * sp, cout), 1.0 / B, s, None, workspace=ws))
+            form = "patches"
+        fl = 2.0 * B * sp * sp * 9 * cin * cout
+        layers.append({"layer": f"conv {cin}->{cout} @{sp}", "form": form, "ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1)})
+        t_stat += ms; flops += fl
+        del A, D, s, ws
+    for fin, fout in fcs:
+        X, D = rnd(B, fin), rnd(B, fout) * 1e-3
+        s = torch.empty(fin, fout, dtype=torch.float32, device=dev)
+        ms = timed(lambda: vgc.sqgrad(vgc.FC, X, D, 1.0 / B, s, None))
+        layers.append({"layer": f"fc {fin}x{fout}", "form": "fc", "ms": round(ms, 4),
+                       "GBs": round(4.0 * fin * fout / ms / 1e6, 1)})
+        t_stat += ms
+        del X, D, s
+
+    cfg = W.CONFIGS["C4"]
+    sizes = [L["size"] for L in cfg["layers"]]
+    plan = vgc.Plan(W.groups_from_sizes(sizes), dev)
+    n = plan.n
+    sig = torch.from_numpy(np.repeat(W.layer_sigmas(cfg["seed"], len(sizes)), sizes).astype(np.float32)).to(dev)
+    z = torch.randn(n, generator=gen, device=dev)
+    chi = torch.zeros(n, device=dev)
+    for _ in range(B - 1):
+        w = torch.randn(n, generator=gen, device=dev); chi += w * w
+    g = sig * z / B ** 0.5
+    s = sig * sig * (chi + z * z) / (B * B)
+    del z, chi, sig
+    r = torch.zeros(n, dtype=torch.float32, device=dev); v = torch.zeros(n, dtype=torch.float32, device=dev)
+    scratch, hdrs, status = plan.new_scratch(), plan.new_headers(), plan.new_status()
+    words = torch.empty(n, dtype=torch.int32, device=dev)
+
+    def select_pack():
+        r.zero_(); v.zero_()
+        vgc.accumulate_select(g, s, r, v, plan, 1.0, zeta, scratch)
+        vgc.pack(plan, scratch, words, hdrs, status)
+    t_sp = timed(select_pack) - timed(lambda: (r.zero_(), v.zero_()))
+    total = vgc.read_status(status)[0]
+    param, mom = torch.zeros(n, device=dev), torch.zeros(n, device=dev)
+    t_up = timed(lambda: vgc.unpack_apply([words] * 8, [total] * 8, [hdrs] * 8, plan, 0.125, param, mom,
+                                          kind=vgc.MOMENTUM_SGD, lr=1e-3, momentum=0.9))
+    return {"batch": B, "n_params": n, "statistic_ms": round(t_stat, 3), "statistic_conv_TFLOPs": round(flops / 1e12, 3),
+            "select_plus_pack_ms": round(t_sp, 3), "sent_fraction": round(total / n, 4),
+            "decode8_plus_momentum_sgd_ms": round(t_up, 3), "total_ms": round(t_stat + t_sp + t_up, 3), "layers": layers}
 
 
 def cpu_baseline(pair, a, cfg, sample):

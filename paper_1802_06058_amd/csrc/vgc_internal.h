@@ -152,6 +152,7 @@ int launch_sqgrad_simple(int kind, int dtype, const void* X, const void* D, uint
 
 // LDS-tiled kernels (vgc_sqgrad_tiled.hip, vgc_sqgrad_fc.hip)
 uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C);
+size_t conv_workspace_bytes(uint32_t B, uint32_t P, uint32_t J, uint32_t C);
 bool conv_tiled_supported(int dtype, uint32_t P, uint32_t J, uint32_t C);
 void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg, float cs, float* g_out, float* s_out,
                           hipStream_t stream);

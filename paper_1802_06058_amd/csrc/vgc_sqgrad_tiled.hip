@@ -70,17 +70,30 @@ struct ChunkStream {
         sample_bytes = P * W * 2u;
         wrap_bytes = sample_bytes - (n_chunks - 1u) * chunk_bytes;
         const uint64_t addr = reinterpret_cast<uint64_t>(base) + (uint64_t)z * sample_bytes;
-        lo = (uint32_t)addr;
-        hi = (uint32_t)(addr >> 32) & 0xFFFFu;
-        rem = sample_bytes;
+        // everything here is uniform over the workgroup; pin it to scalar registers
+        lo = __builtin_amdgcn_readfirstlane((uint32_t)addr);
+        hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32) & 0xFFFFu);
+        rem = __builtin_amdgcn_readfirstlane(sample_bytes);
+        chunk_bytes = __builtin_amdgcn_readfirstlane(chunk_bytes);
+        wrap_bytes = __builtin_amdgcn_readfirstlane(wrap_bytes);
+        sample_bytes = __builtin_amdgcn_readfirstlane(sample_bytes);
     }
     __device__ __forceinline__ i4v rsrc() const {
         i4v r;
-        r[0] = (int)lo;
-        r[1] = (int)hi;
-        r[2] = (int)rem;
+        r[0] = (int)__builtin_amdgcn_readfirstlane(lo);          // uniform values; the asm operand must be scalar registers
+        r[1] = (int)__builtin_amdgcn_readfirstlane(hi);
+        r[2] = (int)__builtin_amdgcn_readfirstlane(rem);
         r[3] = 0x00020000;
         return r;
+    }
+    __device__ __forceinline__ void skip(uint32_t chunks) {      // start `chunks` chunks into the sample
+        const uint32_t off = chunks * chunk_bytes;               // below the sample's size, which is below 2^31
+        lo += off;
+        hi += (lo < off) ? 1u : 0u;
+        rem -= off;
+        lo = __builtin_amdgcn_readfirstlane(lo);
+        hi = __builtin_amdgcn_readfirstlane(hi);
+        rem = __builtin_amdgcn_readfirstlane(rem);
     }
     // Moves on one chunk (into the next sample if new_sample).  Past the last chunk (!live) the range becomes and
     // stays empty.  Scalar adds and selects only: the loop body stays one block.
@@ -99,7 +112,7 @@ template <int BM, int BN, bool kWantG, bool kImplicit>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
 void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                  uint32_t B, uint32_t P, uint32_t J, uint32_t C,
-                 uint32_t z_per_split, uint32_t splits, float cg, float cs,
+                 uint32_t z_per_split, uint32_t splits, uint32_t split_p, float cg, float cs,
                  float* __restrict__ g_out, float* __restrict__ s_out, float* __restrict__ ws, ConvGeom G) {
     constexpr int NW = (BM / 64) * (BN / 64);
     constexpr int kABytes = kKC * BM * 2, kBBytes = kKC * BN * 2, kBufBytes = kABytes + kBBytes;
@@ -126,10 +139,15 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     const uint32_t logical = xcd * per + min(xcd, rem) + slot;
     const uint32_t tile_c = logical % tiles_c, tile_j = (logical / tiles_c) % tiles_j, split = logical / (tiles_c * tiles_j);
     const uint32_t j0 = tile_j * BM, c0 = tile_c * BN;
-    const uint32_t z_begin = split * z_per_split;
-    const uint32_t z_end = min(B, z_begin + z_per_split);
+    // split_p > 1: the workgroup owns part `part` of the positions of the single sample split / split_p and
+    // leaves the unsquared partial product in the workspace (the sum over the parts has to precede the square)
     const uint32_t n_chunks = (P + kKC - 1) / kKC;
-    const uint32_t total = (z_end - z_begin) * n_chunks;
+    const uint32_t part = split_p > 1 ? split % split_p : 0u;
+    const uint32_t chunks_per_part = (n_chunks + split_p - 1) / split_p;
+    const uint32_t c_begin = min(n_chunks, part * chunks_per_part);
+    const uint32_t z_begin = split_p > 1 ? split / split_p : split * z_per_split;
+    const uint32_t z_end = split_p > 1 ? z_begin + 1u : min(B, z_begin + z_per_split);
+    const uint32_t total = split_p > 1 ? min(n_chunks, c_begin + chunks_per_part) - c_begin : (z_end - z_begin) * n_chunks;
 
     // the compiler must see a store to the array: everything else arrives behind its back
     reinterpret_cast<uint32_t*>(sh + kRingBytes)[tid & 255u] = 0u;
@@ -151,8 +169,9 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         const uint32_t piece = (((p >> 2) ^ swizzle<BM>(row)) << 2) | (p & 3u);
         if (kImplicit) {
             const uint32_t col = j0 + piece * 8u, tap = col / G.Cin, ky = tap / G.kw;
-            y0A[j] = yA[j] = row / G.Wo;
-            x0A[j] = xA[j] = row - y0A[j] * G.Wo;
+            const uint32_t pos0 = c_begin * kKC + row;      // the lane's row in the workgroup's first chunk
+            y0A[j] = yA[j] = pos0 / G.Wo;
+            x0A[j] = xA[j] = pos0 - y0A[j] * G.Wo;
             tapY[j] = (int32_t)ky - (int32_t)G.ph;
             tapX[j] = (int32_t)(tap - ky * G.kw) - (int32_t)G.pw;
             // input offset (elements) of the tap relative to the row's own (y sh, x sw), plus the channel
@@ -213,7 +232,9 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         sa.init(U, z_begin, P, J, kKC, n_chunks);
     }
     sb.init(D, z_begin, P, C, kKC, n_chunks);
-    uint32_t pcl = 0, issued = 0, bo_fill = 0;           // position in the sample, chunks requested, ring buffer (byte offset)
+    sa.skip(c_begin);
+    sb.skip(c_begin);
+    uint32_t pcl = c_begin, issued = 0, bo_fill = 0;           // position in the sample, chunks requested, ring buffer (byte offset)
     auto next_buf = [&](uint32_t bo) -> uint32_t { return bo + kBufBytes == (uint32_t)kRingBytes ? 0u : bo + kBufBytes; };
     auto issue = [&]() {                                 // request the next chunk into the next ring buffer
         const i4v ra = sa.rsrc(), rb = sb.rsrc();        // past the last chunk the ranges are empty: zeros arrive
@@ -276,7 +297,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     // count of the pipelined loop is rounded up to a multiple of its unroll factor; the surplus chunks are
     // all zeros and add nothing.
     constexpr int kInFlight = (kNB - 2) * kPer;
-    uint32_t left = n_chunks;                            // chunks until the current sample's product is complete
+    uint32_t left = split_p > 1 ? 0u : n_chunks;         // chunks until the current sample's product is complete (0: never)
 #pragma unroll 1
     for (int i = 0; i < kNB; ++i) issue();
     wait_loads_but<kInFlight>();                         // chunks 0 and 1 have landed
@@ -349,11 +370,13 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     }
     wait_loads_but<0>();                                 // nothing may still be landing when the workgroup ends
 
-    // ---- epilogue: scaled result, or unscaled partial sums for the fixed-order reduction ----
+    // ---- epilogue: scaled result, or unscaled partial sums for the fixed-order reduction, or (split_p > 1) the
+    // partial per-sample product ----
     const bool direct = (splits == 1);
     const size_t JC = (size_t)J * C;
     float* so = direct ? s_out : ws + (size_t)split * 2 * JC;
     float* go = direct ? g_out : ws + (size_t)split * 2 * JC + JC;
+    if (split_p > 1) so = ws + (size_t)split * JC;
     const float fs = direct ? cs : 1.0f, fg = direct ? cg : 1.0f;
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt)
@@ -365,8 +388,12 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                 const uint32_t row = j0 + wm * 64 + mt * 32 + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
                 if (row < J && col < C) {
                     const size_t o = (size_t)row * C + col;
-                    __builtin_nontemporal_store(fs * s_acc[mt][nt][i], so + o);
-                    if (kWantG) __builtin_nontemporal_store(fg * g_acc[mt][nt][i], go + o);
+                    if (split_p > 1) {
+                        __builtin_nontemporal_store(acc[mt][nt][i], so + o);
+                    } else {
+                        __builtin_nontemporal_store(fs * s_acc[mt][nt][i], so + o);
+                        if (kWantG) __builtin_nontemporal_store(fg * g_acc[mt][nt][i], go + o);
+                    }
                 }
             }
         }
@@ -398,12 +425,36 @@ static ConvTile conv_tile(uint32_t J, uint32_t C) {
     return t;
 }
 
-// How many ways to split the samples.  Workgroups run in rounds of `slots` (compute units x resident
-// workgroups); the cost of a choice is rounds x samples per workgroup, plus one pass over the partial
-// sums per split for the reduction (weighted as a fraction of one sample's work on a tile).
-uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C) {
-    const ConvTile t = conv_tile(J, C);
-    const uint64_t tiles = (uint64_t)((J + t.bm - 1) / t.bm) * ((C + t.bn - 1) / t.bn);
+// Sums the parts of every sample's product, then squares and sums over the samples, in a fixed order: a
+// workgroup owns 16 outputs; thread (output, lane q) takes samples q, q + 16, ..., and the 16 lanes' sums are
+// added in lane order.
+__global__ __launch_bounds__(256) void k_sqgrad_reduce_parts(const float* __restrict__ ws, uint32_t B, uint32_t split_p, size_t JC,
+                                                             float cg, float cs, float* __restrict__ g_out,
+                                                             float* __restrict__ s_out) {
+    __shared__ float sh_s[16][17], sh_g[16][17];
+    const uint32_t il = threadIdx.x & 15u, q = threadIdx.x >> 4;
+    const size_t i = (size_t)blockIdx.x * 16 + il;
+    float s = 0.f, g = 0.f;
+    if (i < JC) {
+        for (uint32_t z = q; z < B; z += 16) {
+            float G = 0.f;
+            for (uint32_t k = 0; k < split_p; ++k) G += ws[((size_t)z * split_p + k) * JC + i];
+            s = __builtin_fmaf(G, G, s);
+            g += G;
+        }
+    }
+    sh_s[q][il] = s;
+    sh_g[q][il] = g;
+    __syncthreads();
+    if (q == 0 && i < JC) {
+        float st = 0.f, gt = 0.f;
+        for (int k = 0; k < 16; ++k) { st += sh_s[k][il]; gt += sh_g[k][il]; }
+        s_out[i] = cs * st;
+        if (g_out) g_out[i] = cg * gt;
+    }
+}
+
+static uint64_t conv_slots(const ConvTile& t) {
     static int n_cu = 0;
     if (n_cu == 0) {
         int dev = 0, v = 0;
@@ -411,7 +462,16 @@ uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C) {
         else n_cu = 256;
     }
     const uint64_t waves_per_wg = (uint64_t)(t.bm / 64) * (t.bn / 64);
-    const uint64_t slots = (uint64_t)n_cu * (8 / waves_per_wg);
+    return (uint64_t)n_cu * (8 / waves_per_wg);
+}
+
+// How many ways to split the samples.  Workgroups run in rounds of `slots` (compute units x resident
+// workgroups); the cost of a choice is rounds x samples per workgroup, plus one pass over the partial
+// sums per split for the reduction (weighted as a fraction of one sample's work on a tile).
+uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C) {
+    const ConvTile t = conv_tile(J, C);
+    const uint64_t tiles = (uint64_t)((J + t.bm - 1) / t.bm) * ((C + t.bn - 1) / t.bn);
+    const uint64_t slots = conv_slots(t);
     double best = 1e300;
     uint32_t best_s = 1;
     for (uint32_t s = 1; s <= B; ++s) {
@@ -424,11 +484,33 @@ uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C) {
     return best_s;
 }
 
+// When [J, C] has so few tiles that one workgroup per (tile, sample) fills less than half of the chip's
+// workgroup slots, the positions of a sample are split as well, into as many parts as fit one round (at
+// least eight chunks per part).  1 = no split over positions.  (Between half a round and a full one the
+// split does not pay: workgroups that have a compute unit to themselves run faster.)
+uint32_t conv_split_p(uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
+    const ConvTile t = conv_tile(J, C);
+    const uint64_t tiles = (uint64_t)((J + t.bm - 1) / t.bm) * ((C + t.bn - 1) / t.bn);
+    const uint64_t slots = conv_slots(t);
+    const uint32_t n_chunks = (P + kKC - 1) / kKC;
+    if (tiles * B * 2 > slots || n_chunks < 16) return 1;
+    const uint64_t sp = slots / (tiles * B);
+    return (uint32_t)(sp < n_chunks / 8 ? sp : n_chunks / 8);
+}
+
+// Workspace the tiled bf16 conv kernel wants for a shape (0: none).
+size_t conv_workspace_bytes(uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
+    const uint32_t sp = conv_split_p(B, P, J, C);
+    if (sp > 1) return (size_t)B * sp * J * C * sizeof(float);
+    const uint32_t splits = conv_splits(B, J, C);
+    return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
+}
+
 size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
     if (kind != VGC_CONV) return 0;
+    if (conv_tiled_supported(dtype, P, J, C)) return conv_workspace_bytes(B, P, J, C);
     uint32_t splits = 1;
-    if (conv_tiled_supported(dtype, P, J, C)) splits = conv_splits(B, J, C);
-    else if (dtype == VGC_F32 && conv_f32_tiled_supported(P, J, C)) splits = conv_f32_splits(B, J, C);
+    if (dtype == VGC_F32 && conv_f32_tiled_supported(P, J, C)) splits = conv_f32_splits(B, J, C);
     return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
 }
 
@@ -446,15 +528,16 @@ void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg,
 
 template <int BM, int BN, bool kImplicit>
 static void launch_conv_bf16(uint32_t nblk, hipStream_t stream, const void* X, const void* D, uint32_t B, uint32_t P,
-                             uint32_t J, uint32_t C, uint32_t zper, uint32_t splits, float cg, float cs,
+                             uint32_t J, uint32_t C, uint32_t zper, uint32_t splits, uint32_t split_p, float cg, float cs,
                              float* g_out, float* s_out, float* ws, const ConvGeom& G) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
-    if (g_out)
+    // with the positions split the partial products are unsquared: the variant without g serves both
+    if (g_out && split_p == 1)
         hipLaunchKernelGGL((k_conv_bf16<BM, BN, true, kImplicit>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
-                           (const uint16_t*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
+                           (const uint16_t*)D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
     else
         hipLaunchKernelGGL((k_conv_bf16<BM, BN, false, kImplicit>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
-                           (const uint16_t*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
+                           (const uint16_t*)D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
 }
 
 template <bool kImplicit>
@@ -462,18 +545,29 @@ static int launch_conv_any(const void* X, const void* D, uint32_t B, uint32_t P,
                            float* g_out, float* s_out, void* workspace, size_t workspace_bytes, const ConvGeom& G,
                            hipStream_t stream) {
     const ConvTile t = conv_tile(J, C);
-    uint32_t splits = conv_splits(B, J, C);
-    if (splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * J * C * sizeof(float))) splits = 1;
-    const uint32_t zper = (B + splits - 1) / splits;
-    splits = (B + zper - 1) / zper;
+    const size_t JC = (size_t)J * C;
+    uint32_t split_p = conv_split_p(B, P, J, C);
+    if (split_p > 1 && (!workspace || workspace_bytes < (size_t)B * split_p * JC * sizeof(float))) split_p = 1;
+    uint32_t splits = split_p > 1 ? B * split_p : conv_splits(B, J, C);
+    if (split_p == 1 && splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * JC * sizeof(float))) splits = 1;
+    uint32_t zper = 1;
+    if (split_p == 1) {
+        zper = (B + splits - 1) / splits;
+        splits = (B + zper - 1) / zper;
+    }
     const uint64_t nblk = (uint64_t)((C + t.bn - 1) / t.bn) * ((J + t.bm - 1) / t.bm) * splits;
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
-    if (t.bm == 256 && t.bn == 128) launch_conv_bf16<256, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
-    else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
-    else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
-    else launch_conv_bf16<128, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
+    if (t.bm == 256 && t.bn == 128) launch_conv_bf16<256, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    else launch_conv_bf16<128, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    if (split_p > 1) {
+        hipLaunchKernelGGL(k_sqgrad_reduce_parts, dim3((uint32_t)((JC + 15) / 16)), dim3(256), 0, stream, ws, B, split_p, JC, cg, cs,
+                           g_out, s_out);
+        return hip_check(hipGetLastError(), "launch k_conv_bf16");
+    }
     if (splits > 1) launch_sqgrad_reduce(ws, splits, (size_t)J * C, cg, cs, g_out, s_out, stream);
     return hip_check(hipGetLastError(), "launch k_conv_bf16");
 }

@@ -69,6 +69,8 @@ GEOMS = [  # B, H, W, Cin, C, kh, kw, stride, pad
     (2, 6, 1, 24, 16, 3, 1, (1, 1), (1, 0)),       # output one column wide
     (5, 28, 28, 128, 136, 3, 3, (1, 1), (1, 1)),   # several row tiles and a ragged column tile, samples split
     (2, 16, 16, 256, 128, 3, 3, (1, 1), (1, 1)),   # a 256-column tile inside one tap
+    (2, 40, 37, 16, 16, 3, 3, (1, 1), (1, 1)),     # one tile, 1480 positions: the positions are split over workgroups
+    (3, 64, 50, 8, 24, 3, 3, (2, 1), (1, 1)),      # the same with a stride
 ]
 
 
