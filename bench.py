@@ -191,6 +191,7 @@ def main():
     if not a.no_sqgrad:
         out["stages"]["sqgrad"] = bench_sqgrad(dev)
         out["stages"]["vgg16_iteration"] = bench_vgg_iteration(dev, zeta)
+        out["stages"]["resnet50_iteration"] = bench_resnet_iteration(dev, zeta)
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(pool[0], a, cfg, min(a.cpu_sample, N))
     print(json.dumps(out))
@@ -379,66 +380,72 @@ def bench_sqgrad(dev):
     return res
 
 
-def bench_vgg_iteration(dev, zeta):
-    """One worker's whole compression step on the VGG-16-shaped configuration (C4: batch 64, bfloat16 activations):
-    the statistic s of every layer (convolutions from their NHWC inputs, the 3-channel first layer through its patch
-    matrix, FC layers in the FC form; g comes from the framework's own backward pass and is synthetic here),
-    then select + pack over the 138 M parameters, then the decode of 8 such messages fused with a Momentum SGD step."""
+def _timed(fn, reps=3):
     import torch
-    from paper_1802_06058_amd import vgc, workloads as W
-    B = 64
-    convs = [(3, 64, 224), (64, 64, 224), (64, 128, 112), (128, 128, 112), (128, 256, 56), (256, 256, 56), (256, 256, 56),
-             (256, 512, 28), (512, 512, 28), (512, 512, 28), (512, 512, 14), (512, 512, 14), (512, 512, 14)]
-    fcs = [(25088, 4096), (4096, 4096), (4096, 1000)]
+    fn(); torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record(); torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def _statistic_of_layers(dev, dt, B, convs, fcs):
+    """s of every layer of a network: convolutions (cin, cout, input extent, kernel, stride, pad) from their NHWC
+    inputs, those whose channel count is not a multiple of 16 bytes through a patch matrix (columns padded to a
+    multiple of 16 bytes), FC layers in the FC form.  Returns (per-layer list, total ms, conv flops)."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    code = vgc.BF16 if dt == torch.bfloat16 else vgc.F32
+    piece = 8 if dt == torch.bfloat16 else 4
     gen = torch.Generator(device=dev); gen.manual_seed(5)
-    rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(torch.bfloat16)
-
-    def timed(fn, reps=3):
-        fn(); torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(reps):
-            fn()
-        e1.record(); torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / reps
-
+    rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(dt)
     layers, t_stat, flops = [], 0.0, 0.0
-    for cin, cout, sp in convs:
-        D = rnd(B, sp, sp, cout) * 1e-3
-        J = 9 * cin
-        s = torch.empty(J, cout, dtype=torch.float32, device=dev)
-        if cin % 8 == 0:
+    for cin, cout, sp, k, st, pd in convs:
+        so = (sp + 2 * pd - k) // st + 1
+        D = rnd(B, so, so, cout) * 1e-3
+        J = k * k * cin
+        if cin % piece == 0:
             A = rnd(B, sp, sp, cin)
-            nb = vgc.sqgrad_conv2d_workspace_bytes(vgc.BF16, B, sp, sp, cin, cout, 3, 3, (1, 1), (1, 1))
-            ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
-            ms = timed(lambda: vgc.sqgrad_conv2d(A, D, 3, 3, (1, 1), (1, 1), 1.0 / B, s, None, workspace=ws))
-            form = "nhwc"
-        else:                                             # 3 input channels: patch matrix [B, P, 27] (padded to 32 columns)
-            A = rnd(B, sp * sp, 32)
-            A[:, :, 27:] = 0
-            J = 32
             s = torch.empty(J, cout, dtype=torch.float32, device=dev)
-            nb = vgc.sqgrad_workspace_bytes(vgc.CONV, vgc.BF16, B, sp * sp, J, cout)
+            nb = vgc.sqgrad_conv2d_workspace_bytes(code, B, sp, sp, cin, cout, k, k, (st, st), (pd, pd))
             ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
-            ms = timed(lambda: vgc.sqgrad(vgc.CONV, A, D.view(B, sp * sp, cout), 1.0 / B, s, None, workspace=ws))
+            ms = _timed(lambda: vgc.sqgrad_conv2d(A, D, k, k, (st, st), (pd, pd), 1.0 / B, s, None, workspace=ws))
+            form = "nhwc"
+        else:
+            Jp = (J + piece - 1) // piece * piece
+            A = rnd(B, so * so, Jp)
+            A[:, :, J:] = 0
+            s = torch.empty(Jp, cout, dtype=torch.float32, device=dev)
+            nb = vgc.sqgrad_workspace_bytes(vgc.CONV, code, B, so * so, Jp, cout)
+            ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
+            ms = _timed(lambda: vgc.sqgrad(vgc.CONV, A, D.view(B, so * so, cout), 1.0 / B, s, None, workspace=ws))
             form = "patches"
-        fl = 2.0 * B * sp * sp * 9 * cin * cout
-        layers.append({"layer": f"conv {cin}->{cout} @{sp}", "form": form, "ms": round(ms, 4), "TFLOPs": round(fl / ms / 1e9, 1)})
+        fl = 2.0 * B * so * so * J * cout
+        layers.append({"layer": f"conv{k}x{k}/{st} {cin}->{cout} @{sp}", "form": form, "ms": round(ms, 4),
+                       "TFLOPs": round(fl / ms / 1e9, 1)})
         t_stat += ms; flops += fl
         del A, D, s, ws
     for fin, fout in fcs:
         X, D = rnd(B, fin), rnd(B, fout) * 1e-3
         s = torch.empty(fin, fout, dtype=torch.float32, device=dev)
-        ms = timed(lambda: vgc.sqgrad(vgc.FC, X, D, 1.0 / B, s, None))
-        layers.append({"layer": f"fc {fin}x{fout}", "form": "fc", "ms": round(ms, 4),
-                       "GBs": round(4.0 * fin * fout / ms / 1e6, 1)})
+        ms = _timed(lambda: vgc.sqgrad(vgc.FC, X, D, 1.0 / B, s, None))
+        layers.append({"layer": f"fc {fin}x{fout}", "form": "fc", "ms": round(ms, 4), "GBs": round(4.0 * fin * fout / ms / 1e6, 1)})
         t_stat += ms
         del X, D, s
+    return layers, t_stat, flops
 
-    cfg = W.CONFIGS["C4"]
+
+def _select_pack_update(dev, cfg_name, B, zeta):
+    """select + pack over a model's parameter set, then the decode of 8 such messages fused with a Momentum SGD step."""
+    import torch
+    from paper_1802_06058_amd import vgc, workloads as W
+    cfg = W.CONFIGS[cfg_name]
     sizes = [L["size"] for L in cfg["layers"]]
     plan = vgc.Plan(W.groups_from_sizes(sizes), dev)
     n = plan.n
+    gen = torch.Generator(device=dev); gen.manual_seed(6)
     sig = torch.from_numpy(np.repeat(W.layer_sigmas(cfg["seed"], len(sizes)), sizes).astype(np.float32)).to(dev)
     z = torch.randn(n, generator=gen, device=dev)
     chi = torch.zeros(n, device=dev)
@@ -455,13 +462,57 @@ def bench_vgg_iteration(dev, zeta):
         r.zero_(); v.zero_()
         vgc.accumulate_select(g, s, r, v, plan, 1.0, zeta, scratch)
         vgc.pack(plan, scratch, words, hdrs, status)
-    t_sp = timed(select_pack) - timed(lambda: (r.zero_(), v.zero_()))
+    t_sp = _timed(select_pack) - _timed(lambda: (r.zero_(), v.zero_()))
     total = vgc.read_status(status)[0]
     param, mom = torch.zeros(n, device=dev), torch.zeros(n, device=dev)
-    t_up = timed(lambda: vgc.unpack_apply([words] * 8, [total] * 8, [hdrs] * 8, plan, 0.125, param, mom,
-                                          kind=vgc.MOMENTUM_SGD, lr=1e-3, momentum=0.9))
+    t_up = _timed(lambda: vgc.unpack_apply([words] * 8, [total] * 8, [hdrs] * 8, plan, 0.125, param, mom,
+                                           kind=vgc.MOMENTUM_SGD, lr=1e-3, momentum=0.9))
+    return n, t_sp, total / n, t_up
+
+
+def bench_vgg_iteration(dev, zeta):
+    """One worker's whole compression step on the VGG-16-shaped configuration (C4: batch 64, bfloat16 activations):
+    the statistic s of every layer (g comes from the framework's own backward pass and is synthetic here), select +
+    pack over the 138 M parameters, the decode of 8 such messages fused with a Momentum SGD step."""
+    import torch
+    B = 64
+    convs = [(cin, cout, sp, 3, 1, 1) for cin, cout, sp in
+             [(3, 64, 224), (64, 64, 224), (64, 128, 112), (128, 128, 112), (128, 256, 56), (256, 256, 56), (256, 256, 56),
+              (256, 512, 28), (512, 512, 28), (512, 512, 28), (512, 512, 14), (512, 512, 14), (512, 512, 14)]]
+    layers, t_stat, flops = _statistic_of_layers(dev, torch.bfloat16, B, convs, [(25088, 4096), (4096, 4096), (4096, 1000)])
+    n, t_sp, rho, t_up = _select_pack_update(dev, "C4", B, zeta)
     return {"batch": B, "n_params": n, "statistic_ms": round(t_stat, 3), "statistic_conv_TFLOPs": round(flops / 1e12, 3),
-            "select_plus_pack_ms": round(t_sp, 3), "sent_fraction": round(total / n, 4),
+            "select_plus_pack_ms": round(t_sp, 3), "sent_fraction": round(rho, 4),
+            "decode8_plus_momentum_sgd_ms": round(t_up, 3), "total_ms": round(t_stat + t_sp + t_up, 3), "layers": layers}
+
+
+def bench_resnet_iteration(dev, zeta):
+    """The same for the ResNet-50-shaped configuration (C3: batch 32, float32 activations); identical layers are
+    timed once and counted as often as they occur."""
+    import torch
+    B = 32
+    convs, count = [], []
+    def add(spec, times=1):
+        convs.append(spec); count.append(times)
+    add((3, 64, 224, 7, 2, 3))
+    cin, prev_sp = 64, 56
+    for width, blocks, sp in [(64, 3, 56), (128, 4, 28), (256, 6, 14), (512, 3, 7)]:
+        st = prev_sp // sp
+        add((cin, width, prev_sp, 1, 1, 0)); add((width, width, prev_sp, 3, st, 1)); add((width, 4 * width, sp, 1, 1, 0))
+        add((cin, 4 * width, prev_sp, 1, st, 0))
+        add((4 * width, width, sp, 1, 1, 0), blocks - 1); add((width, width, sp, 3, 1, 1), blocks - 1)
+        add((width, 4 * width, sp, 1, 1, 0), blocks - 1)
+        cin, prev_sp = 4 * width, sp
+    layers, _, _ = _statistic_of_layers(dev, torch.float32, B, convs, [(2048, 1000)])
+    t_stat, flops = 0.0, 0.0
+    for L, c in zip(layers, count + [1]):
+        L["count"] = c
+        t_stat += c * L["ms"]
+        if "TFLOPs" in L:
+            flops += c * L["TFLOPs"] * L["ms"] * 1e9
+    n, t_sp, rho, t_up = _select_pack_update(dev, "C3", B, zeta)
+    return {"batch": B, "n_params": n, "statistic_ms": round(t_stat, 3), "statistic_conv_TFLOPs": round(flops / 1e12, 3),
+            "select_plus_pack_ms": round(t_sp, 3), "sent_fraction": round(rho, 4),
             "decode8_plus_momentum_sgd_ms": round(t_up, 3), "total_ms": round(t_stat + t_sp + t_up, 3), "layers": layers}
 
 

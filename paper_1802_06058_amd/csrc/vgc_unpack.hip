@@ -120,17 +120,22 @@ template <int kMax, int kMode>
 __global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs<kMax> A, const PlanGroup* __restrict__ groups,
                                                           const PlanRun* __restrict__ runs, uint32_t n_runs,
                                                           float scale, float* __restrict__ dense, int overwrite,
-                                                          UpdateArgs O) {
+                                                          UpdateArgs O, uint32_t tiles_per_wave) {
     __shared__ __attribute__((aligned(16))) float sh_tile[4][kTile];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-    const uint32_t run = blockIdx.x * 4 + wave;
+    // a run of kRunTiles tiles is shared by kRunTiles / tiles_per_wave waves (small parameter sets have few runs)
+    const uint32_t per_run = (uint32_t)kRunTiles / tiles_per_wave;
+    const uint32_t gw = blockIdx.x * 4 + wave;
+    const uint32_t run = gw / per_run;
     if (run >= n_runs) return;
     float* T = sh_tile[wave];
     const uint32_t k = runs[run].group;
-    const uint32_t t0 = runs[run].first_tile;                // first tile of the run, counted inside the group
     const PlanGroup pg = groups[k];
     const uint32_t nt_group = (pg.size + kTile - 1) / kTile;
-    const uint32_t t1 = min(t0 + (uint32_t)kRunTiles, nt_group);
+    const uint32_t run_end = min(runs[run].first_tile + (uint32_t)kRunTiles, nt_group);
+    const uint32_t t0 = runs[run].first_tile + (gw % per_run) * tiles_per_wave;   // first tile of this wave, counted inside the group
+    if (t0 >= run_end) return;
+    const uint32_t t1 = min(t0 + tiles_per_wave, run_end);
 
     // per message (lane w < p): segment of group k and the cursor = first word with index >= run start
     uint64_t cur = 0, seg_end = 0;
@@ -262,6 +267,14 @@ __global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs<kMax> A, con
     }
 }
 
+// Tiles one wave takes: a whole run when there are plenty of runs, fewer (a power of two) when the parameter
+// set is small, so that there are about 16 K waves to spread over the chip.
+static uint32_t tiles_per_wave(uint64_t n_runs) {
+    uint32_t tpw = kRunTiles;
+    while (tpw > 1 && n_runs * (kRunTiles / tpw) < 16384) tpw /= 2;
+    return tpw;
+}
+
 template <int kMax>
 static BatchArgs<kMax> batch_args(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
                                   uint32_t first, uint32_t p) {
@@ -279,12 +292,13 @@ static BatchArgs<kMax> batch_args(const uint32_t* const* words, const uint64_t* 
 int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
                             uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs,
                             float scale, int overwrite, float* dense, hipStream_t stream) {
-    const uint32_t blocks = (uint32_t)((n_runs + 3) / 4);
+    const uint32_t tpw = tiles_per_wave(n_runs);
+    const uint32_t blocks = (uint32_t)((n_runs * (kRunTiles / tpw) + 3) / 4);
     const uint32_t chunks = p ? (p + kBatchMax - 1) / kBatchMax : 1;     // p == 0: only the optional clear
     for (uint32_t ch = 0; ch < chunks; ++ch) {
         const BatchArgs<kBatchMax> A = batch_args<kBatchMax>(words, n_words, hdrs, ch * kBatchMax, p);
         hipLaunchKernelGGL((k_unpack_add_batch<kBatchMax, kToDense>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
-                           (uint32_t)n_runs, scale, dense, (overwrite && ch == 0) ? 1 : 0, UpdateArgs{});
+                           (uint32_t)n_runs, scale, dense, (overwrite && ch == 0) ? 1 : 0, UpdateArgs{}, tpw);
     }
     return hip_check(hipGetLastError(), "launch k_unpack_add_batch");
 }
@@ -293,17 +307,18 @@ int launch_unpack_apply(const uint32_t* const* words, const uint64_t* n_words, c
                         uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs, float scale,
                         int kind, float lr, float mu, float b1, float b2, float omb1, float omb2, float bias1, float bias2,
                         float eps, float* param, float* state1, float* state2, hipStream_t stream) {
-    const uint32_t blocks = (uint32_t)((n_runs + 3) / 4);
+    const uint32_t tpw = tiles_per_wave(n_runs);
+    const uint32_t blocks = (uint32_t)((n_runs * (kRunTiles / tpw) + 3) / 4);
     const BatchArgs<kApplyMax> A = batch_args<kApplyMax>(words, n_words, hdrs, 0, p);
     UpdateArgs O;
     O.w = param; O.s1 = state1; O.s2 = state2;
     O.lr = lr; O.mu = mu; O.b1 = b1; O.b2 = b2; O.omb1 = omb1; O.omb2 = omb2; O.bias1 = bias1; O.bias2 = bias2; O.eps = eps;
     if (kind == VGC_OPT_ADAM)
         hipLaunchKernelGGL((k_unpack_add_batch<kApplyMax, kAdam>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
-                           (uint32_t)n_runs, scale, static_cast<float*>(nullptr), 1, O);
+                           (uint32_t)n_runs, scale, static_cast<float*>(nullptr), 1, O, tpw);
     else
         hipLaunchKernelGGL((k_unpack_add_batch<kApplyMax, kMomentumSgd>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
-                           (uint32_t)n_runs, scale, static_cast<float*>(nullptr), 1, O);
+                           (uint32_t)n_runs, scale, static_cast<float*>(nullptr), 1, O, tpw);
     return hip_check(hipGetLastError(), "launch k_unpack_add_batch (update)");
 }
 
