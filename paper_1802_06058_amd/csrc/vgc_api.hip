@@ -208,8 +208,7 @@ size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint
     if (conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, &Ho, &Wo) != VGC_OK) return 0;
     const uint32_t J = kh * kw * Cin;
     if (dtype == VGC_BF16) return conv_workspace_bytes(B, Ho * Wo, J, C);
-    const uint32_t splits = conv_f32_splits(B, J, C);
-    return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
+    return conv_f32_workspace_bytes(B, Ho * Wo, J, C);
 }
 
 int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin,

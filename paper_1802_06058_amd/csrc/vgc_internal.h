@@ -159,6 +159,9 @@ void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg,
 bool fc_tiled_supported(int dtype, uint32_t B, uint32_t J, uint32_t C);
 bool conv_f32_tiled_supported(uint32_t P, uint32_t J, uint32_t C);
 uint32_t conv_f32_splits(uint32_t B, uint32_t J, uint32_t C);
+size_t conv_f32_workspace_bytes(uint32_t B, uint32_t P, uint32_t J, uint32_t C);
+void launch_sqgrad_reduce_parts(const float* ws, uint32_t B, uint32_t split_p, size_t JC, float cg, float cs, float* g_out,
+                                float* s_out, hipStream_t stream);
 int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t J, uint32_t C, float c,
                     float* g_out, float* s_out, hipStream_t stream);
 int launch_conv_f32_tiled(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,

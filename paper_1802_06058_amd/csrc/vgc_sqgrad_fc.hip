@@ -180,7 +180,7 @@ __device__ __forceinline__ void stage32(float* A, float* Bm, const Chunk32& R, u
 template <bool kConv, bool kWantG, bool kImplicit>
 __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
                                                       uint32_t B, uint32_t P, uint32_t J, uint32_t C,
-                                                      uint32_t z_per_split, uint32_t splits, float cg, float cs,
+                                                      uint32_t z_per_split, uint32_t splits, uint32_t split_p, float cg, float cs,
                                                       float* __restrict__ g_out, float* __restrict__ s_out,
                                                       float* __restrict__ ws, ConvGeom G) {
     __shared__ __attribute__((aligned(16))) float shA[2][kR32 * kPitch32];
@@ -193,10 +193,15 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
     const uint32_t tile_c = logical % tiles_c, tile_j = (logical / tiles_c) % tiles_j, split = logical / (tiles_c * tiles_j);
     const uint32_t j0 = tile_j * kT, c0 = tile_c * kT;
     const uint32_t rowsP = kConv ? P : B;                            // K extent of one "sample"
-    const uint32_t z_begin = kConv ? split * z_per_split : 0u;
-    const uint32_t z_end = kConv ? min(B, z_begin + z_per_split) : 1u;
+    // split_p > 1 (conv only): the workgroup owns part `part` of the positions of the single sample split / split_p
+    // and leaves the unsquared partial product in the workspace
     const uint32_t n_chunks = (rowsP + kR32 - 1) / kR32;
-    const uint32_t total = (z_end - z_begin) * n_chunks;
+    const uint32_t part = split_p > 1 ? split % split_p : 0u;
+    const uint32_t chunks_per_part = (n_chunks + split_p - 1) / split_p;
+    const uint32_t c_begin = min(n_chunks, part * chunks_per_part);
+    const uint32_t z_begin = !kConv ? 0u : (split_p > 1 ? split / split_p : split * z_per_split);
+    const uint32_t z_end = !kConv ? 1u : (split_p > 1 ? z_begin + 1u : min(B, z_begin + z_per_split));
+    const uint32_t total = split_p > 1 ? min(n_chunks, c_begin + chunks_per_part) - c_begin : (z_end - z_begin) * n_chunks;
 
     f16v acc[2][2], s_acc[2][2], g_acc[2][2];
 #pragma unroll
@@ -212,8 +217,9 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
         for (int i = 0; i < 2; ++i) {
             const uint32_t idx = tid + 256u * i, row = idx >> 5, colj = j0 + (idx & 31u) * 4u;
             const uint32_t tap = colj / G.Cin, ky = tap / G.kw;
-            y0A[i] = yA[i] = row / G.Wo;
-            x0A[i] = xA[i] = row - y0A[i] * G.Wo;
+            const uint32_t pos0 = c_begin * kR32 + row;           // the lane's row in the workgroup's first chunk
+            y0A[i] = yA[i] = pos0 / G.Wo;
+            x0A[i] = xA[i] = pos0 - y0A[i] * G.Wo;
             const int32_t ty = (int32_t)ky - (int32_t)G.ph;
             tapX[i] = (int32_t)(tap - ky * G.kw) - (int32_t)G.pw;
             tapOff[i] = (ty * (int32_t)G.W + tapX[i]) * (int32_t)G.Cin + (int32_t)(colj - tap * G.Cin);
@@ -221,7 +227,7 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
         }
     }
     Chunk32 R[2];
-    uint32_t zl = z_begin, pcl = 0, issued = 0;
+    uint32_t zl = z_begin, pcl = c_begin, issued = 0;
     auto issue = [&](int slot_) {
         const bool live = issued < total;
         const uint32_t zz = live ? zl : z_begin;
@@ -266,7 +272,7 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
     __syncthreads();
 
     const uint32_t col = lane & 31u, kh = lane >> 5;
-    uint32_t pc = 0, zdone = z_begin;
+    uint32_t left = split_p > 1 ? 0u : n_chunks;                     // chunks until the sample's product is complete (0: never)
     for (uint32_t q0 = 0; q0 < total; q0 += 2) {
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -296,9 +302,8 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
             const int ns = u ^ 1;
             stage32(shA[buf ^ 1u], shB[buf ^ 1u], R[ns], tid);
             issue(ns);
-            if (kConv && ++pc == n_chunks && zdone < z_end) {     // sample finished: G_z is complete in acc
-                pc = 0;
-                ++zdone;
+            if (kConv && --left == 0) {                           // sample finished: G_z is complete in acc
+                left = n_chunks;                                  // (a surplus chunk of zeros may "finish" a sample: adds nothing)
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -318,6 +323,10 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
 
     const bool direct = (splits == 1);
     const size_t JC = (size_t)J * C;
+    if (split_p > 1) {                                               // the partial product itself, for k_sqgrad_reduce_parts
+        store_tile(1.0f, 1.0f, acc, acc, false, ws + (size_t)split * JC, nullptr, j0, c0, J, C, wm, wn, lane);
+        return;
+    }
     float* so = direct ? s_out : ws + (size_t)split * 2 * JC;
     float* go = direct ? g_out : ws + (size_t)split * 2 * JC + JC;
     store_tile(direct ? cs : 1.0f, direct ? cg : 1.0f, s_acc, g_acc, kWantG, so, go, j0, c0, J, C, wm, wn, lane);
@@ -361,27 +370,53 @@ int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_
         if (g_out) hipLaunchKernelGGL(k_fc_bf16<true>, dim3((uint32_t)nblk), dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, J, C, cg, cs, g_out, s_out);
         else hipLaunchKernelGGL(k_fc_bf16<false>, dim3((uint32_t)nblk), dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, J, C, cg, cs, g_out, s_out);
     } else {
-        if (g_out) hipLaunchKernelGGL((k_tiled_f32<false, true, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
-        else hipLaunchKernelGGL((k_tiled_f32<false, false, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
+        if (g_out) hipLaunchKernelGGL((k_tiled_f32<false, true, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
+        else hipLaunchKernelGGL((k_tiled_f32<false, false, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
     }
     return hip_check(hipGetLastError(), "launch fc tiled");
+}
+
+// Positions split (see conv_split_p of the bf16 kernel): when (tiles x samples) fills less than half of the
+// 512 workgroup slots, into as many parts as fit one round, at least eight chunks each.
+uint32_t conv_f32_split_p(uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
+    const uint64_t tiles = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT);
+    const uint64_t slots = 512;
+    const uint32_t n_chunks = (P + kR32 - 1) / kR32;
+    if (tiles * B * 2 > slots || n_chunks < 16) return 1;
+    const uint64_t sp = slots / (tiles * B);
+    return (uint32_t)(sp < n_chunks / 8 ? sp : n_chunks / 8);
+}
+
+size_t conv_f32_workspace_bytes(uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
+    const uint32_t sp = conv_f32_split_p(B, P, J, C);
+    if (sp > 1) return (size_t)B * sp * J * C * sizeof(float);
+    const uint32_t splits = conv_f32_splits(B, J, C);
+    return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
 }
 
 template <bool kImplicit>
 static int launch_conv_f32_any(const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
                                float* g_out, float* s_out, void* workspace, size_t workspace_bytes, const ConvGeom& G,
                                hipStream_t stream) {
-    uint32_t splits = conv_f32_splits(B, J, C);
-    if (splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * J * C * sizeof(float))) splits = 1;
-    const uint32_t zper = (B + splits - 1) / splits;
-    splits = (B + zper - 1) / zper;
+    const size_t JC = (size_t)J * C;
+    uint32_t split_p = conv_f32_split_p(B, P, J, C);
+    if (split_p > 1 && (!workspace || workspace_bytes < (size_t)B * split_p * JC * sizeof(float))) split_p = 1;
+    uint32_t splits = split_p > 1 ? B * split_p : conv_f32_splits(B, J, C);
+    if (split_p == 1 && splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * JC * sizeof(float))) splits = 1;
+    uint32_t zper = 1;
+    if (split_p == 1) {
+        zper = (B + splits - 1) / splits;
+        splits = (B + zper - 1) / zper;
+    }
     const uint64_t nblk = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT) * splits;
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
-    if (g_out) hipLaunchKernelGGL((k_tiled_f32<true, true, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
-    else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, cg, cs, g_out, s_out, ws, G);
-    if (splits > 1) launch_sqgrad_reduce(ws, splits, (size_t)J * C, cg, cs, g_out, s_out, stream);
+    // with the positions split the partial products are unsquared: the variant without g serves both
+    if (g_out && split_p == 1) hipLaunchKernelGGL((k_tiled_f32<true, true, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    if (split_p > 1) launch_sqgrad_reduce_parts(ws, B, split_p, JC, cg, cs, g_out, s_out, stream);
+    else if (splits > 1) launch_sqgrad_reduce(ws, splits, JC, cg, cs, g_out, s_out, stream);
     return hip_check(hipGetLastError(), "launch k_tiled_f32");
 }
 

@@ -509,15 +509,20 @@ size_t conv_workspace_bytes(uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
 size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
     if (kind != VGC_CONV) return 0;
     if (conv_tiled_supported(dtype, P, J, C)) return conv_workspace_bytes(B, P, J, C);
-    uint32_t splits = 1;
-    if (dtype == VGC_F32 && conv_f32_tiled_supported(P, J, C)) splits = conv_f32_splits(B, J, C);
-    return splits > 1 ? (size_t)splits * 2 * J * C * sizeof(float) : 0;
+    if (dtype == VGC_F32 && conv_f32_tiled_supported(P, J, C)) return conv_f32_workspace_bytes(B, P, J, C);
+    return 0;
 }
 
 bool conv_tiled_supported(int dtype, uint32_t P, uint32_t J, uint32_t C) {
     const uint64_t limit = 0x7FFFFFFFull;               // buffer ranges and offsets are 32-bit
     return dtype == VGC_BF16 && (J % 8 == 0) && (C % 8 == 0) && (uint64_t)(P + 64) * J * 2 < limit &&
            (uint64_t)(P + 64) * C * 2 < limit;
+}
+
+void launch_sqgrad_reduce_parts(const float* ws, uint32_t B, uint32_t split_p, size_t JC, float cg, float cs, float* g_out,
+                                float* s_out, hipStream_t stream) {
+    hipLaunchKernelGGL(k_sqgrad_reduce_parts, dim3((uint32_t)((JC + 15) / 16)), dim3(256), 0, stream, ws, B, split_p, JC, cg, cs,
+                       g_out, s_out);
 }
 
 void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg, float cs, float* g_out, float* s_out,
@@ -564,8 +569,7 @@ static int launch_conv_any(const void* X, const void* D, uint32_t B, uint32_t P,
     else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
     else launch_conv_bf16<128, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
     if (split_p > 1) {
-        hipLaunchKernelGGL(k_sqgrad_reduce_parts, dim3((uint32_t)((JC + 15) / 16)), dim3(256), 0, stream, ws, B, split_p, JC, cg, cs,
-                           g_out, s_out);
+        launch_sqgrad_reduce_parts(ws, B, split_p, JC, cg, cs, g_out, s_out, stream);
         return hip_check(hipGetLastError(), "launch k_conv_bf16");
     }
     if (splits > 1) launch_sqgrad_reduce(ws, splits, (size_t)J * C, cg, cs, g_out, s_out, stream);
