@@ -83,6 +83,39 @@ def test_flat_1e9_stream_select_pack_decode(dev):
         del g, s
 
 
+def test_group_of_maximum_size(dev):
+    """One group of exactly 2^28 elements (the most a 28-bit index can address, Section 4.2), sixteen scan
+    segments, followed by a small group: every output against the oracle, and the last index uses all 28 bits."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    sizes = [1 << 28, 1000]
+    groups = W.groups_from_sizes(sizes)
+    n = sum(sizes)
+    plan = vgc.Plan(groups, dev)
+    rng = np.random.default_rng(28)
+    g = rng.standard_normal(n, dtype=F32)
+    g *= F32(0.01)
+    s = rng.random(n, dtype=F32)
+    s *= F32(2e-4)
+    g[(1 << 28) - 1] = F32(1.0)                                   # the last element of the big group is sent for sure
+    r = torch.zeros(n, dtype=torch.float32, device=dev); v = torch.zeros(n, dtype=torch.float32, device=dev)
+    scratch, hdrs, status = plan.new_scratch(), plan.new_headers(), plan.new_status()
+    words = torch.empty(n // 2, dtype=torch.int32, device=dev)
+    vgc.accumulate_select(torch.from_numpy(g).to(dev), torch.from_numpy(s).to(dev), r, v, plan, 2.0, 0.999, scratch)
+    vgc.pack(plan, scratch, words, hdrs, status)
+    torch.cuda.synchronize()
+    total, overflow = vgc.read_status(status)
+    z = np.zeros(n, F32)
+    r_acc, r_ref, v_ref, send = O.accumulate_select(g, s, z, z, 2.0, 0.999)
+    del z
+    w_ref, h_ref, _ = O.pack(r_acc, send, groups, check=False)
+    assert overflow == 0 and total == w_ref.size and vgc.read_headers(hdrs) == h_ref
+    got = words[:total].cpu().numpy().view(U32)
+    assert np.array_equal(got, w_ref)
+    assert (got[h_ref[0][1] - 1] & U32(0x0FFFFFFF)) == U32(0x0FFFFFFF)
+    assert np.array_equal(_bits(r.cpu().numpy()), _bits(r_ref)) and np.array_equal(_bits(v.cpu().numpy()), _bits(v_ref))
+
+
 @pytest.mark.parametrize("name,alpha,steps", [("C3", 1.0, 2), ("C4", 2.0, 1)])
 def test_model_parameter_sets_full_oracle(dev, name, alpha, steps):
     """ResNet-50-shaped (161 groups, 25.6 M) and VGG-16-shaped (32 groups, 138 M) parameter sets with
