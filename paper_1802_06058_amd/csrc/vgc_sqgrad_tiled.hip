@@ -399,19 +399,31 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         }
 }
 
-// Adds the per-split partial sums in split order and applies the scale factors.
+// Adds the per-split partial sums in a fixed order and applies the scale factors.  `lanes` (1, 4 or 16) threads
+// share an output: thread (output, lane q) takes splits q, q + lanes, ..., and the lanes' sums are added in lane
+// order.  A workgroup owns 256 / lanes consecutive outputs.
 __global__ __launch_bounds__(256) void k_sqgrad_reduce(const float* __restrict__ ws, uint32_t splits, size_t JC,
                                                        float cg, float cs, float* __restrict__ g_out,
-                                                       float* __restrict__ s_out) {
-    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= JC) return;
+                                                       float* __restrict__ s_out, uint32_t lanes) {
+    __shared__ float sh_s[256], sh_g[256];
+    const uint32_t opb = 256u / lanes, il = threadIdx.x % opb, q = threadIdx.x / opb;
+    const size_t i = (size_t)blockIdx.x * opb + il;
     float s = 0.f, g = 0.f;
-    for (uint32_t k = 0; k < splits; ++k) {
-        s += ws[(size_t)k * 2 * JC + i];
-        if (g_out) g += ws[(size_t)k * 2 * JC + JC + i];
+    if (i < JC) {
+        for (uint32_t k = q; k < splits; k += lanes) {
+            s += ws[(size_t)k * 2 * JC + i];
+            if (g_out) g += ws[(size_t)k * 2 * JC + JC + i];
+        }
     }
-    s_out[i] = cs * s;
-    if (g_out) g_out[i] = cg * g;
+    sh_s[threadIdx.x] = s;
+    sh_g[threadIdx.x] = g;
+    __syncthreads();
+    if (q == 0 && i < JC) {
+        float st = 0.f, gt = 0.f;
+        for (uint32_t k = 0; k < lanes; ++k) { st += sh_s[k * opb + il]; gt += sh_g[k * opb + il]; }
+        s_out[i] = cs * st;
+        if (g_out) g_out[i] = cg * gt;
+    }
 }
 
 // Block tile for a shape: wide in J (256) when J has room, 64 / 128 in C following C.
@@ -527,8 +539,10 @@ void launch_sqgrad_reduce_parts(const float* ws, uint32_t B, uint32_t split_p, s
 
 void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg, float cs, float* g_out, float* s_out,
                           hipStream_t stream) {
-    hipLaunchKernelGGL(k_sqgrad_reduce, dim3((uint32_t)((JC + 255) / 256)), dim3(256), 0, stream, ws, splits, JC, cg, cs,
-                       g_out, s_out);
+    const uint32_t lanes = splits <= 4 ? 1u : (splits <= 16 ? 4u : 16u);
+    const uint32_t opb = 256u / lanes;
+    hipLaunchKernelGGL(k_sqgrad_reduce, dim3((uint32_t)((JC + opb - 1) / opb)), dim3(256), 0, stream, ws, splits, JC, cg, cs,
+                       g_out, s_out, lanes);
 }
 
 template <int BM, int BN, bool kImplicit>
