@@ -6,7 +6,9 @@
 // per-sample product in MFMA accumulators; when the sample is finished the accumulators are squared
 // into s (and added into g) and cleared, so a per-sample gradient never leaves registers.  The sample
 // range can be split over workgroups to fill the chip when [J, C] has few tiles; the partial sums then
-// go to a workspace and are added in fixed order by k_sqgrad_reduce.
+// go to a workspace and are added in fixed order by k_sqgrad_reduce.  For the few layers where that is
+// still too little parallelism the positions of a sample are split as well: those workgroups leave
+// their part of the sample's product in the workspace and k_sqgrad_reduce_parts completes it.
 //
 // Chunks travel from global memory straight into LDS (buffer loads with the LDS modifier: lane l of a
 // wave-wide load deposits its 16 bytes at M0 + 16 l), several chunks ahead of the one being multiplied,

@@ -118,3 +118,32 @@ def test_missing_library_fails_loudly(monkeypatch, tmp_path):
     monkeypatch.setattr(vgc, "LIB_PATH", str(tmp_path / "libvgc.so"))
     with pytest.raises(vgc.VgcError):
         vgc.load()
+
+
+def test_conv2d_and_update_argument_checks_need_no_gpu():
+    """Geometry and hyper-parameter validation happens on the host before anything is launched."""
+    lib = vgc.load()
+    fake = C.c_void_p(0x1000)                                     # never dereferenced: every call below is rejected first
+    conv = lambda dtype, Cin, Cc, kh, ph: lib.vgc_sqgrad_conv2d(dtype, fake, fake, 2, 8, 8, Cin, Cc, kh, 3, 1, 1, ph, 1, 1.0,
+                                                                 None, fake, None, 0, None)
+    assert conv(vgc.BF16, 12, 8, 3, 1) == -2 and b"multiples of 16 bytes" in lib.vgc_last_error()
+    assert conv(vgc.F32, 6, 8, 3, 1) == -2
+    assert conv(vgc.BF16, 8, 8, 3, 3) == -2 and b"pad" in lib.vgc_last_error()
+    assert conv(9, 8, 8, 3, 1) == -4
+    assert lib.vgc_sqgrad_conv2d(vgc.BF16, None, fake, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, None, fake, None, 0, None) == -1
+    # the workspace query is pure host code: a layer with few tiles and many positions wants room for partial products
+    assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1) > 0
+    assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 6, 64, 3, 3, 1, 1, 1, 1) == 0     # unsupported shape
+
+    arr, n = _groups([100, 200])
+    opt = vgc.Optimizer(vgc.MOMENTUM_SGD, 0.1, 1.5, 0.9, 0.999, 1e-8, 1)
+    call = lambda o, p=0, s2=None: lib.vgc_unpack_apply(None, None, None, p, arr, 2, fake, 1.0, C.byref(o), fake, fake, s2, n, None)
+    assert call(opt) == -6 and b"momentum" in lib.vgc_last_error()
+    opt.kind, opt.momentum = 5, 0.9
+    assert call(opt) == -6
+    opt.kind = vgc.ADAM
+    assert call(opt) == -1                                         # Adam without its second state array
+    opt.step = 0
+    assert call(opt, 0, fake) == -6
+    opt.kind, opt.step = vgc.MOMENTUM_SGD, 1
+    assert call(opt, 65) == -1                                     # message tables missing
