@@ -30,8 +30,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--n", type=int, default=1_000_000_000, help="parameters per worker")
     ap.add_argument("--workers", type=int, default=8)
     ap.add_argument("--alpha", type=float, default=1.0)
@@ -146,7 +146,9 @@ def main():
                    "n_groups": len(groups), "tile": vgc.tile_size(), "sent_fraction": round(rho, 5)},
         "roofline": {"bound": "hbm", "kernel": "k_accumulate_select", "achieved": round(sel_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(sel_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(N), "algorithmic_bytes_per_launch": 24.0 * N, "avg_launch_ms": round(sel, 4)},
+                     "traffic": measured_traffic(N), "algorithmic_bytes_per_launch": 24.0 * N, "avg_launch_ms": round(sel, 4),
+                     "median_launch_ms": round(float(np.median(sel_ms)), 4), "min_launch_ms": round(float(np.min(sel_ms)), 4),
+                     "launches": len(sel_ms)},
         "stages": {
             "select_ms": round(sel, 4), "pack_ms": round(pk, 4), "decode_all_workers_ms": round(dec, 4),
             "select_plus_pack": {"algorithmic_GBs": round(sp_gbs, 1), "frac_of_peak": round(sp_gbs / HBM_PEAK_GBS, 4),
