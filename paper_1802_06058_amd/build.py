@@ -15,6 +15,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvgc.so")
 MICROBENCH = os.path.join(HERE, "vgc_microbench")
+SQGRAD_BENCH = os.path.join(HERE, "vgc_sqgrad_bench")
 OBJDIR = os.path.join(ROOT, "_build", "vgc")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -52,15 +53,16 @@ def build(verbose=True):
     if p.returncode != 0:
         raise RuntimeError("link failed:\n" + p.stderr)
     os.replace(tmp, LIB)
-    # native driver of the C ABI (profiling without a Python process)
-    mb_src = os.path.join(CSRC, "microbench", "vgc_microbench.hip")
-    p = subprocess.run([HIPCC, *FLAGS, mb_src, "-o", MICROBENCH + ".tmp", "-L", HERE, "-lvgc", "-Wl,-rpath,$ORIGIN"],
-                       capture_output=True, text=True)
-    if p.returncode != 0:
-        raise RuntimeError("microbench build failed:\n" + p.stderr)
-    os.replace(MICROBENCH + ".tmp", MICROBENCH)
+    # native drivers of the C ABI (profiling without a Python process)
+    for exe in (MICROBENCH, SQGRAD_BENCH):
+        src = os.path.join(CSRC, "microbench", os.path.basename(exe) + ".hip")
+        p = subprocess.run([HIPCC, *FLAGS, src, "-o", exe + ".tmp", "-L", HERE, "-lvgc", "-Wl,-rpath,$ORIGIN"],
+                           capture_output=True, text=True)
+        if p.returncode != 0:
+            raise RuntimeError(f"build of {src} failed:\n" + p.stderr)
+        os.replace(exe + ".tmp", exe)
     if verbose:
-        print(f"built {LIB} ({os.path.getsize(LIB)} bytes) from {len(objs)} sources, and {MICROBENCH}")
+        print(f"built {LIB} ({os.path.getsize(LIB)} bytes) from {len(objs)} sources, {MICROBENCH} and {SQGRAD_BENCH}")
     return LIB
 
 
