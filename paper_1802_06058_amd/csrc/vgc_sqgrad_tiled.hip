@@ -35,6 +35,7 @@ typedef short s8v __attribute__((ext_vector_type(8)));
 typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 typedef int i4v __attribute__((ext_vector_type(4)));
+typedef float f4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s4v* lds_s4v_ptr;
 
 constexpr int kKC = 32;                  // positions per LDS stage
@@ -401,30 +402,50 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         }
 }
 
+// kV consecutive floats (kV = 1 or 4) as one load or store.
+template <int kV> struct FloatVec { float v[kV]; };
+template <int kV> __device__ __forceinline__ FloatVec<kV> load_vec(const float* p) {
+    FloatVec<kV> r;
+    if constexpr (kV == 4) { const f4v t = *reinterpret_cast<const f4v*>(p); r.v[0] = t[0]; r.v[1] = t[1]; r.v[2] = t[2]; r.v[3] = t[3]; }
+    else r.v[0] = *p;
+    return r;
+}
+template <int kV> __device__ __forceinline__ void store_vec(float* p, const FloatVec<kV>& r) {
+    if constexpr (kV == 4) *reinterpret_cast<f4v*>(p) = (f4v){r.v[0], r.v[1], r.v[2], r.v[3]};
+    else *p = r.v[0];
+}
+
 // Adds the per-split partial sums in a fixed order and applies the scale factors.  `lanes` (1, 4 or 16) threads
-// share an output: thread (output, lane q) takes splits q, q + lanes, ..., and the lanes' sums are added in lane
-// order.  A workgroup owns 256 / lanes consecutive outputs.
+// share kV consecutive outputs: thread (outputs, lane q) takes splits q, q + lanes, ..., and the lanes' sums are
+// added in lane order.  A workgroup owns 256 / lanes * kV consecutive outputs; JC is a multiple of kV.
+template <int kV>
 __global__ __launch_bounds__(256) void k_sqgrad_reduce(const float* __restrict__ ws, uint32_t splits, size_t JC,
                                                        float cg, float cs, float* __restrict__ g_out,
                                                        float* __restrict__ s_out, uint32_t lanes) {
-    __shared__ float sh_s[256], sh_g[256];
+    __shared__ FloatVec<kV> sh_s[256], sh_g[256];
     const uint32_t opb = 256u / lanes, il = threadIdx.x % opb, q = threadIdx.x / opb;
-    const size_t i = (size_t)blockIdx.x * opb + il;
-    float s = 0.f, g = 0.f;
+    const size_t i = ((size_t)blockIdx.x * opb + il) * kV;
+    FloatVec<kV> s = {}, g = {};
     if (i < JC) {
         for (uint32_t k = q; k < splits; k += lanes) {
-            s += ws[(size_t)k * 2 * JC + i];
-            if (g_out) g += ws[(size_t)k * 2 * JC + JC + i];
+            const FloatVec<kV> ps = load_vec<kV>(ws + (size_t)k * 2 * JC + i);
+            for (int e = 0; e < kV; ++e) s.v[e] += ps.v[e];
+            if (g_out) {
+                const FloatVec<kV> pg = load_vec<kV>(ws + (size_t)k * 2 * JC + JC + i);
+                for (int e = 0; e < kV; ++e) g.v[e] += pg.v[e];
+            }
         }
     }
     sh_s[threadIdx.x] = s;
     sh_g[threadIdx.x] = g;
     __syncthreads();
     if (q == 0 && i < JC) {
-        float st = 0.f, gt = 0.f;
-        for (uint32_t k = 0; k < lanes; ++k) { st += sh_s[k * opb + il]; gt += sh_g[k * opb + il]; }
-        s_out[i] = cs * st;
-        if (g_out) g_out[i] = cg * gt;
+        FloatVec<kV> st = {}, gt = {};
+        for (uint32_t k = 0; k < lanes; ++k)
+            for (int e = 0; e < kV; ++e) { st.v[e] += sh_s[k * opb + il].v[e]; gt.v[e] += sh_g[k * opb + il].v[e]; }
+        for (int e = 0; e < kV; ++e) { st.v[e] *= cs; gt.v[e] *= cg; }
+        store_vec<kV>(s_out + i, st);
+        if (g_out) store_vec<kV>(g_out + i, gt);
     }
 }
 
@@ -440,31 +461,36 @@ static ConvTile conv_tile(uint32_t J, uint32_t C) {
 }
 
 // Sums the parts of every sample's product, then squares and sums over the samples, in a fixed order: a
-// workgroup owns 16 outputs; thread (output, lane q) takes samples q, q + 16, ..., and the 16 lanes' sums are
-// added in lane order.
+// workgroup owns 16 kV consecutive outputs; thread (outputs, lane q) takes samples q, q + 16, ..., and the 16
+// lanes' sums are added in lane order.  JC is a multiple of kV.
+template <int kV>
 __global__ __launch_bounds__(256) void k_sqgrad_reduce_parts(const float* __restrict__ ws, uint32_t B, uint32_t split_p, size_t JC,
                                                              float cg, float cs, float* __restrict__ g_out,
                                                              float* __restrict__ s_out) {
-    __shared__ float sh_s[16][17], sh_g[16][17];
+    __shared__ FloatVec<kV> sh_s[16][17], sh_g[16][17];
     const uint32_t il = threadIdx.x & 15u, q = threadIdx.x >> 4;
-    const size_t i = (size_t)blockIdx.x * 16 + il;
-    float s = 0.f, g = 0.f;
+    const size_t i = ((size_t)blockIdx.x * 16 + il) * kV;
+    FloatVec<kV> s = {}, g = {};
     if (i < JC) {
         for (uint32_t z = q; z < B; z += 16) {
-            float G = 0.f;
-            for (uint32_t k = 0; k < split_p; ++k) G += ws[((size_t)z * split_p + k) * JC + i];
-            s = __builtin_fmaf(G, G, s);
-            g += G;
+            FloatVec<kV> G = {};
+            for (uint32_t k = 0; k < split_p; ++k) {
+                const FloatVec<kV> part = load_vec<kV>(ws + ((size_t)z * split_p + k) * JC + i);
+                for (int e = 0; e < kV; ++e) G.v[e] += part.v[e];
+            }
+            for (int e = 0; e < kV; ++e) { s.v[e] = __builtin_fmaf(G.v[e], G.v[e], s.v[e]); g.v[e] += G.v[e]; }
         }
     }
     sh_s[q][il] = s;
     sh_g[q][il] = g;
     __syncthreads();
     if (q == 0 && i < JC) {
-        float st = 0.f, gt = 0.f;
-        for (int k = 0; k < 16; ++k) { st += sh_s[k][il]; gt += sh_g[k][il]; }
-        s_out[i] = cs * st;
-        if (g_out) g_out[i] = cg * gt;
+        FloatVec<kV> st = {}, gt = {};
+        for (int k = 0; k < 16; ++k)
+            for (int e = 0; e < kV; ++e) { st.v[e] += sh_s[k][il].v[e]; gt.v[e] += sh_g[k][il].v[e]; }
+        for (int e = 0; e < kV; ++e) { st.v[e] *= cs; gt.v[e] *= cg; }
+        store_vec<kV>(s_out + i, st);
+        if (g_out) store_vec<kV>(g_out + i, gt);
     }
 }
 
@@ -533,18 +559,31 @@ bool conv_tiled_supported(int dtype, uint32_t P, uint32_t J, uint32_t C) {
            (uint64_t)(P + 64) * C * 2 < limit;
 }
 
+// Four outputs per thread when the planes and the outputs allow 16-byte accesses.
+static bool reduce_vec4(const float* ws, size_t JC, const float* g_out, const float* s_out) {
+    return JC % 4 == 0 && (((uintptr_t)ws | (uintptr_t)g_out | (uintptr_t)s_out) & 15u) == 0;
+}
+
 void launch_sqgrad_reduce_parts(const float* ws, uint32_t B, uint32_t split_p, size_t JC, float cg, float cs, float* g_out,
                                 float* s_out, hipStream_t stream) {
-    hipLaunchKernelGGL(k_sqgrad_reduce_parts, dim3((uint32_t)((JC + 15) / 16)), dim3(256), 0, stream, ws, B, split_p, JC, cg, cs,
-                       g_out, s_out);
+    if (reduce_vec4(ws, JC, g_out, s_out))
+        hipLaunchKernelGGL(k_sqgrad_reduce_parts<4>, dim3((uint32_t)((JC / 4 + 15) / 16)), dim3(256), 0, stream, ws, B, split_p, JC,
+                           cg, cs, g_out, s_out);
+    else
+        hipLaunchKernelGGL(k_sqgrad_reduce_parts<1>, dim3((uint32_t)((JC + 15) / 16)), dim3(256), 0, stream, ws, B, split_p, JC, cg,
+                           cs, g_out, s_out);
 }
 
 void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg, float cs, float* g_out, float* s_out,
                           hipStream_t stream) {
     const uint32_t lanes = splits <= 4 ? 1u : (splits <= 16 ? 4u : 16u);
     const uint32_t opb = 256u / lanes;
-    hipLaunchKernelGGL(k_sqgrad_reduce, dim3((uint32_t)((JC + opb - 1) / opb)), dim3(256), 0, stream, ws, splits, JC, cg, cs,
-                       g_out, s_out, lanes);
+    if (reduce_vec4(ws, JC, g_out, s_out))
+        hipLaunchKernelGGL(k_sqgrad_reduce<4>, dim3((uint32_t)((JC / 4 + opb - 1) / opb)), dim3(256), 0, stream, ws, splits, JC, cg,
+                           cs, g_out, s_out, lanes);
+    else
+        hipLaunchKernelGGL(k_sqgrad_reduce<1>, dim3((uint32_t)((JC + opb - 1) / opb)), dim3(256), 0, stream, ws, splits, JC, cg, cs,
+                           g_out, s_out, lanes);
 }
 
 template <int BM, int BN, bool kImplicit>
