@@ -188,7 +188,7 @@ def main():
 
     # the sparse regime, one worker of the flat workload on a fresh state
     out["stages"]["sparse_regime_fresh_state"] = alpha_sweep(vgc, plan, pool[0][0], pool[0][1], r[0], v[0], zeta, scratch,
-                                                             words[0], hdrs[0], status[0], (8.0, 16.0))
+                                                             words[0], hdrs[0], status[0], (8.0, 16.0), dense=dense)
     out["stages"]["model_parameter_sets"] = bench_model_sets(dev, a.alpha, zeta)
     if not a.no_sqgrad:
         out["stages"]["sqgrad"] = bench_sqgrad(dev)
@@ -284,8 +284,12 @@ def bench_model_sets(dev, alpha, zeta):
     return res
 
 
-def alpha_sweep(vgc, plan, g, s, r, v, zeta, scratch, words, hdrs, status, alphas):
-    """select + pack on state (r, v) = 0 for each alpha (three repetitions, state cleared before each)."""
+def alpha_sweep(vgc, plan, g, s, r, v, zeta, scratch, words, hdrs, status, alphas, dense=None):
+    """select + pack on state (r, v) = 0 for each alpha (three repetitions, state cleared before each).  With a
+    dense buffer, the message of each alpha is also decoded into it (vgc_unpack_add).  A sparse message touches
+    one element per memory transaction, so next to the algorithmic 12 bytes per word (word read, target read and
+    written) the decode rate is also given with whole 64-byte transactions for the target: 4 + 2 x 64 bytes per
+    word; the fraction of peak uses the algorithmic figure."""
     import torch
     n, res = plan.n, {}
     for alpha in alphas:
@@ -298,9 +302,18 @@ def alpha_sweep(vgc, plan, g, s, r, v, zeta, scratch, words, hdrs, status, alpha
             vgc.pack(plan, scratch, words, hdrs, status)
             e1.record(); torch.cuda.synchronize()
             ms.append(e0.elapsed_time(e1))
-        t, rho = min(ms[1:]), vgc.read_status(status)[0] / n
+        n_words = vgc.read_status(status)[0]
+        t, rho = min(ms[1:]), n_words / n
         res[str(alpha)] = {"ms": round(t, 4), "sent_fraction": float(f"{rho:.3g}"),
                            "frac_of_peak": round((24 + 4 * rho) * n / (t * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+        if dense is not None:
+            td = _timed(lambda: vgc.unpack_add(words, n_words, hdrs, plan, 1.0, dense), warm_ms=20.0, timed_ms=40.0)
+            res[str(alpha)]["decode"] = {
+                "ms": round(td, 4), "words": n_words,
+                "algorithmic_GBs_12B_per_word": round(12.0 * n_words / (td * 1e-3) / 1e9, 1),
+                "frac_of_peak": round(12.0 * n_words / (td * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "transaction_GBs_132B_per_word": round(132.0 * n_words / (td * 1e-3) / 1e9, 1),
+                "transaction_bytes": 64}
     return res
 
 
@@ -329,15 +342,7 @@ def bench_sqgrad(dev):
         peak = 2500.0 if dt == torch.bfloat16 else 157.3
         entry = {}
         for tag, gg in (("s_only", None), ("g_and_s", g)):
-            vgc.sqgrad(kind, X, D, 1.0 / B, s, gg, workspace=ws)
-            torch.cuda.synchronize()
-            reps = 5
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                vgc.sqgrad(kind, X, D, 1.0 / B, s, gg, workspace=ws)
-            e1.record(); torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / reps
+            ms = _timed(lambda: vgc.sqgrad(kind, X, D, 1.0 / B, s, gg, workspace=ws))
             chains = 2.0 if (kind == vgc.FC and gg is not None) else 1.0      # FC: one contraction per output array
             flops = chains * 2.0 * B * P * J * C
             out_bytes = (8.0 if gg is not None else 4.0) * J * C
@@ -363,15 +368,7 @@ def bench_sqgrad(dev):
         ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
         entry = {}
         for tag, gg in (("s_only", None), ("g_and_s", g)):
-            vgc.sqgrad_conv2d(A, D, 3, 3, (1, 1), (1, 1), 1.0 / B, s, gg, workspace=ws)
-            torch.cuda.synchronize()
-            reps = 5
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                vgc.sqgrad_conv2d(A, D, 3, 3, (1, 1), (1, 1), 1.0 / B, s, gg, workspace=ws)
-            e1.record(); torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / reps
+            ms = _timed(lambda: vgc.sqgrad_conv2d(A, D, 3, 3, (1, 1), (1, 1), 1.0 / B, s, gg, workspace=ws))
             tf = 2.0 * B * H * H * J * C / (ms * 1e-3) / 1e12
             io = 2.0 * B * H * H * (Cin + C) + (8.0 if gg is not None else 4.0) * J * C
             entry[tag] = {"ms": round(ms, 4), "TFLOPs": round(tf, 1), "mfma_frac": round(tf / 2500.0, 4),
@@ -382,10 +379,18 @@ def bench_sqgrad(dev):
     return res
 
 
-def _timed(fn, reps=3):
+def _timed(fn, warm_ms=150.0, timed_ms=100.0):
+    """Average duration of fn() in steady state: the matrix-core clock takes on the order of 100 ms of load to
+    settle after idle (the same call measures up to 20 % slower in the first milliseconds), so fn is repeated for
+    about warm_ms untimed and then for about timed_ms between two events."""
     import torch
     fn(); torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); fn(); e1.record(); torch.cuda.synchronize()
+    once = max(e0.elapsed_time(e1), 1e-3)
+    for _ in range(min(2000, max(1, int(warm_ms / once)))):
+        fn()
+    reps = min(2000, max(3, int(timed_ms / once)))
     e0.record()
     for _ in range(reps):
         fn()
@@ -393,50 +398,81 @@ def _timed(fn, reps=3):
     return e0.elapsed_time(e1) / reps
 
 
-def _statistic_of_layers(dev, dt, B, convs, fcs):
+def _statistic_of_layers(dev, dt, B, convs, fcs, counts=None):
     """s of every layer of a network: convolutions (cin, cout, input extent, kernel, stride, pad) from their NHWC
     inputs, those whose channel count is not a multiple of 16 bytes through a patch matrix (columns padded to a
-    multiple of 16 bytes), FC layers in the FC form.  Returns (per-layer list, total ms, conv flops)."""
+    multiple of 16 bytes), FC layers in the FC form.  counts[i] says how often layer i occurs in the network (its
+    inputs are shared, every occurrence has outputs and a workspace of its own).  Each distinct layer is timed
+    alone; then the calls of the whole network are timed in one sweep, on one stream and spread over four (the
+    layers are independent, so kernels of different layers can fill each other's tails).
+    Returns (per-layer list, sum of the layers' times x counts, conv flops, sweep ms on 1 stream, on 4 streams)."""
     import torch
     from paper_1802_06058_amd import vgc
     code = vgc.BF16 if dt == torch.bfloat16 else vgc.F32
     piece = 8 if dt == torch.bfloat16 else 4
     gen = torch.Generator(device=dev); gen.manual_seed(5)
     rnd = lambda *shape: torch.randn(shape, generator=gen, device=dev, dtype=torch.float32).to(dt)
-    layers, t_stat, flops = [], 0.0, 0.0
-    for cin, cout, sp, k, st, pd in convs:
+    counts = list(counts) if counts is not None else [1] * (len(convs) + len(fcs))
+    layers, calls, t_stat, flops = [], [], 0.0, 0.0
+    for (cin, cout, sp, k, st, pd), cnt in zip(convs, counts):
         so = (sp + 2 * pd - k) // st + 1
         D = rnd(B, so, so, cout) * 1e-3
         J = k * k * cin
+        mine = []
         if cin % piece == 0:
             A = rnd(B, sp, sp, cin)
-            s = torch.empty(J, cout, dtype=torch.float32, device=dev)
             nb = vgc.sqgrad_conv2d_workspace_bytes(code, B, sp, sp, cin, cout, k, k, (st, st), (pd, pd))
-            ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
-            ms = _timed(lambda: vgc.sqgrad_conv2d(A, D, k, k, (st, st), (pd, pd), 1.0 / B, s, None, workspace=ws))
+            for _ in range(cnt):
+                s = torch.empty(J, cout, dtype=torch.float32, device=dev)
+                ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
+                mine.append(lambda A=A, D=D, s=s, ws=ws, k=k, st=st, pd=pd:
+                            vgc.sqgrad_conv2d(A, D, k, k, (st, st), (pd, pd), 1.0 / B, s, None, workspace=ws))
             form = "nhwc"
         else:
             Jp = (J + piece - 1) // piece * piece
             A = rnd(B, so * so, Jp)
             A[:, :, J:] = 0
-            s = torch.empty(Jp, cout, dtype=torch.float32, device=dev)
+            Dm = D.view(B, so * so, cout)
             nb = vgc.sqgrad_workspace_bytes(vgc.CONV, code, B, so * so, Jp, cout)
-            ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
-            ms = _timed(lambda: vgc.sqgrad(vgc.CONV, A, D.view(B, so * so, cout), 1.0 / B, s, None, workspace=ws))
+            for _ in range(cnt):
+                s = torch.empty(Jp, cout, dtype=torch.float32, device=dev)
+                ws = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
+                mine.append(lambda A=A, Dm=Dm, s=s, ws=ws: vgc.sqgrad(vgc.CONV, A, Dm, 1.0 / B, s, None, workspace=ws))
             form = "patches"
+        ms = _timed(mine[0])
         fl = 2.0 * B * so * so * J * cout
-        layers.append({"layer": f"conv{k}x{k}/{st} {cin}->{cout} @{sp}", "form": form, "ms": round(ms, 4),
+        layers.append({"layer": f"conv{k}x{k}/{st} {cin}->{cout} @{sp}", "form": form, "count": cnt, "ms": round(ms, 4),
                        "TFLOPs": round(fl / ms / 1e9, 1)})
-        t_stat += ms; flops += fl
-        del A, D, s, ws
-    for fin, fout in fcs:
+        t_stat += cnt * ms; flops += cnt * fl
+        calls += mine
+    for (fin, fout), cnt in zip(fcs, counts[len(convs):]):
         X, D = rnd(B, fin), rnd(B, fout) * 1e-3
-        s = torch.empty(fin, fout, dtype=torch.float32, device=dev)
-        ms = _timed(lambda: vgc.sqgrad(vgc.FC, X, D, 1.0 / B, s, None))
-        layers.append({"layer": f"fc {fin}x{fout}", "form": "fc", "ms": round(ms, 4), "GBs": round(4.0 * fin * fout / ms / 1e6, 1)})
-        t_stat += ms
-        del X, D, s
-    return layers, t_stat, flops
+        mine = []
+        for _ in range(cnt):
+            s = torch.empty(fin, fout, dtype=torch.float32, device=dev)
+            mine.append(lambda X=X, D=D, s=s: vgc.sqgrad(vgc.FC, X, D, 1.0 / B, s, None))
+        ms = _timed(mine[0])
+        layers.append({"layer": f"fc {fin}x{fout}", "form": "fc", "count": cnt, "ms": round(ms, 4),
+                       "GBs": round(4.0 * fin * fout / ms / 1e6, 1)})
+        t_stat += cnt * ms
+        calls += mine
+
+    main = torch.cuda.current_stream()
+    side = [torch.cuda.Stream() for _ in range(4)]
+    def sweep_1():
+        for c in calls:
+            c()
+    def sweep_4():
+        start = torch.cuda.Event(); start.record(main)
+        for st_ in side:
+            st_.wait_event(start)
+        for i, c in enumerate(calls):
+            with torch.cuda.stream(side[i % 4]):
+                c()
+        for st_ in side:
+            e = torch.cuda.Event(); e.record(st_); main.wait_event(e)
+    t1, t4 = _timed(sweep_1), _timed(sweep_4)
+    return layers, t_stat, flops, t1, t4
 
 
 def _select_pack_update(dev, cfg_name, B, zeta):
@@ -481,16 +517,23 @@ def bench_vgg_iteration(dev, zeta):
     convs = [(cin, cout, sp, 3, 1, 1) for cin, cout, sp in
              [(3, 64, 224), (64, 64, 224), (64, 128, 112), (128, 128, 112), (128, 256, 56), (256, 256, 56), (256, 256, 56),
               (256, 512, 28), (512, 512, 28), (512, 512, 28), (512, 512, 14), (512, 512, 14), (512, 512, 14)]]
-    layers, t_stat, flops = _statistic_of_layers(dev, torch.bfloat16, B, convs, [(25088, 4096), (4096, 4096), (4096, 1000)])
+    layers, t_stat, flops, t1, t4 = _statistic_of_layers(dev, torch.bfloat16, B, convs, [(25088, 4096), (4096, 4096), (4096, 1000)])
     n, t_sp, rho, t_up = _select_pack_update(dev, "C4", B, zeta)
-    return {"batch": B, "n_params": n, "statistic_ms": round(t_stat, 3), "statistic_conv_TFLOPs": round(flops / 1e12, 3),
-            "select_plus_pack_ms": round(t_sp, 3), "sent_fraction": round(rho, 4),
-            "decode8_plus_momentum_sgd_ms": round(t_up, 3), "total_ms": round(t_stat + t_sp + t_up, 3), "layers": layers}
+    return _iteration_entry(B, n, layers, t_stat, flops, t1, t4, t_sp, rho, t_up)
+
+
+def _iteration_entry(B, n, layers, t_stat, flops, t1, t4, t_sp, rho, t_up):
+    """total_ms takes the statistic as one sweep over four streams, the way a training loop can issue it."""
+    return {"batch": B, "n_params": n, "statistic_sum_of_layers_ms": round(t_stat, 3),
+            "statistic_sweep_1_stream_ms": round(t1, 3), "statistic_sweep_4_streams_ms": round(t4, 3),
+            "statistic_conv_TFLOPs": round(flops / 1e12, 3), "select_plus_pack_ms": round(t_sp, 3),
+            "sent_fraction": round(rho, 4), "decode8_plus_momentum_sgd_ms": round(t_up, 3),
+            "total_ms": round(min(t1, t4) + t_sp + t_up, 3), "layers": layers}
 
 
 def bench_resnet_iteration(dev, zeta):
     """The same for the ResNet-50-shaped configuration (C3: batch 32, float32 activations); identical layers are
-    timed once and counted as often as they occur."""
+    timed alone once and issued as often as they occur in the sweeps."""
     import torch
     B = 32
     convs, count = [], []
@@ -505,17 +548,9 @@ def bench_resnet_iteration(dev, zeta):
         add((4 * width, width, sp, 1, 1, 0), blocks - 1); add((width, width, sp, 3, 1, 1), blocks - 1)
         add((width, 4 * width, sp, 1, 1, 0), blocks - 1)
         cin, prev_sp = 4 * width, sp
-    layers, _, _ = _statistic_of_layers(dev, torch.float32, B, convs, [(2048, 1000)])
-    t_stat, flops = 0.0, 0.0
-    for L, c in zip(layers, count + [1]):
-        L["count"] = c
-        t_stat += c * L["ms"]
-        if "TFLOPs" in L:
-            flops += c * L["TFLOPs"] * L["ms"] * 1e9
+    layers, t_stat, flops, t1, t4 = _statistic_of_layers(dev, torch.float32, B, convs, [(2048, 1000)], count + [1])
     n, t_sp, rho, t_up = _select_pack_update(dev, "C3", B, zeta)
-    return {"batch": B, "n_params": n, "statistic_ms": round(t_stat, 3), "statistic_conv_TFLOPs": round(flops / 1e12, 3),
-            "select_plus_pack_ms": round(t_sp, 3), "sent_fraction": round(rho, 4),
-            "decode8_plus_momentum_sgd_ms": round(t_up, 3), "total_ms": round(t_stat + t_sp + t_up, 3), "layers": layers}
+    return _iteration_entry(B, n, layers, t_stat, flops, t1, t4, t_sp, rho, t_up)
 
 
 def cpu_baseline(pair, a, cfg, sample):
