@@ -47,66 +47,48 @@ template <int W> __device__ __forceinline__ uint32_t swizzle(uint32_t row) {
 }
 
 // One 16-byte piece per lane from the bounded buffer `rsrc` (byte offset voff) to LDS byte address
-// lds_addr + 16 * lane.  Lanes outside the range deposit zeros.  Counted by vmcnt.
+// lds_base + lds_off + 16 * lane (two scalar registers, added on the way into m0).  Lanes outside the range deposit zeros.  Counted by vmcnt.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"          // m0 is named as clobbered on purpose
-__device__ __forceinline__ void load_to_lds(uint32_t lds_addr, uint32_t voff, i4v rsrc) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-                 :: "s"(lds_addr), "v"(voff), "s"(rsrc) : "memory", "m0");
+__device__ __forceinline__ void load_to_lds(uint32_t lds_base, uint32_t lds_off, uint32_t voff, i4v rsrc) {
+    asm volatile("s_add_u32 m0, %0, %1\n\ts_nop 0\n\tbuffer_load_dwordx4 %2, %3, 0 offen lds"
+                 :: "s"(lds_base), "s"(lds_off), "v"(voff), "s"(rsrc) : "memory", "m0", "scc");
 }
 #pragma clang diagnostic pop
 template <int N> __device__ __forceinline__ void wait_loads_but() {
     asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
 }
 
-// Scalar cursor over the chunks of one operand ([B, P, W] bf16): the buffer descriptor covers the rest
-// of the current sample from the chunk's first row on, so rows past P read as zeros.
-struct ChunkStream {
-    uint32_t lo, hi, rem;   // the current chunk: address of its first row (48 bits), bytes from there to the end of the sample
-    uint32_t chunk_bytes;   // from one chunk to the next inside a sample
-    uint32_t wrap_bytes;    // from the last chunk of a sample to the first of the next
+// Buffer descriptor over the current sample of one operand ([B, rows, W] bf16), all in scalar registers.  Lanes
+// address their pieces by byte offset inside the sample; rows past the sample's end read as zeros.  The window
+// moves only when the chunk requests cross into the next sample, and closes (empty range: every lane reads
+// zeros) once the workgroup's last chunk has been requested.
+struct SampleWindow {
+    uint32_t lo, hi, range;  // 48-bit address of the sample, its size in bytes
     uint32_t sample_bytes;
-    // rows_per_chunk = 0: the descriptor stays on the sample's first row (the implicit form addresses through offsets)
-    __device__ __forceinline__ void init(const uint16_t* base, uint32_t z, uint32_t P, uint32_t W, uint32_t rows_per_chunk,
-                                         uint32_t n_chunks) {
-        chunk_bytes = rows_per_chunk * W * 2u;
-        sample_bytes = P * W * 2u;
-        wrap_bytes = sample_bytes - (n_chunks - 1u) * chunk_bytes;
+    uint32_t kind;           // the descriptor's fourth word, in a register of the window's own (a shared one gets copied around)
+    __device__ __forceinline__ void init(const uint16_t* base, uint32_t z, uint32_t rows, uint32_t W) {
+        sample_bytes = __builtin_amdgcn_readfirstlane(rows * W * 2u);
         const uint64_t addr = reinterpret_cast<uint64_t>(base) + (uint64_t)z * sample_bytes;
         // everything here is uniform over the workgroup; pin it to scalar registers
         lo = __builtin_amdgcn_readfirstlane((uint32_t)addr);
         hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32) & 0xFFFFu);
-        rem = __builtin_amdgcn_readfirstlane(sample_bytes);
-        chunk_bytes = __builtin_amdgcn_readfirstlane(chunk_bytes);
-        wrap_bytes = __builtin_amdgcn_readfirstlane(wrap_bytes);
-        sample_bytes = __builtin_amdgcn_readfirstlane(sample_bytes);
+        range = sample_bytes;
+        asm volatile("s_mov_b32 %0, 0x00020000" : "=s"(kind));
     }
     __device__ __forceinline__ i4v rsrc() const {
         i4v r;
         r[0] = (int)__builtin_amdgcn_readfirstlane(lo);          // uniform values; the asm operand must be scalar registers
         r[1] = (int)__builtin_amdgcn_readfirstlane(hi);
-        r[2] = (int)__builtin_amdgcn_readfirstlane(rem);
-        r[3] = 0x00020000;
+        r[2] = (int)__builtin_amdgcn_readfirstlane(range);
+        r[3] = (int)kind;
         return r;
     }
-    __device__ __forceinline__ void skip(uint32_t chunks) {      // start `chunks` chunks into the sample
-        const uint32_t off = chunks * chunk_bytes;               // below the sample's size, which is below 2^31
-        lo += off;
-        hi += (lo < off) ? 1u : 0u;
-        rem -= off;
-        lo = __builtin_amdgcn_readfirstlane(lo);
-        hi = __builtin_amdgcn_readfirstlane(hi);
-        rem = __builtin_amdgcn_readfirstlane(rem);
+    __device__ __forceinline__ void next_sample() {
+        lo += sample_bytes;
+        hi += (lo < sample_bytes) ? 1u : 0u;
     }
-    // Moves on one chunk (into the next sample if new_sample).  Past the last chunk (!live) the range becomes and
-    // stays empty.  Scalar adds and selects only: the loop body stays one block.
-    __device__ __forceinline__ void next(bool new_sample, bool live) {
-        const uint32_t inc = new_sample ? wrap_bytes : chunk_bytes;
-        lo += inc;
-        hi += (lo < inc) ? 1u : 0u;
-        const uint32_t r = new_sample ? sample_bytes : rem - chunk_bytes;
-        rem = live ? r : 0u;
-    }
+    __device__ __forceinline__ void close() { range = 0u; }
 };
 
 // BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.  kImplicit: U is the layer's NHWC input seen
@@ -158,30 +140,38 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
 
     // ---- global side: which piece each lane fetches, per wave-wide load ----
     // Load ii of an operand covers rows ii * rpi .. + rpi - 1 of the chunk (1 KiB of the staged tile);
-    // lane l lands on row ii * rpi + l / npr, physical piece l % npr.
+    // lane l lands on row ii * rpi + l / npr, physical piece l % npr.  What is kept per load is the byte offset
+    // of the lane's piece inside the sample for the chunk requested next; one chunk further is one add.
     // In the implicit form the lane's piece of 8 columns lies inside one filter tap (Cin is a multiple
-    // of 8); what is kept per load is the tap's offset in the input and the lane's row in the chunk, and
-    // the byte offset is formed per chunk from the row's output position.
+    // of 8), and the offset is that of input element (y sh + ky - ph, x sw + kx - pw) for the lane's output
+    // position (y, x); x sw and y are kept beside it, for the tests against the image's edges, and a chunk
+    // of kKC positions further is (step_y rows, step_x columns) with at most one carry from x into y.
+    const uint32_t strideA = kImplicit ? 0u : kKC * J * 2u, strideB = kKC * C * 2u;      // bytes from chunk to chunk
     uint32_t voffA[kPerA], voffB[kPerB];
-    uint32_t y0A[kPerA], x0A[kPerA], yA[kPerA], xA[kPerA];       // output position of the lane's row: chunk 0, current chunk
-    int32_t tapY[kPerA], tapX[kPerA], tapOff[kPerA];
+    uint32_t xsA[kPerA], yA[kPerA], xs0A[kPerA], y0A[kPerA];    // implicit: x sw and y of the lane's row; the same in a sample's first chunk
+    int32_t obA[kPerA], ob0A[kPerA], tapX[kPerA];               // implicit: byte offset of the tap's element; kx - pw
+    const uint32_t sxw = G.step_x * G.sw, WoSw = G.Wo * G.sw;
+    const int32_t dO = (int32_t)((G.step_y * G.sh * G.W + sxw) * G.Cin * 2u);            // offset change per chunk, no carry
+    const int32_t dOC = dO + (int32_t)(G.sh * G.W - WoSw) * (int32_t)(G.Cin * 2u);       // ... with a carry into y
 #pragma unroll
     for (int j = 0; j < kPerA; ++j) {
         constexpr uint32_t npr = BM / 8, rpi = 64 / npr;
         const uint32_t ii = wave + (uint32_t)NW * j, row = ii * rpi + lane / npr, p = lane % npr;
         const uint32_t piece = (((p >> 2) ^ swizzle<BM>(row)) << 2) | (p & 3u);
         if (kImplicit) {
+            // A column past J (last row tile) lands on some other element of the sample or outside it: whatever
+            // comes back only reaches rows of the tile that are never stored.
             const uint32_t col = j0 + piece * 8u, tap = col / G.Cin, ky = tap / G.kw;
             const uint32_t pos0 = c_begin * kKC + row;      // the lane's row in the workgroup's first chunk
-            y0A[j] = yA[j] = pos0 / G.Wo;
-            x0A[j] = xA[j] = pos0 - y0A[j] * G.Wo;
-            tapY[j] = (int32_t)ky - (int32_t)G.ph;
+            const uint32_t y0 = pos0 / G.Wo, x0 = pos0 - y0 * G.Wo;
             tapX[j] = (int32_t)(tap - ky * G.kw) - (int32_t)G.pw;
-            // input offset (elements) of the tap relative to the row's own (y sh, x sw), plus the channel
-            tapOff[j] = (tapY[j] * (int32_t)G.W + tapX[j]) * (int32_t)G.Cin + (int32_t)(col - tap * G.Cin);
-            if (col >= J) tapY[j] = -0x400000;           // a column past J: never inside the input
+            const int32_t tapY = (int32_t)ky - (int32_t)G.ph;
+            const int32_t tapOff = (tapY * (int32_t)G.W + tapX[j]) * (int32_t)G.Cin + (int32_t)(col - tap * G.Cin);
+            xs0A[j] = xsA[j] = x0 * G.sw;
+            y0A[j] = yA[j] = y0;
+            ob0A[j] = obA[j] = ((int32_t)((y0 * G.sh * G.W + x0 * G.sw) * G.Cin) + tapOff) * 2;
         } else {
-            voffA[j] = (row * J + j0 + piece * 8u) * 2u;
+            voffA[j] = (row * J + j0 + piece * 8u) * 2u + c_begin * strideA;
         }
     }
 #pragma unroll
@@ -189,7 +179,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         constexpr uint32_t npr = BN / 8, rpi = 64 / npr;
         const uint32_t ii = wave + (uint32_t)NW * j, row = ii * rpi + lane / npr, p = lane % npr;
         const uint32_t piece = (((p >> 2) ^ swizzle<BN>(row)) << 2) | (p & 3u);
-        voffB[j] = (row * C + c0 + piece * 8u) * 2u;
+        voffB[j] = (row * C + c0 + piece * 8u) * 2u + c_begin * strideB;
     }
 
     // ---- LDS side: fragment addresses (bytes inside a buffer) for the two 32-wide tiles of each operand ----
@@ -228,59 +218,63 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         }
 
     // ---- the stream of chunk requests ----
-    ChunkStream sa, sb;
-    if (kImplicit) {
-        sa.init(U, z_begin, G.H * G.W, G.Cin, 0, n_chunks);   // the descriptor covers the whole input of the sample
-    } else {
-        sa.init(U, z_begin, P, J, kKC, n_chunks);
-    }
-    sb.init(D, z_begin, P, C, kKC, n_chunks);
-    sa.skip(c_begin);
-    sb.skip(c_begin);
-    uint32_t pcl = c_begin, issued = 0, bo_fill = 0;           // position in the sample, chunks requested, ring buffer (byte offset)
+    SampleWindow wa, wb;
+    if (kImplicit) wa.init(U, z_begin, G.H * G.W, G.Cin);       // the whole input of the sample
+    else wa.init(U, z_begin, P, J);
+    wb.init(D, z_begin, P, C);
+    // where this wave's loads land inside a staged chunk
+    uint32_t ldsA[kPerA], ldsB[kPerB];
+#pragma unroll
+    for (int j = 0; j < kPerA; ++j) ldsA[j] = __builtin_amdgcn_readfirstlane((wave + (uint32_t)NW * j) * 1024u);
+#pragma unroll
+    for (int j = 0; j < kPerB; ++j) ldsB[j] = __builtin_amdgcn_readfirstlane(kABytes + (wave + (uint32_t)NW * j) * 1024u);
     auto next_buf = [&](uint32_t bo) -> uint32_t { return bo + kBufBytes == (uint32_t)kRingBytes ? 0u : bo + kBufBytes; };
-    auto issue = [&]() {                                 // request the next chunk into the next ring buffer
-        const i4v ra = sa.rsrc(), rb = sb.rsrc();        // past the last chunk the ranges are empty: zeros arrive
+    // Requests the next chunk into the ring buffer at byte offset bo and moves the lanes' offsets on by one chunk.
+    auto issue = [&](uint32_t bo) {
+        const i4v ra = wa.rsrc(), rb = wb.rsrc();
+        const uint32_t base = lds0 + bo;
 #pragma unroll
         for (int j = 0; j < kPerA; ++j) {
             uint32_t voff;
             if (kImplicit) {
-                // All factors are below 2^23 (checked on the host): 24-bit multiplies, full rate.  Rows of the
-                // input above or below the image need no test: their offset is negative or past the sample's
-                // range, which the buffer load answers with zeros; a column outside would alias into the
+                // Rows of the input above or below the image need no test: their offset is negative or past the
+                // sample's range, which the buffer load answers with zeros; a column outside would alias into the
                 // neighbouring row, and a position past P into a valid one, so those two are masked.
-                const int32_t ys = __mul24((int32_t)yA[j], (int32_t)G.sh);
-                const int32_t xs = __mul24((int32_t)xA[j], (int32_t)G.sw);
-                const bool inside = ((uint32_t)(xs + tapX[j]) < G.W) & (yA[j] < G.Ho);
-                const int32_t lin = __mul24(ys, (int32_t)G.W) + xs;
-                const int32_t off = __mul24(lin, (int32_t)G.Cin) + tapOff[j];
-                voff = ((uint32_t)off << 1) | (inside ? 0u : 0xFFFFFFFFu);
+                const bool inside = ((uint32_t)((int32_t)xsA[j] + tapX[j]) < G.W) & (yA[j] < G.Ho);
+                voff = (uint32_t)obA[j] | (inside ? 0u : 0xFFFFFFFFu);
+                const uint32_t t = xsA[j] + sxw;
+                const bool carry = t >= WoSw;
+                xsA[j] = min(t, t - WoSw);
+                yA[j] += G.step_y + (carry ? 1u : 0u);
+                obA[j] += carry ? dOC : dO;
             } else {
                 voff = voffA[j];
+                voffA[j] += strideA;
             }
-            load_to_lds(lds0 + bo_fill + (wave + (uint32_t)NW * j) * 1024u, voff, ra);
+            load_to_lds(base, ldsA[j], voff, ra);
         }
 #pragma unroll
-        for (int j = 0; j < kPerB; ++j) load_to_lds(lds0 + bo_fill + kABytes + (wave + (uint32_t)NW * j) * 1024u, voffB[j], rb);
-        ++issued;
-        const bool wrap = (++pcl == n_chunks);
-        if (wrap) pcl = 0;
-        if (kImplicit) {
-#pragma unroll
-            for (int j = 0; j < kPerA; ++j) {            // the lane's row of the next chunk: kKC positions further
-                const uint32_t x = xA[j] + G.step_x, xw = x - G.Wo;
-                const uint32_t carry = x >= G.Wo ? 1u : 0u;
-                const uint32_t keep = wrap ? 0u : 0xFFFFFFFFu;           // bit select, not a branch on the uniform flag
-                xA[j] = (min(x, xw) & keep) | (x0A[j] & ~keep);
-                yA[j] = ((yA[j] + G.step_y + carry) & keep) | (y0A[j] & ~keep);
-            }
+        for (int j = 0; j < kPerB; ++j) {
+            load_to_lds(base, ldsB[j], voffB[j], rb);
+            voffB[j] += strideB;
         }
-        const bool live = issued < total;
-        sa.next(wrap, live);
-        sb.next(wrap, live);
-        bo_fill = next_buf(bo_fill);
     };
-    auto sample_end = [&]() {                            // G_z is complete in acc: square into s, add into g, clear
+    // The rare steps, kept out of the per-chunk code: the requests cross into the next sample ...
+    auto wrap = [&]() {
+        wa.next_sample();
+        wb.next_sample();
+#pragma unroll
+        for (int j = 0; j < kPerA; ++j) {
+            if (kImplicit) { xsA[j] = xs0A[j]; yA[j] = y0A[j]; obA[j] = ob0A[j]; }
+            else voffA[j] -= n_chunks * strideA;
+        }
+#pragma unroll
+        for (int j = 0; j < kPerB; ++j) voffB[j] -= n_chunks * strideB;
+    };
+    // ... the last chunk has been requested: whatever is requested after it is zeros ...
+    auto close = [&]() { wa.close(); wb.close(); };
+    // ... and the per-sample product G_z is complete in acc: square into s, add into g, clear.
+    auto sample_end = [&]() {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -300,11 +294,36 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     // count of the pipelined loop is rounded up to a multiple of its unroll factor; the surplus chunks are
     // all zeros and add nothing.
     constexpr int kInFlight = (kNB - 2) * kPer;
-    uint32_t left = split_p > 1 ? 0u : n_chunks;         // chunks until the current sample's product is complete (0: never)
+    constexpr uint32_t kNever = 0x3FFFFFFFu;
+    // chunks until: the requests reach the end of a sample, the last request, the consumed sample is complete
+    uint32_t to_wrap = __builtin_amdgcn_readfirstlane(n_chunks - c_begin);
+    uint32_t todo = __builtin_amdgcn_readfirstlane(total);
+    {
+        uint32_t bo = 0;
 #pragma unroll 1
-    for (int i = 0; i < kNB; ++i) issue();
+        for (int i = 0; i < kNB; ++i) {
+            issue(bo);
+            bo = next_buf(bo);
+            if (--to_wrap == 0) { to_wrap = n_chunks; wrap(); }
+            if (--todo == 0) { todo = kNever; close(); }
+        }
+    }
+    uint32_t left = split_p > 1 ? kNever : n_chunks;     // (with the positions split the product is stored unsquared)
+    // One countdown serves the three: `span` chunks from the last rare step to the next one.
+    uint32_t span = min(left, min(to_wrap, todo)), ev = span;
+    auto tick = [&]() {                                  // after chunk q is consumed and chunk q + kNB requested
+        if (--ev == 0) {
+            left -= span; to_wrap -= span; todo -= span;
+            // (a surplus chunk may complete a "sample" of zeros when P fits one chunk: it adds nothing)
+            if (left == 0) { left = n_chunks; sample_end(); }
+            if (to_wrap == 0) { to_wrap = n_chunks; wrap(); }
+            if (todo == 0) { todo = kNever; close(); }
+            span = ev = min(left, min(to_wrap, todo));
+        }
+    };
     wait_loads_but<kInFlight>();                         // chunks 0 and 1 have landed
     __syncthreads();
+    uint32_t bo_cur = 0;                                 // buffer of the chunk being consumed
     if constexpr (!kWantG) {
         // Pipelined across the barrier: the operand fragments of chunk q+1 are read from LDS while the
         // MFMAs of chunk q run from registers.
@@ -317,7 +336,6 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                 F[0][ks][1][t] = frag_b(0, ks, t);
             }
         __syncthreads();                                 // buffer 0 is free
-        uint32_t bo_next = kBufBytes;                    // buffer of chunk q+1
         // A wave issues in order, and the two waves of a SIMD run in lockstep between barriers: if the
         // MFMAs sat in one block and the LDS traffic in another, the matrix pipe would idle during the
         // LDS phase and vice versa.  So the instruction stream is interleaved by hand: after every MFMA
@@ -326,6 +344,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         for (uint32_t q0 = 0; q0 < total; q0 += 2) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {                // chunk q = q0 + u lives in fragment set u
+                const uint32_t bo_next = next_buf(bo_cur);
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {            // MFMA i = (ks, mt, nt); fragment i = (ks, A/B, t) of chunk q+1
                     const int ks = i >> 2, mt = (i >> 1) & 1, nt = i & 1;
@@ -333,22 +352,20 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                     const int fk = i >> 2, fo = (i >> 1) & 1, ft = i & 1;
                     if (fo == 0) F[u ^ 1][fk][0][ft] = frag_a(bo_next, fk, ft);
                     else F[u ^ 1][fk][1][ft] = frag_b(bo_next, fk, ft);
-                    if (i == 3) issue();                 // chunk q + kNB into chunk q's buffer
+                    if (i == 3) issue(bo_cur);           // chunk q + kNB into chunk q's buffer
                 }
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {            // pin the order above for the instruction scheduler
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);      // two LDS reads
                 }
-                bo_next = next_buf(bo_next);
-                // (a surplus chunk may complete a "sample" of zeros when P fits one chunk: it adds nothing)
-                if (--left == 0) { left = n_chunks; sample_end(); }
+                bo_cur = bo_next;
+                tick();
                 wait_loads_but<kInFlight>();             // chunk q+2 has landed (this wave's pieces)
                 __syncthreads();
             }
         }
     } else {
-        uint32_t bo_cur = 0;
         for (uint32_t q = 0; q < total; ++q) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
@@ -364,11 +381,11 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                     for (int nt = 0; nt < 2; ++nt)
                         acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
             }
-            if (--left == 0) { left = n_chunks; sample_end(); }
-            bo_cur = next_buf(bo_cur);
             wait_loads_but<kInFlight>();                 // chunk q+1 has landed (this wave's pieces)
             __syncthreads();                             // ... everybody's, and chunk q's buffer is free
-            issue();                                     // chunk q + kNB into chunk q's buffer
+            issue(bo_cur);                               // chunk q + kNB into chunk q's buffer
+            bo_cur = next_buf(bo_cur);
+            tick();
         }
     }
     wait_loads_but<0>();                                 // nothing may still be landing when the workgroup ends
