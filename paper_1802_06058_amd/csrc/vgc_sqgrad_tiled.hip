@@ -656,7 +656,8 @@ int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint3
 
 bool conv2d_supported(int dtype, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t P) {
     const uint64_t limit = 0x7FFFFFFFull;               // buffer ranges and offsets are 32-bit
-    // the kernels' address arithmetic multiplies (y sh W + x sw) by Cin with 24-bit multiplies
+    // the fp32 kernel's address arithmetic multiplies (y sh W + x sw) by Cin with 24-bit multiplies; the same
+    // limits keep the bf16 kernel's incremental offsets inside 32 bits
     const uint64_t m24 = 1u << 23;
     const uint64_t es = dtype == VGC_BF16 ? 2 : 4, piece = 16 / es;
     return (dtype == VGC_BF16 || dtype == VGC_F32) && (Cin % piece == 0) && (C % piece == 0) &&
