@@ -106,6 +106,9 @@ def test_conv_form(dev, B, P, J, C, prec):
     assert (np.abs(g1 - g64) / absG).max() <= tol and (np.abs(s1 - s64) / sabs).max() <= tol
     _, s2 = _run(vgc.CONV, U, D, c, dev, bf16, want_g=False)
     assert np.array_equal(s, s2)
+    # ... also when one workgroup walks through all the samples (the s-only kernel has a loop of its own)
+    _, s3 = _run(vgc.CONV, U, D, c, dev, bf16, want_g=False, use_workspace=False)
+    assert np.array_equal(s1, s3)
 
 
 def test_sampled_outputs_at_vgg_fc6_shape(dev):

@@ -101,6 +101,10 @@ def test_conv2d_matches_oracle(dev, geom, prec):
     assert (np.abs(g1 - g64) / np.maximum(absG, 1e-300)).max() <= TOL and (np.abs(s1 - s64) / np.maximum(sabs, 1e-300)).max() <= TOL
     _, s2 = _run(A, D, kh, kw, stride, pad, c, dev, want_g=False)
     assert (np.abs(s2 - s64) / np.maximum(sabs, 1e-300)).max() <= TOL
+    assert np.array_equal(s2, s)
+    # ... also when one workgroup walks through all the samples (the s-only kernel has a loop of its own)
+    _, s3 = _run(A, D, kh, kw, stride, pad, c, dev, want_g=False, use_workspace=False)
+    assert np.array_equal(s3, s1)
 
 
 def test_conv2d_equals_patch_matrix_path(dev):
@@ -139,6 +143,8 @@ def test_conv2d_sampled_outputs_at_vgg_conv4_shape(dev):
         j = (ky * 3 + kx) * Cin + i
         assert abs(g[j, o] - per_sample.sum()) <= TOL * mag.sum()
         assert abs(s[j, o] - (per_sample ** 2).sum()) <= TOL * (mag ** 2).sum()
+    _, s_only = _run(A, D, kh, kw, stride, pad, 1.0 / B, dev, want_g=False)    # the kernel the benchmark times
+    assert np.array_equal(s_only, s)
 
 
 def test_conv2d_rejects_what_it_cannot_do(dev):
