@@ -185,13 +185,21 @@ __device__ __forceinline__ void tile_body(const float* __restrict__ g, const flo
     }
 
     // histogram of rel over the wave (uniform values; scalar popcounts)
-#pragma unroll
-    for (int j = 0; j < (int)kRelBins; ++j) {
+    if (kHybrid) {
+        // every staged element is +-1.0f and so is the tile's maximum: rel = 1 for all of them
         uint32_t cnt = 0;
 #pragma unroll
-        for (int e = 0; e < E; ++e)
-            cnt += __popcll(__ballot(((stagedmask >> e) & 1u) && ((entry[e] >> 12) == (uint32_t)j)));
-        if (lane == 0) sh_hist[wave][j] = cnt;
+        for (int e = 0; e < E; ++e) cnt += __popcll(__ballot((stagedmask >> e) & 1u));
+        if (lane < kRelBins) sh_hist[wave][lane] = (lane == 1u) ? cnt : 0u;
+    } else {
+#pragma unroll
+        for (int j = 0; j < (int)kRelBins; ++j) {
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int e = 0; e < E; ++e)
+                cnt += __popcll(__ballot(((stagedmask >> e) & 1u) && ((entry[e] >> 12) == (uint32_t)j)));
+            if (lane == 0) sh_hist[wave][j] = cnt;
+        }
     }
 
     // rank of each staged element inside its segment, and segment totals
