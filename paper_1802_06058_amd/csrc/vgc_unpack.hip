@@ -61,7 +61,7 @@ int launch_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_h
 // ------------------------------------------------------------------------------------------------
 namespace vgc {
 
-constexpr int kRounds = 4;          // words per lane loaded ahead per message
+constexpr int kRounds = 8;          // words per lane loaded ahead per message
 
 template <int kMax>
 struct BatchArgs {
