@@ -229,12 +229,12 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
 #pragma unroll
     for (int j = 0; j < kPerB; ++j) ldsB[j] = __builtin_amdgcn_readfirstlane(kABytes + (wave + (uint32_t)NW * j) * 1024u);
     auto next_buf = [&](uint32_t bo) -> uint32_t { return bo + kBufBytes == (uint32_t)kRingBytes ? 0u : bo + kBufBytes; };
-    // Requests the next chunk into the ring buffer at byte offset bo and moves the lanes' offsets on by one chunk.
-    auto issue = [&](uint32_t bo) {
-        const i4v ra = wa.rsrc(), rb = wb.rsrc();
+    // Load n (A loads first, then B loads) of the request for the next chunk, into the ring buffer at byte offset
+    // bo; moves the lane's offset for that load on by one chunk.
+    auto issue_one = [&](uint32_t bo, int n) {
         const uint32_t base = lds0 + bo;
-#pragma unroll
-        for (int j = 0; j < kPerA; ++j) {
+        if (n < kPerA) {
+            const int j = n;
             uint32_t voff;
             if (kImplicit) {
                 // Rows of the input above or below the image need no test: their offset is negative or past the
@@ -251,13 +251,16 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                 voff = voffA[j];
                 voffA[j] += strideA;
             }
-            load_to_lds(base, ldsA[j], voff, ra);
-        }
-#pragma unroll
-        for (int j = 0; j < kPerB; ++j) {
-            load_to_lds(base, ldsB[j], voffB[j], rb);
+            load_to_lds(base, ldsA[j], voff, wa.rsrc());
+        } else {
+            const int j = n - kPerA;
+            load_to_lds(base, ldsB[j], voffB[j], wb.rsrc());
             voffB[j] += strideB;
         }
+    };
+    auto issue = [&](uint32_t bo) {                      // the whole request
+#pragma unroll
+        for (int n = 0; n < kPer; ++n) issue_one(bo, n);
     };
     // The rare steps, kept out of the per-chunk code: the requests cross into the next sample ...
     auto wrap = [&]() {
@@ -352,7 +355,10 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                     const int fk = i >> 2, fo = (i >> 1) & 1, ft = i & 1;
                     if (fo == 0) F[u ^ 1][fk][0][ft] = frag_a(bo_next, fk, ft);
                     else F[u ^ 1][fk][1][ft] = frag_b(bo_next, fk, ft);
-                    if (i == 3) issue(bo_cur);           // chunk q + kNB into chunk q's buffer
+                    // chunk q + kNB into chunk q's buffer, its loads spread over MFMAs 1 .. 6 (all at once costs 1-3 %)
+#pragma unroll
+                    for (int n = 0; n < kPer; ++n)
+                        if (i == 1 + (n * 6) / kPer) issue_one(bo_cur, n);
                 }
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {            // pin the order above for the instruction scheduler
