@@ -71,6 +71,10 @@ GEOMS = [  # B, H, W, Cin, C, kh, kw, stride, pad
     (2, 16, 16, 256, 128, 3, 3, (1, 1), (1, 1)),   # a 256-column tile inside one tap
     (2, 40, 37, 16, 16, 3, 3, (1, 1), (1, 1)),     # one tile, 1480 positions: the positions are split over workgroups
     (3, 64, 50, 8, 24, 3, 3, (2, 1), (1, 1)),      # the same with a stride
+    (2, 39, 27, 112, 96, 5, 5, (3, 1), (3, 1)),    # 5x5, stride 3 down, padding larger than the stride
+    (5, 9, 11, 144, 128, 2, 5, (1, 2), (1, 2)),    # even kernel height, wide kernel
+    (3, 23, 31, 32, 24, 4, 2, (3, 3), (0, 0)),     # stride larger than the kernel's width: input columns skipped
+    (1, 73, 72, 32, 32, 5, 4, (1, 2), (0, 0)),     # one sample, 2415 positions
 ]
 
 
