@@ -80,7 +80,8 @@ def test_fc_form(dev, B, J, C, prec):
 
 @pytest.mark.parametrize("B,P,J,C", [(4, 49, 64, 64), (3, 5, 27, 16), (2, 1, 40, 40), (8, 196, 576, 64), (5, 9, 100, 33),
                                      (6, 33, 200, 136), (3, 64, 384, 256), (2, 784, 128, 128),
-                                     (3, 2000, 64, 72), (2, 1111, 24, 16)])      # few tiles, many positions: split over positions
+                                     (3, 2000, 64, 72), (2, 1111, 24, 16),       # few tiles, many positions: split over positions
+                                     (40, 100, 1024, 512)])                      # more (tile, sample) pairs than workgroup slots: several samples per workgroup
 @pytest.mark.parametrize("prec", ["f32", "bf16"])
 def test_conv_form(dev, B, P, J, C, prec):
     from paper_1802_06058_amd import vgc
