@@ -147,3 +147,15 @@ def test_conv2d_and_update_argument_checks_need_no_gpu():
     assert call(opt, 0, fake) == -6
     opt.kind, opt.step = vgc.MOMENTUM_SGD, 1
     assert call(opt, 65) == -1                                     # message tables missing
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: bench.py --gpus N with N above 1 exits with a message that says so,
+    before anything touches a GPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0
+    assert "one GPU" in p.stderr
+    assert p.stdout.strip() == ""
