@@ -180,7 +180,7 @@ __device__ __forceinline__ void stage32(float* A, float* Bm, const Chunk32& R, u
 template <bool kConv, bool kWantG, bool kImplicit>
 __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
                                                       uint32_t B, uint32_t P, uint32_t J, uint32_t C,
-                                                      uint32_t z_per_split, uint32_t splits, uint32_t split_p, float cg, float cs,
+                                                      uint32_t splits, uint32_t split_p, float cg, float cs,
                                                       float* __restrict__ g_out, float* __restrict__ s_out,
                                                       float* __restrict__ ws, ConvGeom G) {
     __shared__ __attribute__((aligned(16))) float shA[2][kR32 * kPitch32];
@@ -199,8 +199,9 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
     const uint32_t part = split_p > 1 ? split % split_p : 0u;
     const uint32_t chunks_per_part = (n_chunks + split_p - 1) / split_p;
     const uint32_t c_begin = min(n_chunks, part * chunks_per_part);
-    const uint32_t z_begin = !kConv ? 0u : (split_p > 1 ? split / split_p : split * z_per_split);
-    const uint32_t z_end = !kConv ? 1u : (split_p > 1 ? z_begin + 1u : min(B, z_begin + z_per_split));
+    // sample ranges of the splits differ by at most one sample
+    const uint32_t z_begin = !kConv ? 0u : (split_p > 1 ? split / split_p : (uint32_t)((uint64_t)split * B / splits));
+    const uint32_t z_end = !kConv ? 1u : (split_p > 1 ? z_begin + 1u : (uint32_t)((uint64_t)(split + 1u) * B / splits));
     const uint32_t total = split_p > 1 ? min(n_chunks, c_begin + chunks_per_part) - c_begin : (z_end - z_begin) * n_chunks;
 
     f16v acc[2][2], s_acc[2][2], g_acc[2][2];
@@ -370,8 +371,8 @@ int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_
         if (g_out) hipLaunchKernelGGL(k_fc_bf16<true>, dim3((uint32_t)nblk), dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, J, C, cg, cs, g_out, s_out);
         else hipLaunchKernelGGL(k_fc_bf16<false>, dim3((uint32_t)nblk), dim3(256), 0, stream, (const uint16_t*)X, (const uint16_t*)D, B, J, C, cg, cs, g_out, s_out);
     } else {
-        if (g_out) hipLaunchKernelGGL((k_tiled_f32<false, true, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
-        else hipLaunchKernelGGL((k_tiled_f32<false, false, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, B, 1u, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
+        if (g_out) hipLaunchKernelGGL((k_tiled_f32<false, true, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, 1u, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
+        else hipLaunchKernelGGL((k_tiled_f32<false, false, false>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, 1u, J, C, 1u, 1u, cg, cs, g_out, s_out, (float*)nullptr, ConvGeom{});
     }
     return hip_check(hipGetLastError(), "launch fc tiled");
 }
@@ -403,18 +404,13 @@ static int launch_conv_f32_any(const void* X, const void* D, uint32_t B, uint32_
     if (split_p > 1 && (!workspace || workspace_bytes < (size_t)B * split_p * JC * sizeof(float))) split_p = 1;
     uint32_t splits = split_p > 1 ? B * split_p : conv_f32_splits(B, J, C);
     if (split_p == 1 && splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * JC * sizeof(float))) splits = 1;
-    uint32_t zper = 1;
-    if (split_p == 1) {
-        zper = (B + splits - 1) / splits;
-        splits = (B + zper - 1) / zper;
-    }
     const uint64_t nblk = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT) * splits;
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
     // with the positions split the partial products are unsquared: the variant without g serves both
-    if (g_out && split_p == 1) hipLaunchKernelGGL((k_tiled_f32<true, true, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
-    else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    if (g_out && split_p == 1) hipLaunchKernelGGL((k_tiled_f32<true, true, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
     if (split_p > 1) launch_sqgrad_reduce_parts(ws, B, split_p, JC, cg, cs, g_out, s_out, stream);
     else if (splits > 1) launch_sqgrad_reduce(ws, splits, JC, cg, cs, g_out, s_out, stream);
     return hip_check(hipGetLastError(), "launch k_tiled_f32");

@@ -97,7 +97,7 @@ template <int BM, int BN, bool kWantG, bool kImplicit>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
 void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                  uint32_t B, uint32_t P, uint32_t J, uint32_t C,
-                 uint32_t z_per_split, uint32_t splits, uint32_t split_p, float cg, float cs,
+                 uint32_t splits, uint32_t split_p, float cg, float cs,
                  float* __restrict__ g_out, float* __restrict__ s_out, float* __restrict__ ws, ConvGeom G) {
     constexpr int NW = (BM / 64) * (BN / 64);
     constexpr int kABytes = kKC * BM * 2, kBBytes = kKC * BN * 2, kBufBytes = kABytes + kBBytes;
@@ -130,8 +130,9 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     const uint32_t part = split_p > 1 ? split % split_p : 0u;
     const uint32_t chunks_per_part = (n_chunks + split_p - 1) / split_p;
     const uint32_t c_begin = min(n_chunks, part * chunks_per_part);
-    const uint32_t z_begin = split_p > 1 ? split / split_p : split * z_per_split;
-    const uint32_t z_end = split_p > 1 ? z_begin + 1u : min(B, z_begin + z_per_split);
+    // sample ranges of the splits differ by at most one sample
+    const uint32_t z_begin = split_p > 1 ? split / split_p : (uint32_t)((uint64_t)split * B / splits);
+    const uint32_t z_end = split_p > 1 ? z_begin + 1u : (uint32_t)((uint64_t)(split + 1u) * B / splits);
     const uint32_t total = split_p > 1 ? min(n_chunks, c_begin + chunks_per_part) - c_begin : (z_end - z_begin) * n_chunks;
 
     // the compiler must see a store to the array: everything else arrives behind its back
@@ -611,16 +612,16 @@ void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg,
 
 template <int BM, int BN, bool kImplicit>
 static void launch_conv_bf16(uint32_t nblk, hipStream_t stream, const void* X, const void* D, uint32_t B, uint32_t P,
-                             uint32_t J, uint32_t C, uint32_t zper, uint32_t splits, uint32_t split_p, float cg, float cs,
+                             uint32_t J, uint32_t C, uint32_t splits, uint32_t split_p, float cg, float cs,
                              float* g_out, float* s_out, float* ws, const ConvGeom& G) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
     // with the positions split the partial products are unsquared: the variant without g serves both
     if (g_out && split_p == 1)
         hipLaunchKernelGGL((k_conv_bf16<BM, BN, true, kImplicit>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
-                           (const uint16_t*)D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+                           (const uint16_t*)D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
     else
         hipLaunchKernelGGL((k_conv_bf16<BM, BN, false, kImplicit>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
-                           (const uint16_t*)D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+                           (const uint16_t*)D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
 }
 
 template <bool kImplicit>
@@ -633,19 +634,14 @@ static int launch_conv_any(const void* X, const void* D, uint32_t B, uint32_t P,
     if (split_p > 1 && (!workspace || workspace_bytes < (size_t)B * split_p * JC * sizeof(float))) split_p = 1;
     uint32_t splits = split_p > 1 ? B * split_p : conv_splits(B, J, C);
     if (split_p == 1 && splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * JC * sizeof(float))) splits = 1;
-    uint32_t zper = 1;
-    if (split_p == 1) {
-        zper = (B + splits - 1) / splits;
-        splits = (B + zper - 1) / zper;
-    }
     const uint64_t nblk = (uint64_t)((C + t.bn - 1) / t.bn) * ((J + t.bm - 1) / t.bm) * splits;
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
-    if (t.bm == 256 && t.bn == 128) launch_conv_bf16<256, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
-    else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
-    else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
-    else launch_conv_bf16<128, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, zper, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    if (t.bm == 256 && t.bn == 128) launch_conv_bf16<256, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    else launch_conv_bf16<128, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
     if (split_p > 1) {
         launch_sqgrad_reduce_parts(ws, B, split_p, JC, cg, cs, g_out, s_out, stream);
         return hip_check(hipGetLastError(), "launch k_conv_bf16");
