@@ -61,7 +61,6 @@ int launch_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_h
 // ------------------------------------------------------------------------------------------------
 namespace vgc {
 
-constexpr int kRounds = 8;          // words per lane loaded ahead per message
 
 template <int kMax>
 struct BatchArgs {
@@ -121,6 +120,9 @@ __global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs<kMax> A, con
                                                           const PlanRun* __restrict__ runs, uint32_t n_runs,
                                                           float scale, float* __restrict__ dense, int overwrite,
                                                           UpdateArgs O, uint32_t tiles_per_wave) {
+    // wave-wide word loads in flight per message: eight where the words are most of what the wave waits for, four
+    // where the optimizer's arrays are in flight as well (there the words loaded past the tile's end cost more)
+    constexpr int kRounds = kMode == kToDense ? 8 : 4;
     __shared__ __attribute__((aligned(16))) float sh_tile[4][kTile];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     // a run of kRunTiles tiles is shared by kRunTiles / tiles_per_wave waves (small parameter sets have few runs)
