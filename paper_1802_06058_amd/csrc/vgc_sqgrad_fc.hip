@@ -27,7 +27,6 @@ typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 constexpr int kT = 128;                  // block tile edge
 constexpr int kPitch16 = kT + 32;        // bf16 row pitch (elements): rows start 16 banks apart
-constexpr int kPitch32 = kT + 32;        // float row pitch (elements): rows start 32 banks apart
 
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes) {
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
@@ -150,24 +149,37 @@ __global__ __launch_bounds__(256, 2) void k_fc_bf16(const uint16_t* __restrict__
 // ------------------------------------------------------------------------------------------------
 constexpr int kR32 = 16;                 // rows per LDS stage
 
-struct Chunk32 { f4v a[2], b[2]; };
+// One staged chunk in registers: kR32 rows of a BM-wide and of a BN-wide float matrix, PA resp. PB 16-byte
+// pieces per thread of a workgroup of NT threads.  Piece idx of an operand W columns wide sits in row
+// idx / (W / 4), columns 4 (idx % (W / 4)) .. + 3.
+template <int PA, int PB> struct Chunk32 { f4v a[PA], b[PB]; };
 
-__device__ __forceinline__ void load32(Chunk32& R, rsrc_t ra, rsrc_t rb, uint32_t J, uint32_t C, uint32_t p0,
+template <int BM, int BN, int NT, int PA, int PB>
+__device__ __forceinline__ void load32(Chunk32<PA, PB>& R, rsrc_t ra, rsrc_t rb, uint32_t J, uint32_t C, uint32_t p0,
                                        uint32_t j0, uint32_t c0, uint32_t tid) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const uint32_t idx = tid + 256u * i, row = idx >> 5, col = (idx & 31u) * 4u;
+    for (int i = 0; i < PA; ++i) {
+        const uint32_t idx = tid + (uint32_t)NT * i, row = idx / (BM / 4), col = (idx % (BM / 4)) * 4u;
         R.a[i] = __builtin_bit_cast(f4v, __builtin_amdgcn_raw_buffer_load_b128(ra, (int)(((p0 + row) * J + j0 + col) * 4u), 0, 0));
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+        const uint32_t idx = tid + (uint32_t)NT * i, row = idx / (BN / 4), col = (idx % (BN / 4)) * 4u;
         R.b[i] = __builtin_bit_cast(f4v, __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(((p0 + row) * C + c0 + col) * 4u), 0, 0));
     }
 }
 
-__device__ __forceinline__ void stage32(float* A, float* Bm, const Chunk32& R, uint32_t tid) {
+template <int BM, int BN, int NT, int PA, int PB>
+__device__ __forceinline__ void stage32(float* A, float* Bm, const Chunk32<PA, PB>& R, uint32_t tid) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const uint32_t idx = tid + 256u * i, off = (idx >> 5) * kPitch32 + (idx & 31u) * 4u;
-        *reinterpret_cast<f4v*>(A + off) = R.a[i];
-        *reinterpret_cast<f4v*>(Bm + off) = R.b[i];
+    for (int i = 0; i < PA; ++i) {
+        const uint32_t idx = tid + (uint32_t)NT * i;
+        *reinterpret_cast<f4v*>(A + (idx / (BM / 4)) * (BM + 32) + (idx % (BM / 4)) * 4u) = R.a[i];
+    }
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+        const uint32_t idx = tid + (uint32_t)NT * i;
+        *reinterpret_cast<f4v*>(Bm + (idx / (BN / 4)) * (BN + 32) + (idx % (BN / 4)) * 4u) = R.b[i];
     }
 }
 
@@ -177,21 +189,26 @@ __device__ __forceinline__ void stage32(float* A, float* Bm, const Chunk32& R, u
 // kImplicit (with kConv): X is the layer's NHWC input [B, H, W, Cin] seen through the geometry G, J = kh kw Cin; the
 //         lane's piece of 4 columns lies inside one filter tap (Cin is a multiple of 4) and its offset in the input
 //         is formed per chunk from the output position of its row, which is kept incrementally.
-template <bool kConv, bool kWantG, bool kImplicit>
-__global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
-                                                      uint32_t B, uint32_t P, uint32_t J, uint32_t C,
-                                                      uint32_t splits, uint32_t split_p, float cg, float cs,
-                                                      float* __restrict__ g_out, float* __restrict__ s_out,
-                                                      float* __restrict__ ws, ConvGeom G) {
-    __shared__ __attribute__((aligned(16))) float shA[2][kR32 * kPitch32];
-    __shared__ __attribute__((aligned(16))) float shB[2][kR32 * kPitch32];
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, wm = wave >> 1, wn = wave & 1u;
-    const uint32_t tiles_c = (C + kT - 1) / kT, tiles_j = (J + kT - 1) / kT;
+// BM x BN: the block tile (64 or 128 each), one wave per 64 x 64 of it; rows of LDS are padded by 32 floats.
+template <bool kConv, bool kWantG, bool kImplicit, int BM = 128, int BN = 128>
+__global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
+void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
+                 uint32_t B, uint32_t P, uint32_t J, uint32_t C,
+                 uint32_t splits, uint32_t split_p, float cg, float cs,
+                 float* __restrict__ g_out, float* __restrict__ s_out,
+                 float* __restrict__ ws, ConvGeom G) {
+    constexpr int NT = (BM / 64) * (BN / 64) * 64;                   // threads of the workgroup
+    constexpr int PA = kR32 * BM / 4 / NT, PB = kR32 * BN / 4 / NT;  // 16-byte pieces per thread and chunk
+    constexpr int kPitchA = BM + 32, kPitchB = BN + 32;
+    __shared__ __attribute__((aligned(16))) float shA[2][kR32 * kPitchA];
+    __shared__ __attribute__((aligned(16))) float shB[2][kR32 * kPitchB];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6, wm = wave / (BN / 64), wn = wave % (BN / 64);
+    const uint32_t tiles_c = (C + BN - 1) / BN, tiles_j = (J + BM - 1) / BM;
     const uint32_t nblk = gridDim.x, per = nblk / 8u, rem = nblk % 8u;
     const uint32_t xcd = blockIdx.x % 8u, slot = blockIdx.x / 8u;
     const uint32_t logical = xcd * per + min(xcd, rem) + slot;       // contiguous range of tiles per XCD
     const uint32_t tile_c = logical % tiles_c, tile_j = (logical / tiles_c) % tiles_j, split = logical / (tiles_c * tiles_j);
-    const uint32_t j0 = tile_j * kT, c0 = tile_c * kT;
+    const uint32_t j0 = tile_j * BM, c0 = tile_c * BN;
     const uint32_t rowsP = kConv ? P : B;                            // K extent of one "sample"
     // split_p > 1 (conv only): the workgroup owns part `part` of the positions of the single sample split / split_p
     // and leaves the unsquared partial product in the workspace
@@ -211,12 +228,12 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
         for (int b = 0; b < 2; ++b) { acc[a][b] = (f16v){0}; s_acc[a][b] = (f16v){0}; g_acc[a][b] = (f16v){0}; }
 
     // implicit form: per load, the tap of the lane's columns and the output position of its row
-    uint32_t y0A[2], x0A[2], yA[2], xA[2];
-    int32_t tapX[2], tapOff[2];
+    uint32_t y0A[PA], x0A[PA], yA[PA], xA[PA];
+    int32_t tapX[PA], tapOff[PA];
     if (kImplicit) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            const uint32_t idx = tid + 256u * i, row = idx >> 5, colj = j0 + (idx & 31u) * 4u;
+        for (int i = 0; i < PA; ++i) {
+            const uint32_t idx = tid + (uint32_t)NT * i, row = idx / (BM / 4), colj = j0 + (idx % (BM / 4)) * 4u;
             const uint32_t tap = colj / G.Cin, ky = tap / G.kw;
             const uint32_t pos0 = c_begin * kR32 + row;           // the lane's row in the workgroup's first chunk
             y0A[i] = yA[i] = pos0 / G.Wo;
@@ -227,7 +244,7 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
             if (colj >= J) tapX[i] = -0x400000;              // a column past J: never inside the input
         }
     }
-    Chunk32 R[2];
+    Chunk32<PA, PB> R[2];
     uint32_t zl = z_begin, pcl = c_begin, issued = 0;
     auto issue = [&](int slot_) {
         const bool live = issued < total;
@@ -237,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
             const uint32_t sample = G.H * G.W * G.Cin;
             const rsrc_t ra = make_rsrc(X + (size_t)zz * sample, live ? sample * 4u : 0u);
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < PA; ++i) {
                 // rows of the input outside the image give an offset that is negative or past the sample: the load
                 // answers with zeros; columns outside and positions past P are masked
                 const int32_t ys = __mul24((int32_t)yA[i], (int32_t)G.sh), xs = __mul24((int32_t)xA[i], (int32_t)G.sw);
@@ -245,18 +262,21 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
                 const int32_t off = __mul24(__mul24(ys, (int32_t)G.W) + xs, (int32_t)G.Cin) + tapOff[i];
                 const uint32_t voff = ((uint32_t)off << 2) | (inside ? 0u : 0xFFFFFFFFu);
                 R[slot_].a[i] = __builtin_bit_cast(f4v, __builtin_amdgcn_raw_buffer_load_b128(ra, (int)voff, 0, 0));
-                const uint32_t idx = tid + 256u * i, row = idx >> 5, col = (idx & 31u) * 4u;
+            }
+#pragma unroll
+            for (int i = 0; i < PB; ++i) {
+                const uint32_t idx = tid + (uint32_t)NT * i, row = idx / (BN / 4), col = (idx % (BN / 4)) * 4u;
                 R[slot_].b[i] = __builtin_bit_cast(f4v, __builtin_amdgcn_raw_buffer_load_b128(rb, (int)(((pcl * kR32 + row) * C + c0 + col) * 4u), 0, 0));
             }
         } else {
             const rsrc_t ra = make_rsrc(X + (size_t)zz * rowsP * J, live ? rowsP * J * 4u : 0u);
-            load32(R[slot_], ra, rb, J, C, pcl * kR32, j0, c0, tid);
+            load32<BM, BN, NT>(R[slot_], ra, rb, J, C, pcl * kR32, j0, c0, tid);
         }
         const bool wrap = (++pcl == n_chunks);
         if (wrap) { pcl = 0; ++zl; }
         if (kImplicit) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {                     // the lane's row of the next chunk: kR32 positions further
+            for (int i = 0; i < PA; ++i) {                    // the lane's row of the next chunk: kR32 positions further
                 const uint32_t x = xA[i] + G.step_x, xw = x - G.Wo;
                 const uint32_t carry = x >= G.Wo ? 1u : 0u;
                 const uint32_t keep = wrap ? 0u : 0xFFFFFFFFu;
@@ -268,7 +288,7 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
     };
     issue(0);
     issue(1);
-    stage32(shA[0], shB[0], R[0], tid);
+    stage32<BM, BN, NT>(shA[0], shB[0], R[0], tid);
     issue(0);
     __syncthreads();
 
@@ -285,8 +305,8 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
                 float a[2], b[2];
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    a[t] = A[(ks * 2 + kh) * kPitch32 + wm * 64 + t * 32 + col];
-                    b[t] = Bm[(ks * 2 + kh) * kPitch32 + wn * 64 + t * 32 + col];
+                    a[t] = A[(ks * 2 + kh) * kPitchA + wm * 64 + t * 32 + col];
+                    b[t] = Bm[(ks * 2 + kh) * kPitchB + wn * 64 + t * 32 + col];
                 }
 #pragma unroll
                 for (int mt = 0; mt < 2; ++mt)
@@ -301,7 +321,7 @@ __global__ __launch_bounds__(256, 2) void k_tiled_f32(const float* __restrict__ 
                     }
             }
             const int ns = u ^ 1;
-            stage32(shA[buf ^ 1u], shB[buf ^ 1u], R[ns], tid);
+            stage32<BM, BN, NT>(shA[buf ^ 1u], shB[buf ^ 1u], R[ns], tid);
             issue(ns);
             if (kConv && --left == 0) {                           // sample finished: G_z is complete in acc
                 left = n_chunks;                                  // (a surplus chunk of zeros may "finish" a sample: adds nothing)
@@ -347,9 +367,29 @@ bool conv_f32_tiled_supported(uint32_t P, uint32_t J, uint32_t C) {
     return J % 4 == 0 && C % 4 == 0 && (uint64_t)(P + 16) * J * 4 < limit && (uint64_t)(P + 16) * C * 4 < limit;
 }
 
+// Block tile of the float32 conv kernel for a shape: 64 instead of 128 rows (columns) where that wastes at
+// least a fifth fewer of them (J or C at most 64, or just past a multiple of 128).
+struct F32Tile { uint32_t bm, bn; };
+static uint32_t f32_tile_edge(uint32_t n) {
+    const uint32_t pad128 = (n + 127) / 128 * 128, pad64 = (n + 63) / 64 * 64;
+    return pad64 * 5 <= pad128 * 4 ? 64u : 128u;
+}
+static F32Tile conv_f32_tile(uint32_t J, uint32_t C) { return F32Tile{f32_tile_edge(J), f32_tile_edge(C)}; }
+static uint64_t conv_f32_tiles(const F32Tile& t, uint32_t J, uint32_t C) {
+    return (uint64_t)((J + t.bm - 1) / t.bm) * ((C + t.bn - 1) / t.bn);
+}
+// Workgroups resident at once: 256 compute units x (8 waves, and 160 KB of LDS at two staged chunks per workgroup).
+static uint64_t conv_f32_slots(const F32Tile& t) {
+    const uint64_t waves = (uint64_t)(t.bm / 64) * (t.bn / 64);
+    const uint64_t lds = 2ull * kR32 * (t.bm + 32 + t.bn + 32) * sizeof(float);
+    const uint64_t by_waves = 8 / waves, by_lds = (160ull * 1024) / lds;
+    return 256 * (by_waves < by_lds ? by_waves : by_lds);
+}
+
 uint32_t conv_f32_splits(uint32_t B, uint32_t J, uint32_t C) {
-    const uint64_t tiles = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT);
-    const uint64_t slots = 512;                                      // 256 compute units x 2 resident workgroups
+    const F32Tile t = conv_f32_tile(J, C);
+    const uint64_t tiles = conv_f32_tiles(t, J, C);
+    const uint64_t slots = conv_f32_slots(t);
     double best = 1e300;
     uint32_t best_s = 1;
     for (uint32_t s = 1; s <= B; ++s) {
@@ -378,10 +418,11 @@ int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_
 }
 
 // Positions split (see conv_split_p of the bf16 kernel): when (tiles x samples) fills less than half of the
-// 512 workgroup slots, into as many parts as fit one round, at least eight chunks each.
+// workgroup slots, into as many parts as fit one round, at least eight chunks each.
 uint32_t conv_f32_split_p(uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
-    const uint64_t tiles = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT);
-    const uint64_t slots = 512;
+    const F32Tile t = conv_f32_tile(J, C);
+    const uint64_t tiles = conv_f32_tiles(t, J, C);
+    const uint64_t slots = conv_f32_slots(t);
     const uint32_t n_chunks = (P + kR32 - 1) / kR32;
     if (tiles * B * 2 > slots || n_chunks < 16) return 1;
     const uint64_t sp = slots / (tiles * B);
@@ -404,13 +445,28 @@ static int launch_conv_f32_any(const void* X, const void* D, uint32_t B, uint32_
     if (split_p > 1 && (!workspace || workspace_bytes < (size_t)B * split_p * JC * sizeof(float))) split_p = 1;
     uint32_t splits = split_p > 1 ? B * split_p : conv_f32_splits(B, J, C);
     if (split_p == 1 && splits > 1 && (!workspace || workspace_bytes < (size_t)splits * 2 * JC * sizeof(float))) splits = 1;
-    const uint64_t nblk = (uint64_t)((J + kT - 1) / kT) * ((C + kT - 1) / kT) * splits;
+    const F32Tile t = conv_f32_tile(J, C);
+    const uint64_t nblk = conv_f32_tiles(t, J, C) * splits;
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
     // with the positions split the partial products are unsquared: the variant without g serves both
-    if (g_out && split_p == 1) hipLaunchKernelGGL((k_tiled_f32<true, true, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
-    else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit>), dim3((uint32_t)nblk), dim3(256), 0, stream, (const float*)X, (const float*)D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
+    const bool with_g = g_out && split_p == 1;
+    const float* Xf = static_cast<const float*>(X);
+    const float* Df = static_cast<const float*>(D);
+#define VGC_LAUNCH_F32(BM_, BN_)                                                                                           \
+    do {                                                                                                                   \
+        const dim3 grid((uint32_t)nblk), block((BM_ / 64) * (BN_ / 64) * 64);                                              \
+        if (with_g) hipLaunchKernelGGL((k_tiled_f32<true, true, kImplicit, BM_, BN_>), grid, block, 0, stream, Xf, Df, B,  \
+                                       P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);                             \
+        else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit, BM_, BN_>), grid, block, 0, stream, Xf, Df, B, P, J,  \
+                                C, splits, split_p, cg, cs, g_out, s_out, ws, G);                                          \
+    } while (0)
+    if (t.bm == 128 && t.bn == 128) VGC_LAUNCH_F32(128, 128);
+    else if (t.bm == 128) VGC_LAUNCH_F32(128, 64);
+    else if (t.bn == 128) VGC_LAUNCH_F32(64, 128);
+    else VGC_LAUNCH_F32(64, 64);
+#undef VGC_LAUNCH_F32
     if (split_p > 1) launch_sqgrad_reduce_parts(ws, B, split_p, JC, cg, cs, g_out, s_out, stream);
     else if (splits > 1) launch_sqgrad_reduce(ws, splits, JC, cg, cs, g_out, s_out, stream);
     return hip_check(hipGetLastError(), "launch k_tiled_f32");
