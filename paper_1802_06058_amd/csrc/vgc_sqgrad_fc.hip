@@ -417,15 +417,15 @@ int launch_fc_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_
     return hip_check(hipGetLastError(), "launch fc tiled");
 }
 
-// Positions split (see conv_split_p of the bf16 kernel): when (tiles x samples) fills less than half of the
-// workgroup slots, into as many parts as fit one round, at least eight chunks each.
+// Positions split: the rule of conv_split_p of the bf16 kernel with this kernel's tiles and slots.
 uint32_t conv_f32_split_p(uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
     const F32Tile t = conv_f32_tile(J, C);
     const uint64_t tiles = conv_f32_tiles(t, J, C);
     const uint64_t slots = conv_f32_slots(t);
     const uint32_t n_chunks = (P + kR32 - 1) / kR32;
-    if (tiles * B * 2 > slots || n_chunks < 16) return 1;
-    const uint64_t sp = slots / (tiles * B);
+    if (tiles * B * 3 > slots * 2 || n_chunks < 16) return 1;
+    // up to half a round: as many parts as fill one round; up to two thirds: just under two rounds
+    const uint64_t sp = tiles * B * 2 <= slots ? slots / (tiles * B) : 2 * slots / (tiles * B);
     return (uint32_t)(sp < n_chunks / 8 ? sp : n_chunks / 8);
 }
 

@@ -548,17 +548,18 @@ uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C) {
     return best_s;
 }
 
-// When [J, C] has so few tiles that one workgroup per (tile, sample) fills less than half of the chip's
-// workgroup slots, the positions of a sample are split as well, into as many parts as fit one round (at
-// least eight chunks per part).  1 = no split over positions.  (Between half a round and a full one the
-// split does not pay: workgroups that have a compute unit to themselves run faster.)
+// When [J, C] has so few tiles that one workgroup per (tile, sample) fills at most two thirds of the chip's
+// workgroup slots, the positions of a sample are split as well (at least eight chunks per part): up to half a
+// round into as many parts as fill one round, beyond that into two or three parts, just under two rounds
+// (measured on the box; above two thirds of a round the split does not pay).  1 = no split over positions.
 uint32_t conv_split_p(uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
     const ConvTile t = conv_tile(J, C);
     const uint64_t tiles = (uint64_t)((J + t.bm - 1) / t.bm) * ((C + t.bn - 1) / t.bn);
     const uint64_t slots = conv_slots(t);
     const uint32_t n_chunks = (P + kKC - 1) / kKC;
-    if (tiles * B * 2 > slots || n_chunks < 16) return 1;
-    const uint64_t sp = slots / (tiles * B);
+    if (tiles * B * 3 > slots * 2 || n_chunks < 16) return 1;
+    // up to half a round: as many parts as fill one round; up to two thirds: just under two rounds
+    const uint64_t sp = tiles * B * 2 <= slots ? slots / (tiles * B) : 2 * slots / (tiles * B);
     return (uint32_t)(sp < n_chunks / 8 ? sp : n_chunks / 8);
 }
 
