@@ -126,9 +126,11 @@ size_t vgc_scratch_bitmap_offset(const vgc_group* groups, uint32_t n_groups, uin
  * workspace: optional DEVICE buffer (16-byte aligned) of vgc_sqgrad_workspace_bytes() bytes.  When
  * [J, C] has too few tiles to fill the chip the samples are split over more workgroups and the
  * partial sums are added from the workspace in a fixed order (the result does not depend on
- * scheduling); when even one workgroup per (tile, sample) leaves most of the chip idle, the positions
- * of a sample are split as well and the parts of each sample's gradient are added before the square
- * is taken.  With workspace == NULL or too small the call still works, without the splits.
+ * scheduling); when even one workgroup per (tile, sample) leaves a third or more of the chip idle, the
+ * positions of a sample are split as well and the parts of each sample's gradient are added before the
+ * square is taken.  With workspace == NULL or too small the call still works, without the splits.
+ * Calls on different streams may overlap when each has a workspace of its own (a network's layers are
+ * independent).  Non-finite inputs give unspecified sums, no fault.
  */
 size_t vgc_sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C);
 int vgc_sqgrad(int kind, int dtype, const void* X, const void* D,
