@@ -181,6 +181,37 @@ def sqgrad_workspace_bytes(kind, dtype, B, P, J, Cc):
     return int(load().vgc_sqgrad_workspace_bytes(kind, dtype, B, P, J, Cc))
 
 
+def _need(t, numel, dtype, what):
+    """The library sees raw pointers: a tensor of the wrong size, type or layout is caught here."""
+    if t is None:
+        return
+    if t.dtype != dtype or t.numel() < numel or not t.is_contiguous():
+        raise VgcError(f"{what}: need a contiguous {dtype} tensor of at least {numel} elements, "
+                       f"got {t.dtype} with {t.numel()} (contiguous: {t.is_contiguous()})")
+
+
+def _need_bytes(t, nbytes, what):
+    if t is None:
+        return
+    if t.numel() * t.element_size() < nbytes or not t.is_contiguous():
+        raise VgcError(f"{what}: need a contiguous tensor of at least {nbytes} bytes, got {t.numel() * t.element_size()}")
+
+
+def _need_state(plan, scratch=None, **arrays):
+    import torch
+    for name, t in arrays.items():
+        _need(t, plan.n, torch.float32, name)
+    _need_bytes(scratch, plan.scratch_bytes, "scratch")
+
+
+def _need_messages(plan, words, n_words, hdrs):
+    for w, k, h in zip(words, n_words, hdrs):
+        if w.element_size() != 4:
+            raise VgcError(f"words: need 32-bit elements, got {w.dtype}")
+        _need_bytes(w, 4 * int(k), "words")
+        _need_bytes(h, plan.n_groups * C.sizeof(GroupHdr), "headers")
+
+
 def sqgrad(kind, X, D, c, s_out, g_out=None, workspace=None):
     """vgc_sqgrad.  X, D: float32 or bfloat16 tensors, [B, J]/[B, C] (FC) or [B, P, J]/[B, P, C] (CONV).
     workspace: optional uint8 tensor of sqgrad_workspace_bytes() bytes."""
@@ -194,6 +225,11 @@ def sqgrad(kind, X, D, c, s_out, g_out=None, workspace=None):
     else:
         B, P, J = X.shape
         Cc = D.shape[2]
+    if D.shape[0] != B or (kind != FC and D.shape[1] != P) or not X.is_contiguous() or not D.is_contiguous():
+        raise VgcError(f"X {tuple(X.shape)} and D {tuple(D.shape)} do not belong together (or are not contiguous)")
+    _need(s_out, J * Cc, torch.float32, "s_out")
+    _need(g_out, J * Cc, torch.float32, "g_out")
+    _need(workspace, 0, torch.uint8, "workspace")
     _check(load().vgc_sqgrad(kind, dtype, _ptr(X), _ptr(D), B, P, J, Cc, float(c), _ptr(g_out), _ptr(s_out),
                              _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()))
 
@@ -209,28 +245,44 @@ def sqgrad_conv2d(act, D, kh, kw, stride, pad, c, s_out, g_out=None, workspace=N
     if dtype is None or D.dtype != act.dtype:
         raise VgcError(f"unsupported dtypes {act.dtype}, {D.dtype}")
     B, H, W, Cin = act.shape
+    Ho, Wo = (H + 2 * pad[0] - kh) // stride[0] + 1, (W + 2 * pad[1] - kw) // stride[1] + 1
+    if tuple(D.shape[:3]) != (B, Ho, Wo) or not act.is_contiguous() or not D.is_contiguous():
+        raise VgcError(f"D {tuple(D.shape)} is not the output gradient [B, {Ho}, {Wo}, C] of act {tuple(act.shape)} "
+                       f"(or a tensor is not contiguous)")
+    _need(s_out, kh * kw * Cin * D.shape[3], torch.float32, "s_out")
+    _need(g_out, kh * kw * Cin * D.shape[3], torch.float32, "g_out")
+    _need(workspace, 0, torch.uint8, "workspace")
     _check(load().vgc_sqgrad_conv2d(dtype, _ptr(act), _ptr(D), B, H, W, Cin, D.shape[3], kh, kw, stride[0], stride[1],
                                     pad[0], pad[1], float(c), _ptr(g_out), _ptr(s_out), _ptr(workspace),
                                     0 if workspace is None else workspace.numel(), _stream()))
 
 
 def accumulate_select(g, s, r, v, plan, alpha, zeta, scratch):
+    _need_state(plan, scratch, g=g, s=s, r=r, v=v)
     _check(load().vgc_accumulate_select(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups, plan.n_groups,
                                         _ptr(plan.plan), float(alpha), float(zeta), _ptr(scratch), _stream()))
 
 
 def accumulate_select_hybrid(g, s, r, v, plan, alpha, zeta, tau, scratch):
+    _need_state(plan, scratch, g=g, s=s, r=r, v=v)
     _check(load().vgc_accumulate_select_hybrid(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups,
                                                plan.n_groups, _ptr(plan.plan), float(alpha), float(zeta), float(tau),
                                                _ptr(scratch), _stream()))
 
 
 def pack(plan, scratch, words, hdrs, status):
+    if words.element_size() != 4:
+        raise VgcError(f"words: need 32-bit elements, got {words.dtype}")
+    _need_bytes(scratch, plan.scratch_bytes, "scratch")
+    _need_bytes(hdrs, plan.n_groups * C.sizeof(GroupHdr), "headers")
+    _need_bytes(status, C.sizeof(PackStatus), "status")
     _check(load().vgc_pack(plan.n, plan.c_groups, plan.n_groups, _ptr(plan.plan), _ptr(scratch), _ptr(words),
                            words.numel(), _ptr(hdrs), _ptr(status), _stream()))
 
 
 def unpack_add(words, n_words, hdrs, plan, scale, dense):
+    _need_messages(plan, [words], [n_words], [hdrs])
+    _need_state(plan, dense=dense)
     _check(load().vgc_unpack_add(_ptr(words), int(n_words), _ptr(hdrs), plan.c_groups, plan.n_groups,
                                  _ptr(plan.plan), float(scale), _ptr(dense), plan.n, _stream()))
 
@@ -238,6 +290,10 @@ def unpack_add(words, n_words, hdrs, plan, scale, dense):
 def unpack_add_batch(words, n_words, hdrs, plan, scale, dense, overwrite=False):
     """vgc_unpack_add_batch: lists of word tensors, counts and header tensors, one per message."""
     p = len(words)
+    if len(n_words) != p or len(hdrs) != p:
+        raise VgcError("words, n_words and hdrs must have one entry per message")
+    _need_messages(plan, words, n_words, hdrs)
+    _need_state(plan, dense=dense)
     wp = (C.c_void_p * max(p, 1))(*[w.data_ptr() for w in words])
     hp = (C.c_void_p * max(p, 1))(*[h.data_ptr() for h in hdrs])
     nw = (C.c_uint64 * max(p, 1))(*[int(x) for x in n_words])
@@ -249,6 +305,10 @@ def unpack_apply(words, n_words, hdrs, plan, scale, param, state1, state2=None, 
                  momentum=0.0, beta1=0.9, beta2=0.999, eps=1e-8, step=1):
     """vgc_unpack_apply: decode the messages and take one optimizer step on (param, state1[, state2]) in place."""
     p = len(words)
+    if len(n_words) != p or len(hdrs) != p:
+        raise VgcError("words, n_words and hdrs must have one entry per message")
+    _need_messages(plan, words, n_words, hdrs)
+    _need_state(plan, param=param, state1=state1, state2=state2)
     wp = (C.c_void_p * max(p, 1))(*[w.data_ptr() for w in words])
     hp = (C.c_void_p * max(p, 1))(*[h.data_ptr() for h in hdrs])
     nw = (C.c_uint64 * max(p, 1))(*[int(x) for x in n_words])

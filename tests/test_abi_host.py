@@ -159,3 +159,40 @@ def test_bench_refuses_more_than_one_gpu():
     assert p.returncode != 0
     assert "one GPU" in p.stderr
     assert p.stdout.strip() == ""
+
+
+def test_binding_checks_tensor_sizes_before_any_launch():
+    """The C ABI sees raw pointers; the binding knows the tensors and refuses outputs, state or scratch that are
+    too small or of the wrong type before anything is launched (CPU tensors here: nothing may reach the GPU)."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    vgc.load()
+    act = torch.zeros(2, 6, 6, 8)
+    D = torch.zeros(2, 6, 6, 16)
+    ok = torch.zeros(72, 16)
+    with pytest.raises(vgc.VgcError, match="s_out"):
+        vgc.sqgrad_conv2d(act, D, 3, 3, (1, 1), (1, 1), 0.5, torch.zeros(71, 16))
+    with pytest.raises(vgc.VgcError, match="g_out"):
+        vgc.sqgrad_conv2d(act, D, 3, 3, (1, 1), (1, 1), 0.5, ok, torch.zeros(72, 16, dtype=torch.float64))
+    with pytest.raises(vgc.VgcError, match="output gradient"):
+        vgc.sqgrad_conv2d(act, torch.zeros(2, 5, 6, 16), 3, 3, (1, 1), (1, 1), 0.5, ok)
+    with pytest.raises(vgc.VgcError, match="s_out"):
+        vgc.sqgrad(vgc.FC, torch.zeros(4, 8), torch.zeros(4, 16), 0.25, torch.zeros(8, 15))
+    with pytest.raises(vgc.VgcError, match="belong together"):
+        vgc.sqgrad(vgc.CONV, torch.zeros(4, 5, 8), torch.zeros(4, 6, 16), 0.25, torch.zeros(8, 16))
+    plan = vgc.Plan([(0, 5000), (5000, 3000)], "cpu")
+    f = lambda k: torch.zeros(k)
+    scratch = torch.zeros(plan.scratch_bytes, dtype=torch.uint8)
+    with pytest.raises(vgc.VgcError, match="r:"):
+        vgc.accumulate_select(f(8000), f(8000), f(7999), f(8000), plan, 1.0, 0.999, scratch)
+    with pytest.raises(vgc.VgcError, match="scratch"):
+        vgc.accumulate_select(f(8000), f(8000), f(8000), f(8000), plan, 1.0, 0.999, scratch[:-1])
+    words, hdrs = torch.zeros(100, dtype=torch.int32), plan.new_headers()
+    with pytest.raises(vgc.VgcError, match="words"):
+        vgc.unpack_add(words, 101, hdrs, plan, 1.0, f(8000))
+    with pytest.raises(vgc.VgcError, match="dense"):
+        vgc.unpack_add(words, 100, hdrs, plan, 1.0, f(10))
+    with pytest.raises(vgc.VgcError, match="headers"):
+        vgc.unpack_add_batch([words], [10], [hdrs[:-1]], plan, 1.0, f(8000))
+    with pytest.raises(vgc.VgcError, match="state1"):
+        vgc.unpack_apply([words], [10], [hdrs], plan, 1.0, f(8000), f(3))
