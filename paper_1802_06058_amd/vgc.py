@@ -239,7 +239,8 @@ def sqgrad_conv2d_workspace_bytes(dtype, B, H, W, Cin, Cc, kh, kw, stride, pad):
 
 
 def sqgrad_conv2d(act, D, kh, kw, stride, pad, c, s_out, g_out=None, workspace=None):
-    """vgc_sqgrad_conv2d.  act [B, H, W, Cin], D [B, Ho, Wo, C] (NHWC, bfloat16); s_out, g_out [kh*kw*Cin, C]."""
+    """vgc_sqgrad_conv2d.  act [B, H, W, Cin], D [B, Ho, Wo, C] (NHWC, float32 or bfloat16); s_out, g_out float32
+    [kh*kw*Cin, C]; workspace: optional uint8 tensor of sqgrad_conv2d_workspace_bytes() bytes."""
     import torch
     dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(act.dtype)
     if dtype is None or D.dtype != act.dtype:
