@@ -181,35 +181,62 @@ def sqgrad_workspace_bytes(kind, dtype, B, P, J, Cc):
     return int(load().vgc_sqgrad_workspace_bytes(kind, dtype, B, P, J, Cc))
 
 
-def _need(t, numel, dtype, what):
-    """The library sees raw pointers: a tensor of the wrong size, type or layout is caught here."""
-    if t is None:
-        return
-    if t.dtype != dtype or t.numel() < numel or not t.is_contiguous():
-        raise VgcError(f"{what}: need a contiguous {dtype} tensor of at least {numel} elements, "
-                       f"got {t.dtype} with {t.numel()} (contiguous: {t.is_contiguous()})")
+class _Args:
+    """Checks of one call's tensors before anything is launched.  The library sees raw pointers, so a tensor
+    of the wrong size, type or layout is caught here; and since the kernels dereference data_ptr() as GPU
+    memory, so is a tensor in host memory (a forgotten .to(device)) or on another GPU than the call's.
+    Sizes and types are reported first, devices last (`launchable`)."""
 
+    def __init__(self, device=None):
+        self.device = device
+        self.seen = []
 
-def _need_bytes(t, nbytes, what):
-    if t is None:
-        return
-    if t.numel() * t.element_size() < nbytes or not t.is_contiguous():
-        raise VgcError(f"{what}: need a contiguous tensor of at least {nbytes} bytes, got {t.numel() * t.element_size()}")
+    def on_device(self, t, what):
+        if t is not None:
+            self.seen.append((t, what))
 
+    def need(self, t, numel, dtype, what):
+        if t is None:
+            return
+        self.seen.append((t, what))
+        if t.dtype != dtype or t.numel() < numel or not t.is_contiguous():
+            raise VgcError(f"{what}: need a contiguous {dtype} tensor of at least {numel} elements, "
+                           f"got {t.dtype} with {t.numel()} (contiguous: {t.is_contiguous()})")
 
-def _need_state(plan, scratch=None, **arrays):
-    import torch
-    for name, t in arrays.items():
-        _need(t, plan.n, torch.float32, name)
-    _need_bytes(scratch, plan.scratch_bytes, "scratch")
+    def need_bytes(self, t, nbytes, what):
+        if t is None:
+            return
+        self.seen.append((t, what))
+        if t.numel() * t.element_size() < nbytes or not t.is_contiguous():
+            raise VgcError(f"{what}: need a contiguous tensor of at least {nbytes} bytes, got {t.numel() * t.element_size()}")
 
+    def need_state(self, plan, scratch=None, **arrays):
+        import torch
+        self.on_device(plan.plan, "plan")
+        for name, t in arrays.items():
+            self.need(t, plan.n, torch.float32, name)
+        self.need_bytes(scratch, plan.scratch_bytes, "scratch")
 
-def _need_messages(plan, words, n_words, hdrs):
-    for w, k, h in zip(words, n_words, hdrs):
-        if w.element_size() != 4:
-            raise VgcError(f"words: need 32-bit elements, got {w.dtype}")
-        _need_bytes(w, 4 * int(k), "words")
-        _need_bytes(h, plan.n_groups * C.sizeof(GroupHdr), "headers")
+    def need_messages(self, plan, words, n_words, hdrs):
+        for w, k, h in zip(words, n_words, hdrs):
+            if w.element_size() != 4:
+                raise VgcError(f"words: need 32-bit elements, got {w.dtype}")
+            self.need_bytes(w, 4 * int(k), "words")
+            self.need_bytes(h, plan.n_groups * C.sizeof(GroupHdr), "headers")
+
+    def launchable(self):
+        """Every tensor seen lives in the memory of one GPU: the plan's, else the first tensor's."""
+        import torch
+        want = torch.device(self.device) if self.device is not None else None
+        for t, what in self.seen:
+            if not t.is_cuda:
+                raise VgcError(f"{what}: need a tensor in GPU memory, got one on {t.device}")
+            if want is None or want.type != "cuda":
+                want = t.device
+            elif want.index is None:
+                want = torch.device("cuda", torch.cuda.current_device())
+            if t.device != want:
+                raise VgcError(f"{what}: tensor is on {t.device}, the call's other tensors on {want}")
 
 
 def sqgrad(kind, X, D, c, s_out, g_out=None, workspace=None):
@@ -227,9 +254,12 @@ def sqgrad(kind, X, D, c, s_out, g_out=None, workspace=None):
         Cc = D.shape[2]
     if D.shape[0] != B or (kind != FC and D.shape[1] != P) or not X.is_contiguous() or not D.is_contiguous():
         raise VgcError(f"X {tuple(X.shape)} and D {tuple(D.shape)} do not belong together (or are not contiguous)")
-    _need(s_out, J * Cc, torch.float32, "s_out")
-    _need(g_out, J * Cc, torch.float32, "g_out")
-    _need(workspace, 0, torch.uint8, "workspace")
+    a = _Args()
+    a.on_device(X, "X"); a.on_device(D, "D")
+    a.need(s_out, J * Cc, torch.float32, "s_out")
+    a.need(g_out, J * Cc, torch.float32, "g_out")
+    a.need(workspace, 0, torch.uint8, "workspace")
+    a.launchable()
     _check(load().vgc_sqgrad(kind, dtype, _ptr(X), _ptr(D), B, P, J, Cc, float(c), _ptr(g_out), _ptr(s_out),
                              _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()))
 
@@ -250,22 +280,29 @@ def sqgrad_conv2d(act, D, kh, kw, stride, pad, c, s_out, g_out=None, workspace=N
     if tuple(D.shape[:3]) != (B, Ho, Wo) or not act.is_contiguous() or not D.is_contiguous():
         raise VgcError(f"D {tuple(D.shape)} is not the output gradient [B, {Ho}, {Wo}, C] of act {tuple(act.shape)} "
                        f"(or a tensor is not contiguous)")
-    _need(s_out, kh * kw * Cin * D.shape[3], torch.float32, "s_out")
-    _need(g_out, kh * kw * Cin * D.shape[3], torch.float32, "g_out")
-    _need(workspace, 0, torch.uint8, "workspace")
+    a = _Args()
+    a.on_device(act, "act"); a.on_device(D, "D")
+    a.need(s_out, kh * kw * Cin * D.shape[3], torch.float32, "s_out")
+    a.need(g_out, kh * kw * Cin * D.shape[3], torch.float32, "g_out")
+    a.need(workspace, 0, torch.uint8, "workspace")
+    a.launchable()
     _check(load().vgc_sqgrad_conv2d(dtype, _ptr(act), _ptr(D), B, H, W, Cin, D.shape[3], kh, kw, stride[0], stride[1],
                                     pad[0], pad[1], float(c), _ptr(g_out), _ptr(s_out), _ptr(workspace),
                                     0 if workspace is None else workspace.numel(), _stream()))
 
 
 def accumulate_select(g, s, r, v, plan, alpha, zeta, scratch):
-    _need_state(plan, scratch, g=g, s=s, r=r, v=v)
+    a = _Args(plan.device)
+    a.need_state(plan, scratch, g=g, s=s, r=r, v=v)
+    a.launchable()
     _check(load().vgc_accumulate_select(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups, plan.n_groups,
                                         _ptr(plan.plan), float(alpha), float(zeta), _ptr(scratch), _stream()))
 
 
 def accumulate_select_hybrid(g, s, r, v, plan, alpha, zeta, tau, scratch):
-    _need_state(plan, scratch, g=g, s=s, r=r, v=v)
+    a = _Args(plan.device)
+    a.need_state(plan, scratch, g=g, s=s, r=r, v=v)
+    a.launchable()
     _check(load().vgc_accumulate_select_hybrid(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups,
                                                plan.n_groups, _ptr(plan.plan), float(alpha), float(zeta), float(tau),
                                                _ptr(scratch), _stream()))
@@ -274,18 +311,32 @@ def accumulate_select_hybrid(g, s, r, v, plan, alpha, zeta, tau, scratch):
 def pack(plan, scratch, words, hdrs, status):
     if words.element_size() != 4:
         raise VgcError(f"words: need 32-bit elements, got {words.dtype}")
-    _need_bytes(scratch, plan.scratch_bytes, "scratch")
-    _need_bytes(hdrs, plan.n_groups * C.sizeof(GroupHdr), "headers")
-    _need_bytes(status, C.sizeof(PackStatus), "status")
+    a = _Args(plan.device)
+    a.on_device(plan.plan, "plan")
+    a.need_bytes(words, 0, "words")
+    a.need_bytes(scratch, plan.scratch_bytes, "scratch")
+    a.need_bytes(hdrs, plan.n_groups * C.sizeof(GroupHdr), "headers")
+    a.need_bytes(status, C.sizeof(PackStatus), "status")
+    a.launchable()
     _check(load().vgc_pack(plan.n, plan.c_groups, plan.n_groups, _ptr(plan.plan), _ptr(scratch), _ptr(words),
                            words.numel(), _ptr(hdrs), _ptr(status), _stream()))
 
 
 def unpack_add(words, n_words, hdrs, plan, scale, dense):
-    _need_messages(plan, [words], [n_words], [hdrs])
-    _need_state(plan, dense=dense)
+    a = _Args(plan.device)
+    a.need_messages(plan, [words], [n_words], [hdrs])
+    a.need_state(plan, dense=dense)
+    a.launchable()
     _check(load().vgc_unpack_add(_ptr(words), int(n_words), _ptr(hdrs), plan.c_groups, plan.n_groups,
                                  _ptr(plan.plan), float(scale), _ptr(dense), plan.n, _stream()))
+
+
+def _message_tables(words, n_words, hdrs):
+    p = len(words)
+    wp = (C.c_void_p * max(p, 1))(*[w.data_ptr() for w in words])
+    hp = (C.c_void_p * max(p, 1))(*[h.data_ptr() for h in hdrs])
+    nw = (C.c_uint64 * max(p, 1))(*[int(x) for x in n_words])
+    return wp, nw, hp
 
 
 def unpack_add_batch(words, n_words, hdrs, plan, scale, dense, overwrite=False):
@@ -293,11 +344,11 @@ def unpack_add_batch(words, n_words, hdrs, plan, scale, dense, overwrite=False):
     p = len(words)
     if len(n_words) != p or len(hdrs) != p:
         raise VgcError("words, n_words and hdrs must have one entry per message")
-    _need_messages(plan, words, n_words, hdrs)
-    _need_state(plan, dense=dense)
-    wp = (C.c_void_p * max(p, 1))(*[w.data_ptr() for w in words])
-    hp = (C.c_void_p * max(p, 1))(*[h.data_ptr() for h in hdrs])
-    nw = (C.c_uint64 * max(p, 1))(*[int(x) for x in n_words])
+    a = _Args(plan.device)
+    a.need_messages(plan, words, n_words, hdrs)
+    a.need_state(plan, dense=dense)
+    a.launchable()
+    wp, nw, hp = _message_tables(words, n_words, hdrs)
     _check(load().vgc_unpack_add_batch(wp, nw, hp, p, plan.c_groups, plan.n_groups, _ptr(plan.plan), float(scale),
                                        1 if overwrite else 0, _ptr(dense), plan.n, _stream()))
 
@@ -308,11 +359,11 @@ def unpack_apply(words, n_words, hdrs, plan, scale, param, state1, state2=None, 
     p = len(words)
     if len(n_words) != p or len(hdrs) != p:
         raise VgcError("words, n_words and hdrs must have one entry per message")
-    _need_messages(plan, words, n_words, hdrs)
-    _need_state(plan, param=param, state1=state1, state2=state2)
-    wp = (C.c_void_p * max(p, 1))(*[w.data_ptr() for w in words])
-    hp = (C.c_void_p * max(p, 1))(*[h.data_ptr() for h in hdrs])
-    nw = (C.c_uint64 * max(p, 1))(*[int(x) for x in n_words])
+    a = _Args(plan.device)
+    a.need_messages(plan, words, n_words, hdrs)
+    a.need_state(plan, param=param, state1=state1, state2=state2)
+    a.launchable()
+    wp, nw, hp = _message_tables(words, n_words, hdrs)
     opt = Optimizer(kind, lr, momentum, beta1, beta2, eps, step)
     _check(load().vgc_unpack_apply(wp, nw, hp, p, plan.c_groups, plan.n_groups, _ptr(plan.plan), float(scale),
                                    C.byref(opt), _ptr(param), _ptr(state1), _ptr(state2), plan.n, _stream()))

@@ -196,3 +196,33 @@ def test_binding_checks_tensor_sizes_before_any_launch():
         vgc.unpack_add_batch([words], [10], [hdrs[:-1]], plan, 1.0, f(8000))
     with pytest.raises(vgc.VgcError, match="state1"):
         vgc.unpack_apply([words], [10], [hdrs], plan, 1.0, f(8000), f(3))
+
+
+def test_binding_rejects_host_tensors_before_any_launch():
+    """The kernels dereference data_ptr() as GPU memory, so the binding must refuse a tensor that lives in
+    host memory (a forgotten .to(device)) before anything is launched.  Runs without a GPU: a plan whose
+    table stays on the host is enough to reach the checks."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    plan = vgc.Plan([(0, 100), (100, 200)], device="cpu")
+    t = torch.zeros(300, dtype=torch.float32)
+    sc = torch.zeros(plan.scratch_bytes, dtype=torch.uint8)
+    with pytest.raises(vgc.VgcError, match="GPU memory"):
+        vgc.accumulate_select(t, t, t, t, plan, 1.0, 0.999, sc)
+    with pytest.raises(vgc.VgcError, match="GPU memory"):
+        vgc.accumulate_select_hybrid(t, t, t, t, plan, 1.0, 0.999, 0.1, sc)
+    words = torch.zeros(300, dtype=torch.int32)
+    with pytest.raises(vgc.VgcError, match="GPU memory"):
+        vgc.pack(plan, sc, words, plan.new_headers(), plan.new_status())
+    with pytest.raises(vgc.VgcError, match="GPU memory"):
+        vgc.unpack_add(words, 0, plan.new_headers(), plan, 1.0, t)
+    with pytest.raises(vgc.VgcError, match="GPU memory"):
+        vgc.unpack_add_batch([words], [0], [plan.new_headers()], plan, 1.0, t)
+    with pytest.raises(vgc.VgcError, match="GPU memory"):
+        vgc.unpack_apply([words], [0], [plan.new_headers()], plan, 1.0, t, t)
+    X, D, s = torch.zeros(4, 8), torch.zeros(4, 8), torch.zeros(8, 8)
+    with pytest.raises(vgc.VgcError, match="GPU memory"):
+        vgc.sqgrad(vgc.FC, X, D, 1.0, s)
+    a, d = torch.zeros(2, 8, 8, 8), torch.zeros(2, 8, 8, 8)
+    with pytest.raises(vgc.VgcError, match="GPU memory"):
+        vgc.sqgrad_conv2d(a, d, 3, 3, (1, 1), (1, 1), 1.0, torch.zeros(72, 8))

@@ -169,9 +169,10 @@ def test_model_parameter_sets_full_oracle(dev, name, alpha, steps):
 
 @pytest.mark.parametrize("B,P,J,C,prec", [(64, 784, 4608, 512, "bf16"), (64, 196, 4608, 512, "bf16"),
                                           (32, 3136, 576, 64, "f32"), (32, 196, 2304, 256, "f32")])
-def test_conv_statistic_sampled_outputs_at_config_shapes(dev, B, P, J, C, prec):
-    """3x3 convolution shapes of the VGG-16 (bf16, batch 64) and ResNet-50 (float32, batch 32) configs:
-    sampled outputs recomputed from the definition on the CPU, one per-sample gradient at a time."""
+def test_conv_statistic_every_output_at_config_shapes(dev, B, P, J, C, prec):
+    """3x3 convolution shapes of the VGG-16 (bf16, batch 64) and ResNet-50 (float32, batch 32) configs as patch
+    matrices, in the launch configuration the benchmark times: every output of s against the float64 oracle at the
+    stated relative tolerance (1e-2 / 1e-5), every output of g against the magnitudes summed."""
     import torch
     from paper_1802_06058_amd import vgc
     bf16 = prec == "bf16"
@@ -185,19 +186,20 @@ def test_conv_statistic_sampled_outputs_at_config_shapes(dev, B, P, J, C, prec):
     nb = vgc.sqgrad_workspace_bytes(vgc.CONV, vgc.BF16 if bf16 else vgc.F32, B, P, J, C)
     ws = torch.empty(max(nb, 16), dtype=torch.uint8, device=dev)
     vgc.sqgrad(vgc.CONV, U, D, 1.0 / B, s, g, workspace=ws if nb else None)
+    s_only = torch.empty_like(s)
+    vgc.sqgrad(vgc.CONV, U, D, 1.0 / B, s_only, None, workspace=ws if nb else None)
     torch.cuda.synchronize()
-    rng = np.random.default_rng(1)
-    jj = np.concatenate([rng.integers(0, J, 60), [0, J - 1, 0, J - 1]])
-    cc = np.concatenate([rng.integers(0, C, 60), [0, C - 1, C - 1, 0]])
     tol = 1e-2 if bf16 else 1e-5
     sh, gh = s.cpu().numpy(), g.cpu().numpy()
-    Uc = {int(j): U[:, :, int(j)].to(torch.float64).cpu().numpy() for j in set(jj.tolist())}
-    Dc = {int(c): D[:, :, int(c)].to(torch.float64).cpu().numpy() for c in set(cc.tolist())}
-    for j, c in zip(jj.tolist(), cc.tolist()):
-        terms = Uc[j] * Dc[c] / B                                # [B, P]
-        Gz = terms.sum(1)
-        s_ref, g_ref = (Gz ** 2).sum(), Gz.sum()
-        mag = np.abs(terms).sum(1)                               # what float32 accumulation error scales with
-        assert abs(sh[j, c] - s_ref) <= tol * (mag ** 2).sum()
-        assert abs(gh[j, c] - g_ref) <= tol * mag.sum()
-    assert np.isfinite(sh).all() and (sh >= 0).all()
+    Uh, Dh = U.to(torch.float32).cpu().numpy(), D.to(torch.float32).cpu().numpy()      # exact widening
+    del U, D
+    g64, s64 = O.sqgrad_conv(Uh, Dh, 1.0 / B)
+    assert (s64 > 0).all()
+    rel = np.abs(sh - s64) / s64
+    print(f"observed max rel err of s: conv {prec} B{B} P{P} J{J} C{C}: {rel.max():.3e}")
+    assert rel.max() <= tol, f"s relative error {rel.max():.3e} at {np.unravel_index(rel.argmax(), rel.shape)}"
+    absG = np.zeros((J, C))
+    for z in range(B):                                             # a scale, not a reference: float32 is enough
+        absG += np.abs(Uh[z]).T @ np.abs(Dh[z])
+    assert (np.abs(gh - g64) / (absG / B)).max() <= tol
+    assert np.array_equal(s_only.cpu().numpy(), sh)                 # the kernel the benchmark times (s alone)

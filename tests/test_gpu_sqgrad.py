@@ -1,8 +1,16 @@
 """Parity of the HIP squared-gradient statistic against the float64 oracle, through the C ABI.
 
-Tolerances (stated by the benchmark spec): s to relative error 1e-5 for float32 inputs and
-1e-2 for bfloat16 inputs.  g is a signed sum, so its error is measured against the sum of the
-magnitudes of its terms (the quantity float32 accumulation error scales with)."""
+Tolerances: every output of s within relative error 1e-5 (float32 inputs) / 1e-2 (bfloat16 inputs)
+of the oracle's value, |s - s64| <= tol * s64, in both forms.  g is a signed sum for which no
+relative bound can hold (it may cancel to zero), so its error is measured against the sum of the
+magnitudes of its terms (the quantity float32 accumulation error scales with).
+
+In the conv form a sample's gradient is itself a signed sum over the P positions, so an output whose
+samples all happen to cancel is ill-conditioned: with two or three samples and a thousand positions a
+few outputs in ten thousand lose more than 1e-5 to float32 rounding whatever the order of summation.
+The signed cases here therefore have at least four samples (eight beyond a thousand positions), as the
+configurations do (32 and 64); the cases with one to three samples run on non-negative inputs, where
+nothing cancels."""
 import numpy as np
 import pytest
 
@@ -48,10 +56,16 @@ def _run(kind, X, D, c, dev, bf16, want_g=True, use_workspace=True):
     return (g.cpu().numpy() if want_g else None), s.cpu().numpy()
 
 
-def _check(g, s, g64, s64, absG, tol):
+OBSERVED = {}          # case -> largest relative error of s seen (printed by the last test of the module)
+
+
+def _check(g, s, g64, s64, absG, tol, tag=None):
     assert np.isfinite(s).all()
     err_s = np.abs(s - s64) / np.maximum(s64, np.finfo(np.float64).tiny)
-    assert err_s[s64 > 0].max() <= tol, f"s relative error {err_s[s64 > 0].max():.3e}"
+    worst = float(err_s[s64 > 0].max()) if (s64 > 0).any() else 0.0
+    if tag is not None:
+        OBSERVED[tag] = max(OBSERVED.get(tag, 0.0), worst)
+    assert worst <= tol, f"s relative error {worst:.3e} at {np.unravel_index(np.argmax(np.where(s64 > 0, err_s, 0)), s.shape)}"
     assert np.all(s[s64 == 0] == 0)
     if g is not None:
         err_g = np.abs(g - g64) / np.maximum(absG, np.finfo(np.float64).tiny)
@@ -73,38 +87,35 @@ def test_fc_form(dev, B, J, C, prec):
     g64, s64 = O.sqgrad_fc(Xw, Dw, c)
     absG = (np.abs(Xw).T @ np.abs(Dw)) * c
     g, s = _run(vgc.FC, X, D, c, dev, bf16)
-    _check(g, s, g64, s64, absG, RTOL[prec])
+    _check(g, s, g64, s64, absG, RTOL[prec], f"fc {prec} B{B} J{J} C{C}")
     _, s2 = _run(vgc.FC, X, D, c, dev, bf16, want_g=False)     # g_out is optional
     assert np.array_equal(s, s2)
 
 
 @pytest.mark.parametrize("B,P,J,C", [(4, 49, 64, 64), (3, 5, 27, 16), (2, 1, 40, 40), (8, 196, 576, 64), (5, 9, 100, 33),
-                                     (6, 33, 200, 136), (3, 64, 384, 256), (2, 784, 128, 128),
-                                     (3, 2000, 64, 72), (2, 1111, 24, 16),       # few tiles, many positions: split over positions
+                                     (6, 33, 200, 136), (3, 64, 384, 256), (6, 784, 128, 128),
+                                     (8, 2000, 64, 72), (8, 1111, 24, 16),       # few tiles, many positions: split over positions
+                                     (2, 1111, 24, 16), (1, 300, 40, 24),        # one or two samples (non-negative inputs)
                                      (40, 100, 1024, 512)])                      # more (tile, sample) pairs than workgroup slots: several samples per workgroup
 @pytest.mark.parametrize("prec", ["f32", "bf16"])
 def test_conv_form(dev, B, P, J, C, prec):
     from paper_1802_06058_amd import vgc
     bf16 = prec == "bf16"
     U, D = W.conv_inputs(22, (B, P, J, C), B, P, J, C, d_sigma=0.02, bf16=bf16)
+    if B < 3 and P > 100:                                      # nothing cancels: see the module docstring
+        U, D = (U & 0x7FFF, D & 0x7FFF) if bf16 else (np.abs(U), np.abs(D))
     c = 1.0 / B
     Uw, Dw = _widen(U, bf16), _widen(D, bf16)
     g64, s64 = O.sqgrad_conv(Uw, Dw, c)
     absG = np.einsum("zpj,zpc->jc", np.abs(Uw), np.abs(Dw)) * c
-    g, s = _run(vgc.CONV, U, D, c, dev, bf16)
-    # the per-sample gradient is a signed sum over positions: its float32 error scales with the
-    # magnitudes summed, and s inherits twice that relative to (sum |terms|)^2
     tol = RTOL[prec]
-    err_g = np.abs(g - g64) / absG
-    assert err_g.max() <= tol
-    sabs = np.einsum("zjc->jc", np.einsum("zpj,zpc->zjc", np.abs(Uw), np.abs(Dw)) ** 2) * c * c
-    assert (np.abs(s - s64) / sabs).max() <= tol
-    well = s64 > 0.05 * sabs                                   # where cancellation is mild, plain relative error
-    if prec == "f32" and well.any():
-        assert (np.abs(s - s64)[well] / s64[well]).max() <= 20 * tol
-    # without a workspace the samples are not split over workgroups; same tolerances, and s alone is the same
+    tag = f"conv {prec} B{B} P{P} J{J} C{C}"
+    g, s = _run(vgc.CONV, U, D, c, dev, bf16)
+    _check(g, s, g64, s64, absG, tol, tag)
+    # without a workspace the samples are not split over workgroups: same tolerances
     g1, s1 = _run(vgc.CONV, U, D, c, dev, bf16, use_workspace=False)
-    assert (np.abs(g1 - g64) / absG).max() <= tol and (np.abs(s1 - s64) / sabs).max() <= tol
+    _check(g1, s1, g64, s64, absG, tol, tag)
+    # s alone is the same, bit for bit
     _, s2 = _run(vgc.CONV, U, D, c, dev, bf16, want_g=False)
     assert np.array_equal(s, s2)
     # ... also when one workgroup walks through all the samples (the s-only kernel has a loop of its own)
@@ -144,3 +155,9 @@ def test_rejects_bad_arguments(dev):
     assert rc == -2
     rc = lib.vgc_sqgrad(vgc.FC, vgc.F32, X.data_ptr(), None, 4, 1, 8, 8, 1.0, None, s.data_ptr(), None, 0, None)
     assert rc == -1 and b"required" in lib.vgc_last_error()
+
+
+def test_zz_report_observed_errors():
+    """Not a check: prints the largest relative error of s each case showed (run with -s to see it)."""
+    for tag, worst in sorted(OBSERVED.items()):
+        print(f"observed max rel err of s: {tag}: {worst:.3e}")

@@ -1,6 +1,9 @@
 """vgc_sqgrad_conv2d (the convolution statistic read from the NHWC input, no patch matrix) against the
-float64 oracle, and against vgc_sqgrad on the materialised patch matrix.  Tolerance for bfloat16
-inputs: 1e-2, for float32 inputs 1e-5, measured like the conv form's (against the magnitudes summed)."""
+float64 oracle, and against vgc_sqgrad on the materialised patch matrix.  Every output of s within relative
+error 1e-2 (bfloat16 inputs) / 1e-5 (float32 inputs) of the oracle's, |s - s64| <= tol * s64; g, a signed sum,
+against the magnitudes summed.  Signed inputs come with at least four samples, the geometries with one to
+three samples with non-negative inputs (a sample's gradient is a signed sum over the positions: with so few
+samples some outputs cancel to where no float32 summation keeps 1e-5; see tests/test_gpu_sqgrad.py)."""
 import numpy as np
 import pytest
 
@@ -8,7 +11,6 @@ from oracle import vgc_oracle as O
 from paper_1802_06058_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
-TOL = 1e-2
 RTOL = {"bf16": 1e-2, "f32": 1e-5}
 
 
@@ -62,20 +64,28 @@ def _patches(a, kh, kw, stride, pad, Ho, Wo):
 
 GEOMS = [  # B, H, W, Cin, C, kh, kw, stride, pad
     (3, 8, 8, 8, 16, 3, 3, (1, 1), (1, 1)),        # one tile, taps narrower than the 16-byte pieces' tile
-    (2, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)),     # VGG-like, small
+    (4, 14, 14, 64, 64, 3, 3, (1, 1), (1, 1)),     # VGG-like, small
     (4, 9, 7, 16, 24, 3, 3, (2, 2), (1, 1)),       # stride 2, ragged everything
-    (2, 12, 10, 32, 40, 1, 1, (1, 1), (0, 0)),     # 1x1
-    (3, 11, 13, 8, 8, 5, 3, (2, 1), (2, 0)),       # rectangular kernel, mixed stride and padding
+    (4, 12, 10, 32, 40, 1, 1, (1, 1), (0, 0)),     # 1x1
+    (5, 11, 13, 8, 8, 5, 3, (2, 1), (2, 0)),       # rectangular kernel, mixed stride and padding
     (2, 6, 1, 24, 16, 3, 1, (1, 1), (1, 0)),       # output one column wide
-    (5, 28, 28, 128, 136, 3, 3, (1, 1), (1, 1)),   # several row tiles and a ragged column tile, samples split
-    (2, 16, 16, 256, 128, 3, 3, (1, 1), (1, 1)),   # a 256-column tile inside one tap
-    (2, 40, 37, 16, 16, 3, 3, (1, 1), (1, 1)),     # one tile, 1480 positions: the positions are split over workgroups
-    (3, 64, 50, 8, 24, 3, 3, (2, 1), (1, 1)),      # the same with a stride
-    (2, 39, 27, 112, 96, 5, 5, (3, 1), (3, 1)),    # 5x5, stride 3 down, padding larger than the stride
+    (8, 28, 28, 128, 136, 3, 3, (1, 1), (1, 1)),   # several row tiles and a ragged column tile, samples split
+    (6, 16, 16, 256, 128, 3, 3, (1, 1), (1, 1)),   # a 256-column tile inside one tap
+    (8, 40, 37, 16, 16, 3, 3, (1, 1), (1, 1)),     # one tile, 1480 positions: the positions are split over workgroups
+    (8, 64, 50, 8, 24, 3, 3, (2, 1), (1, 1)),      # the same with a stride
+    (8, 39, 27, 112, 96, 5, 5, (3, 1), (3, 1)),    # 5x5, stride 3 down, padding larger than the stride
     (5, 9, 11, 144, 128, 2, 5, (1, 2), (1, 2)),    # even kernel height, wide kernel
-    (3, 23, 31, 32, 24, 4, 2, (3, 3), (0, 0)),     # stride larger than the kernel's width: input columns skipped
+    (6, 23, 31, 32, 24, 4, 2, (3, 3), (0, 0)),     # stride larger than the kernel's width: input columns skipped
     (1, 73, 72, 32, 32, 5, 4, (1, 2), (0, 0)),     # one sample, 2415 positions
+    (2, 40, 37, 16, 16, 3, 3, (1, 1), (1, 1)),     # two samples, positions split
 ]
+
+OBSERVED = {}
+
+
+def _rel_s(s, s64):
+    ok = s64 > 0
+    return float((np.abs(s - s64)[ok] / s64[ok]).max()) if ok.any() else 0.0
 
 
 @pytest.mark.parametrize("prec", ["bf16", "f32"])
@@ -85,6 +95,8 @@ def test_conv2d_matches_oracle(dev, geom, prec):
     TOL = RTOL[prec]
     Ho, Wo = O.conv_out_size(H, kh, stride[0], pad[0]), O.conv_out_size(Wd, kw, stride[1], pad[1])
     A, D = W.conv2d_inputs(41, geom[:7], B, H, Wd, Cin, Ho, Wo, C, d_sigma=0.02, bf16=prec == "bf16")
+    if B < 4 and Ho * Wo > 100:                     # nothing cancels: see the module docstring
+        A, D = (A & 0x7FFF, D & 0x7FFF) if prec == "bf16" else (np.abs(A), np.abs(D))
     if prec == "bf16":
         Aw, Dw = W.bf16_bits_to_f32(A).astype(np.float64), W.bf16_bits_to_f32(D).astype(np.float64)
     else:
@@ -92,19 +104,18 @@ def test_conv2d_matches_oracle(dev, geom, prec):
     c = 1.0 / B
     g64, s64 = O.sqgrad_conv_nhwc(Aw, Dw, kh, kw, stride, pad, c)
     Uabs = _patches(np.abs(Aw), kh, kw, stride, pad, Ho, Wo)
-    per_sample_abs = np.einsum("zpj,zpc->zjc", Uabs, np.abs(Dw).reshape(B, Ho * Wo, C))
-    absG = per_sample_abs.sum(0) * c
-    sabs = (per_sample_abs ** 2).sum(0) * c * c
+    absG = np.einsum("zpj,zpc->jc", Uabs, np.abs(Dw).reshape(B, Ho * Wo, C)) * c
+    tag = f"conv2d {prec} {geom}"
     g, s = _run(A, D, kh, kw, stride, pad, c, dev)
     assert np.isfinite(g).all() and np.isfinite(s).all()
     assert (np.abs(g - g64) / np.maximum(absG, 1e-300)).max() <= TOL
-    assert (np.abs(s - s64) / np.maximum(sabs, 1e-300)).max() <= TOL
-    assert np.all(s[sabs == 0] == 0)
+    OBSERVED[tag] = _rel_s(s, s64)
+    assert OBSERVED[tag] <= TOL, f"s relative error {OBSERVED[tag]:.3e}"
+    assert np.all(s[s64 == 0] == 0)
     # no workspace (no sample split), and s alone: same bounds; s alone equals s with g bit for bit
     g1, s1 = _run(A, D, kh, kw, stride, pad, c, dev, use_workspace=False)
-    assert (np.abs(g1 - g64) / np.maximum(absG, 1e-300)).max() <= TOL and (np.abs(s1 - s64) / np.maximum(sabs, 1e-300)).max() <= TOL
+    assert (np.abs(g1 - g64) / np.maximum(absG, 1e-300)).max() <= TOL and _rel_s(s1, s64) <= TOL
     _, s2 = _run(A, D, kh, kw, stride, pad, c, dev, want_g=False)
-    assert (np.abs(s2 - s64) / np.maximum(sabs, 1e-300)).max() <= TOL
     assert np.array_equal(s2, s)
     # ... also when one workgroup walks through all the samples (the s-only kernel has a loop of its own)
     _, s3 = _run(A, D, kh, kw, stride, pad, c, dev, want_g=False, use_workspace=False)
@@ -130,25 +141,40 @@ def test_conv2d_equals_patch_matrix_path(dev):
     assert np.array_equal(s, s_ref.cpu().numpy()) and np.array_equal(g, g_ref.cpu().numpy())
 
 
-def test_conv2d_sampled_outputs_at_vgg_conv4_shape(dev):
-    """VGG-16 conv4_2 (28x28x512 -> 512, 3x3, batch 64): sampled outputs recomputed from the definition."""
-    B, H, Wd, Cin, C, kh, kw, stride, pad = 64, 28, 28, 512, 512, 3, 3, (1, 1), (1, 1)
-    A, D = W.conv2d_inputs(43, (0,), B, H, Wd, Cin, 28, 28, C, d_sigma=1e-3, bf16=True)
-    g, s = _run(A, D, kh, kw, stride, pad, 1.0 / B, dev)
-    Aw = W.bf16_bits_to_f32(A).astype(np.float64); Dw = W.bf16_bits_to_f32(D).astype(np.float64)
-    Ap = np.zeros((B, 30, 30, Cin)); Ap[:, 1:29, 1:29] = Aw
-    rng = np.random.default_rng(1)
-    for _ in range(60):
-        ky, kx, i, o = rng.integers(0, 3), rng.integers(0, 3), rng.integers(0, Cin), rng.integers(0, C)
-        win = Ap[:, ky:ky + 28, kx:kx + 28, i]                     # [B, 28, 28]
-        terms = win * Dw[:, :, :, o]
-        per_sample = terms.sum(axis=(1, 2)) / B
-        mag = np.abs(terms).sum(axis=(1, 2)) / B
-        j = (ky * 3 + kx) * Cin + i
-        assert abs(g[j, o] - per_sample.sum()) <= TOL * mag.sum()
-        assert abs(s[j, o] - (per_sample ** 2).sum()) <= TOL * (mag ** 2).sum()
-    _, s_only = _run(A, D, kh, kw, stride, pad, 1.0 / B, dev, want_g=False)    # the kernel the benchmark times
+@pytest.mark.parametrize("B,H,Cin,C,prec", [(64, 28, 512, 512, "bf16"),      # VGG-16 conv4_2
+                                            (64, 14, 512, 512, "bf16"),      # VGG-16 conv5_x
+                                            (32, 56, 64, 64, "f32"),         # ResNet-50 stage 1, 3x3
+                                            (32, 14, 256, 256, "f32")])      # ResNet-50 stage 3, 3x3
+def test_conv2d_every_output_at_config_shapes(dev, B, H, Cin, C, prec):
+    """3x3 / stride 1 / pad 1 convolutions of the VGG-16 (bfloat16, batch 64) and ResNet-50 (float32, batch 32)
+    configurations, in the launch configuration the benchmark times (workspace, s alone): every output of s
+    against the oracle at the stated relative tolerance, every output of g against the magnitudes summed."""
+    stride, pad = (1, 1), (1, 1)
+    A, D = W.conv2d_inputs(43, (B, H, Cin, C), B, H, H, Cin, H, H, C, d_sigma=1e-3, bf16=prec == "bf16")
+    Aw = W.bf16_bits_to_f32(A) if prec == "bf16" else A
+    Dw = W.bf16_bits_to_f32(D) if prec == "bf16" else D
+    g64, s64 = O.sqgrad_conv_nhwc(Aw, Dw, 3, 3, stride, pad, 1.0 / B)
+    g, s = _run(A, D, 3, 3, stride, pad, 1.0 / B, dev)
+    tol = RTOL[prec]
+    tag = f"conv2d {prec} config shape B{B} {H}x{H}x{Cin}->{C}"
+    OBSERVED[tag] = _rel_s(s, s64)
+    assert OBSERVED[tag] <= tol, f"s relative error {OBSERVED[tag]:.3e}"
+    absG = np.zeros_like(g64)
+    Ap = np.zeros((B, H + 2, H + 2, Cin), np.float32); Ap[:, 1:H + 1, 1:H + 1] = np.abs(Aw)
+    Dm = np.abs(Dw).reshape(B * H * H, C)
+    for ky in range(3):
+        for kx in range(3):
+            win = Ap[:, ky:ky + H, kx:kx + H].reshape(B * H * H, Cin)
+            absG[(ky * 3 + kx) * Cin:(ky * 3 + kx + 1) * Cin] = (win.T.astype(np.float64) @ Dm) / B
+    assert (np.abs(g - g64) / np.maximum(absG, 1e-300)).max() <= tol
+    _, s_only = _run(A, D, 3, 3, stride, pad, 1.0 / B, dev, want_g=False)    # the kernel the benchmark times
     assert np.array_equal(s_only, s)
+
+
+def test_zz_report_observed_errors():
+    """Not a check: prints the largest relative error of s each case showed (run with -s to see it)."""
+    for tag, worst in sorted(OBSERVED.items()):
+        print(f"observed max rel err of s: {tag}: {worst:.3e}")
 
 
 def test_conv2d_rejects_what_it_cannot_do(dev):
