@@ -137,6 +137,21 @@ int vgc_sqgrad(int kind, int dtype, const void* X, const void* D,
                uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
                float* g_out, float* s_out, void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): vgc_sqgrad with the workspace taken from a buffer of VGC_NOALLOC_SCRATCH_BYTES that is
+ * part of the library's own device image (each GPU the library runs on holds one copy until the process ends).
+ * Same kernels, same splits, same results bit for bit as vgc_sqgrad given a workspace of
+ * vgc_sqgrad_workspace_bytes() bytes; X, D, g_out, s_out, stream and errors as there.  A shape whose workspace
+ * would exceed the buffer is refused with VGC_ERR_SIZE (nothing is launched).  The call allocates and frees
+ * nothing and does not synchronise; on its first use on a GPU it looks the buffer's address up once.
+ * Every call on one GPU shares that GPU's buffer: calls that may overlap there (different streams, different
+ * threads) race; calls on one stream are ordered.  Nothing in the buffer needs clearing between calls (every
+ * partial sum a call reads was written by that call). */
+#define VGC_NOALLOC_SCRATCH_BYTES (128u << 20)
+int vgc_sqgrad_noalloc(int kind, int dtype, const void* X, const void* D,
+                       uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
+                       float* g_out, float* s_out, void* stream);
+
 /* The same sums for a 2-d convolution given as the layer stores it, without a patch matrix:
  *   act [B, H, W, Cin] (NHWC) the layer's input, D [B, Ho, Wo, C] (NHWC) the gradient of each sample's
  *   loss w.r.t. the layer's output, Ho = (H + 2 pad_h - kh) / stride_h + 1, Wo likewise.

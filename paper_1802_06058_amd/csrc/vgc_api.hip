@@ -3,6 +3,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "vgc_internal.h"
 
@@ -86,6 +87,33 @@ static PlanView plan_view(const void* plan_dev, uint64_t n_tiles, uint32_t n_gro
     const char* b = static_cast<const char*>(plan_dev);
     return PlanView{reinterpret_cast<const PlanGroup*>(b + go), reinterpret_cast<const PlanTile*>(b + to),
                     reinterpret_cast<const PlanRun*>(b + ro), reinterpret_cast<const PlanSeg*>(b + so)};
+}
+
+// Working memory of vgc_sqgrad_noalloc: one copy per GPU the library's code object is loaded on, held until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress; kernels and copies get
+// the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[VGC_NOALLOC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];          // device address of `scratch` on each GPU, once looked up
+static std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current GPU (looked up on the first call on that GPU).
+static int static_scratch(void** out) {
+    int dev = -1;
+    int rc = hip_check(hipGetDevice(&dev), "hipGetDevice");
+    if (rc != VGC_OK) return rc;
+    if (dev < 0 || dev >= kMaxDevices) { set_error("vgc_sqgrad_noalloc: device ordinal %d out of range", dev); return VGC_ERR_HIP; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        rc = hip_check(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (rc != VGC_OK) return rc;
+        if (!p) { set_error("vgc_sqgrad_noalloc: no device address for the static scratch"); return VGC_ERR_HIP; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return VGC_OK;
 }
 
 }  // namespace vgc
@@ -178,6 +206,23 @@ int vgc_sqgrad(int kind, int dtype, const void* X, const void* D, uint32_t B, ui
     if (workspace && !aligned(workspace, 16)) { set_error("vgc_sqgrad: workspace must be 16-byte aligned"); return VGC_ERR_ALIGN; }
     return launch_sqgrad(kind, dtype, X, D, B, P, J, C, c, g_out, s_out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+int vgc_sqgrad_noalloc(int kind, int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
+                       float c, float* g_out, float* s_out, void* stream) {
+    if (kind != VGC_FC && kind != VGC_CONV) { set_error("vgc_sqgrad_noalloc: unknown kind %d", kind); return VGC_ERR_DTYPE; }
+    if (dtype != VGC_F32 && dtype != VGC_BF16) { set_error("vgc_sqgrad_noalloc: unknown dtype %d", dtype); return VGC_ERR_DTYPE; }
+    if (B == 0 || P == 0 || J == 0 || C == 0) { set_error("vgc_sqgrad_noalloc: zero dimension"); return VGC_ERR_SIZE; }
+    const size_t need = sqgrad_workspace_bytes(kind, dtype, B, P, J, C);
+    if (need > (size_t)VGC_NOALLOC_SCRATCH_BYTES) {
+        set_error("vgc_sqgrad_noalloc: this shape wants %zu bytes of working memory, the static buffer has %zu; "
+                  "call vgc_sqgrad with a workspace of the caller's", need, (size_t)VGC_NOALLOC_SCRATCH_BYTES);
+        return VGC_ERR_SIZE;
+    }
+    void* ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != VGC_OK) return rc;
+    return vgc_sqgrad(kind, dtype, X, D, B, P, J, C, c, g_out, s_out, ws, (size_t)VGC_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 // Validates a convolution's geometry; on success the output extent.

@@ -55,6 +55,8 @@ EXPORTS = {
     "vgc_sqgrad_workspace_bytes": (C.c_size_t, [C.c_int, C.c_int, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32]),
     "vgc_sqgrad": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
                              C.c_uint32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "vgc_sqgrad_noalloc": (C.c_int, [C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32,
+                                     C.c_uint32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p]),
     "vgc_sqgrad_conv2d_workspace_bytes": (C.c_size_t, [C.c_int] + [C.c_uint32] * 11),
     "vgc_sqgrad_conv2d": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p] + [C.c_uint32] * 11 +
                           [C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
@@ -262,6 +264,32 @@ def sqgrad(kind, X, D, c, s_out, g_out=None, workspace=None):
     a.launchable()
     _check(load().vgc_sqgrad(kind, dtype, _ptr(X), _ptr(D), B, P, J, Cc, float(c), _ptr(g_out), _ptr(s_out),
                              _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()))
+
+
+NOALLOC_SCRATCH_BYTES = 128 << 20
+
+
+def sqgrad_noalloc(kind, X, D, c, s_out, g_out=None):
+    """vgc_sqgrad_noalloc: vgc_sqgrad with the library's own static working memory (no workspace argument)."""
+    import torch
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(X.dtype)
+    if dtype is None or D.dtype != X.dtype:
+        raise VgcError(f"unsupported dtypes {X.dtype}, {D.dtype}")
+    if kind == FC:
+        B, J = X.shape
+        P, Cc = 1, D.shape[1]
+    else:
+        B, P, J = X.shape
+        Cc = D.shape[2]
+    if D.shape[0] != B or (kind != FC and D.shape[1] != P) or not X.is_contiguous() or not D.is_contiguous():
+        raise VgcError(f"X {tuple(X.shape)} and D {tuple(D.shape)} do not belong together (or are not contiguous)")
+    a = _Args()
+    a.on_device(X, "X"); a.on_device(D, "D")
+    a.need(s_out, J * Cc, torch.float32, "s_out")
+    a.need(g_out, J * Cc, torch.float32, "g_out")
+    a.launchable()
+    _check(load().vgc_sqgrad_noalloc(kind, dtype, _ptr(X), _ptr(D), B, P, J, Cc, float(c), _ptr(g_out), _ptr(s_out),
+                                     _stream()))
 
 
 def sqgrad_conv2d_workspace_bytes(dtype, B, H, W, Cin, Cc, kh, kw, stride, pad):

@@ -226,3 +226,16 @@ def test_binding_rejects_host_tensors_before_any_launch():
     a, d = torch.zeros(2, 8, 8, 8), torch.zeros(2, 8, 8, 8)
     with pytest.raises(vgc.VgcError, match="GPU memory"):
         vgc.sqgrad_conv2d(a, d, 3, 3, (1, 1), (1, 1), 1.0, torch.zeros(72, 8))
+
+
+def test_noalloc_entry_point_refuses_oversized_shapes_on_the_host():
+    """vgc_sqgrad_noalloc works inside a fixed static buffer: a shape whose partial sums would not fit is
+    refused with VGC_ERR_SIZE before anything touches a GPU (fake pointers here, never dereferenced)."""
+    lib = vgc.load()
+    fake = C.c_void_p(0x1000)
+    B, P, J, Cc = 8, 49, 9216, 1024
+    assert lib.vgc_sqgrad_workspace_bytes(vgc.CONV, vgc.F32, B, P, J, Cc) > vgc.NOALLOC_SCRATCH_BYTES
+    assert lib.vgc_sqgrad_noalloc(vgc.CONV, vgc.F32, fake, fake, B, P, J, Cc, 1.0, None, fake, None) == -2
+    assert b"static buffer" in lib.vgc_last_error()
+    assert lib.vgc_sqgrad_noalloc(vgc.CONV, 9, fake, fake, B, P, J, Cc, 1.0, None, fake, None) == -4
+    assert lib.vgc_sqgrad_noalloc(vgc.CONV, vgc.F32, fake, fake, 0, P, J, Cc, 1.0, None, fake, None) == -2
