@@ -69,7 +69,7 @@ def main():
     # ---- inputs: a pool of P (g, s) pairs; worker w uses pair (w + step) % P at a step, so no worker
     # sees a pair twice within P steps and every pair is resident before timing starts
     t0 = time.time()
-    pool = [W.device_student_stream(N, batch, nu, cfg["seed"] + 1000 * i, dev) for i in range(P)]
+    pool = [student_stream(W, N, batch, nu, cfg["seed"] + 1000 * i, dev) for i in range(P)]
     torch.cuda.synchronize()
     gen_s = time.time() - t0
 
@@ -197,6 +197,28 @@ def main():
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(pool[0], a, cfg, min(a.cpu_sample, N))
     print(json.dumps(out))
+
+
+def student_stream(W, n, batch, nu, seed, device, chunk=1 << 24):
+    """The flat workload's inputs ("squared sums precomputed"): per parameter `batch` Student-t(nu) per-sample
+    gradients y_z from a seeded generator on the device, reduced to the two inputs of a step,
+    g = sum_z y_z / batch and s = sum_z (y_z / batch)^2.  Not timed."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(int(seed))
+    g = torch.empty(n, dtype=torch.float32, device=device)
+    s = torch.empty(n, dtype=torch.float32, device=device)
+    for lo in range(0, n, chunk):
+        m = min(chunk, n - lo)
+        gacc = torch.zeros(m, dtype=torch.float32, device=device)
+        sacc = torch.zeros(m, dtype=torch.float32, device=device)
+        for _ in range(batch):
+            y = W.device_student_draw(m, nu, gen, device) / batch
+            gacc += y
+            sacc += y * y
+        g[lo:lo + m] = gacc
+        s[lo:lo + m] = sacc
+    return g, s
 
 
 def bench_update(vgc, plan, words, hdrs, status, param, N, P, scale):

@@ -66,5 +66,32 @@ def build(verbose=True):
     return LIB
 
 
+def build_hostcheck():
+    """Build csrc/hostcheck/vgc_hostcheck against a copy of vgc_api.hip whose HOST code is compiled with
+    AddressSanitizer and UndefinedBehaviorSanitizer (device code is never sanitized), linked with the ordinary
+    objects of the other sources.  Returns the executable's path; run it with ASAN_OPTIONS=detect_leaks=0 (the HIP
+    runtime keeps its own allocations until exit)."""
+    others = [os.path.join(OBJDIR, os.path.basename(s) + ".o") for s in sources() if not s.endswith("vgc_api.hip")]
+    if not all(os.path.exists(o) for o in others):
+        build(verbose=False)
+    out = os.path.join(OBJDIR, "hostcheck")
+    os.makedirs(out, exist_ok=True)
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined"]
+    api_o, drv_o, exe = os.path.join(out, "vgc_api_san.o"), os.path.join(out, "vgc_hostcheck.o"), os.path.join(out, "vgc_hostcheck")
+    clangxx = os.path.join(os.path.dirname(os.path.dirname(HIPCC)), "lib", "llvm", "bin", "clang++")
+    steps = [
+        [HIPCC, *[f for f in FLAGS if f != "-O3"], "-O1", "-g", *san, "-c", os.path.join(CSRC, "vgc_api.hip"), "-o", api_o],
+        [clangxx, "-std=c++17", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+         "-I", os.path.join(ROOT, "include"), "-c", os.path.join(CSRC, "hostcheck", "vgc_hostcheck.cpp"), "-o", drv_o],
+        [HIPCC, "--offload-arch=gfx950", *san[:4], drv_o, api_o, *others, "-o", exe],
+    ]
+    for cmd in steps:
+        p = subprocess.run(cmd, capture_output=True, text=True)
+        if p.returncode != 0:
+            raise RuntimeError("hostcheck build failed:\n" + " ".join(cmd) + "\n" + p.stderr)
+    return exe
+
+
 if __name__ == "__main__":
     build()

@@ -1,8 +1,8 @@
 """Seeded synthetic inputs with the shapes of the benchmark configurations.
 
 This module serves both the HIP path's tests / benchmark and the CPU oracle's tests.
-It holds input synthesis only: shapes, distributions and seeds.  None of the method's
-arithmetic (test, quantiser, packing, decode) lives here.
+It holds input synthesis only: shapes, distributions, seeds and raw draws.  None of the
+method's arithmetic (the sums over the mini-batch, test, quantiser, packing, decode) lives here.
 
 Every stream is `numpy.random.default_rng` on a `SeedSequence(seed, spawn_key=path)`,
 so the tensor for (config, iteration, layer, role) is the same bytes wherever it is
@@ -157,19 +157,16 @@ def layer_sigmas(seed, n_layers, lo=1e-5, hi=1e-2):
 
 
 # ---------------------------------------------------------------------------------------
-# per-parameter (g, s) streams for the elementwise stages
+# per-sample gradient draws for the elementwise stages
 # ---------------------------------------------------------------------------------------
 
 
-def sample_stream(seed, path, n, batch, dist="normal", sigma=1.0, nu=3.0, chunk=1 << 20):
-    """Draw `batch` i.i.d. per-sample gradients y_z for each of n parameters and return
-    the two per-parameter inputs of the accumulate step as float32:
-        g = sum_z y_z / batch,   s = sum_z (y_z / batch)^2
-    (float64 reduction, rounded once).  dist: "normal" N(0, sigma^2) or "student"
-    sigma * t(nu).  Generated chunk by chunk so no [batch, n] array is ever held."""
+def sample_draws(seed, path, n, batch, dist="normal", sigma=1.0, nu=3.0, chunk=1 << 20):
+    """`batch` i.i.d. per-sample gradients for each of n parameters, chunk by chunk so that no
+    [batch, n] array is ever held: yields (lo, y) with y [batch, m] float64 the draws of parameters
+    lo .. lo + m - 1.  dist: "normal" N(0, sigma^2) or "student" sigma * t(nu).  What a step's two
+    inputs are made of is the caller's business (tests and the benchmark reduce the draws)."""
     rng = stream(seed, *path)
-    g = np.empty(n, np.float32)
-    s = np.empty(n, np.float32)
     for lo in range(0, n, chunk):
         m = min(chunk, n - lo)
         if dist == "normal":
@@ -178,22 +175,8 @@ def sample_stream(seed, path, n, batch, dist="normal", sigma=1.0, nu=3.0, chunk=
             y = rng.standard_t(nu, (batch, m))
         else:
             raise ValueError(dist)
-        y *= sigma / batch
-        g[lo:lo + m] = y.sum(axis=0)
-        s[lo:lo + m] = (y * y).sum(axis=0)
-    return g, s
-
-
-def model_stream(layers, seed, iteration, batch, sigmas=None, dist="normal"):
-    """(g, s) for a whole parameter set, layer after layer, with a per-layer scale."""
-    if sigmas is None:
-        sigmas = layer_sigmas(seed, len(layers))
-    gs, ss = [], []
-    for li, (L, sg) in enumerate(zip(layers, sigmas)):
-        g, s = sample_stream(seed, (iteration, li), L["size"], batch, dist=dist, sigma=float(sg))
-        gs.append(g)
-        ss.append(s)
-    return np.concatenate(gs), np.concatenate(ss)
+        y *= sigma
+        yield lo, y
 
 
 def flat_groups(n, group=1 << 24):
@@ -201,34 +184,20 @@ def flat_groups(n, group=1 << 24):
     return groups_from_sizes([min(group, n - lo) for lo in range(0, n, group)])
 
 
-def device_student_stream(n, batch, nu, seed, device, chunk=1 << 24):
-    """The flat-stream config on the GPU: same recipe as `sample_stream(dist="student")`
-    drawn with a seeded torch generator on `device` (values differ from the numpy stream;
-    both sides of a comparison read the tensors this returns).  Returns float32 (g, s)."""
+def device_student_draw(m, nu, gen, device):
+    """One per-sample gradient for each of m parameters, Student-t(nu) with integer nu, drawn on `device` from the
+    seeded torch generator `gen` as z / sqrt(chi2_nu / nu) (float32).  The flat-stream configuration draws
+    `batch` of these per parameter and step."""
     import torch
 
-    gen = torch.Generator(device=device)
-    gen.manual_seed(int(seed))
-    g = torch.empty(n, dtype=torch.float32, device=device)
-    s = torch.empty(n, dtype=torch.float32, device=device)
     k = int(nu)
     assert k == nu, "integer degrees of freedom only"
-    for lo in range(0, n, chunk):
-        m = min(chunk, n - lo)
-        gacc = torch.zeros(m, dtype=torch.float32, device=device)
-        sacc = torch.zeros(m, dtype=torch.float32, device=device)
-        for _ in range(batch):
-            z = torch.randn(m, generator=gen, device=device, dtype=torch.float32)
-            chi = torch.zeros(m, dtype=torch.float32, device=device)
-            for _ in range(k):
-                w = torch.randn(m, generator=gen, device=device, dtype=torch.float32)
-                chi += w * w
-            y = z / torch.sqrt(chi / k) / batch
-            gacc += y
-            sacc += y * y
-        g[lo:lo + m] = gacc
-        s[lo:lo + m] = sacc
-    return g, s
+    z = torch.randn(m, generator=gen, device=device, dtype=torch.float32)
+    chi = torch.zeros(m, dtype=torch.float32, device=device)
+    for _ in range(k):
+        w = torch.randn(m, generator=gen, device=device, dtype=torch.float32)
+        chi += w * w
+    return z / torch.sqrt(chi / k)
 
 
 # ---------------------------------------------------------------------------------------

@@ -239,3 +239,21 @@ def test_noalloc_entry_point_refuses_oversized_shapes_on_the_host():
     assert b"static buffer" in lib.vgc_last_error()
     assert lib.vgc_sqgrad_noalloc(vgc.CONV, 9, fake, fake, B, P, J, Cc, 1.0, None, fake, None) == -4
     assert lib.vgc_sqgrad_noalloc(vgc.CONV, vgc.F32, fake, fake, 0, P, J, Cc, 1.0, None, fake, None) == -2
+
+
+def test_host_code_under_address_and_undefined_behaviour_sanitizers():
+    """The library's host side (group validation, plan construction, argument checks, dispatch decisions) built
+    with AddressSanitizer + UndefinedBehaviorSanitizer and driven by csrc/hostcheck/vgc_hostcheck.cpp: plans for
+    group lists at every boundary the builder distinguishes are written into buffers allocated to the byte and
+    re-derived, and every entry point is driven into each of its argument errors with fabricated device pointers.
+    A finding of either sanitizer aborts the program."""
+    import subprocess
+    from paper_1802_06058_amd import build
+    exe = build.build_hostcheck()
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")
+    p = subprocess.run([exe], capture_output=True, text=True, timeout=300, env=env)
+    assert p.returncode == 0, p.stdout + p.stderr
+    assert "hostcheck ok" in p.stdout
+    assert "AddressSanitizer" not in p.stderr and "runtime error" not in p.stderr
+    sym = subprocess.run(["nm", os.path.join(os.path.dirname(exe), "vgc_api_san.o")], capture_output=True, text=True).stdout
+    assert "__asan_" in sym and "__ubsan_" in sym, "the API object was not instrumented"

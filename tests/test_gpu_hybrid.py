@@ -5,6 +5,7 @@ import pytest
 
 from oracle import vgc_oracle as O
 from paper_1802_06058_amd import workloads as W
+from streams import device_student_stream, sample_stream
 
 pytestmark = pytest.mark.gpu
 
@@ -43,7 +44,7 @@ def test_hybrid_steps_match_oracle(dev, sizes, alpha, tau):
     d_ref = np.zeros(n, F32)
     sent_total = 0
     for step in range(4):
-        g, s = W.sample_stream(31, (len(sizes), step), n, 16, "student", sigma=0.02)
+        g, s = sample_stream(31, (len(sizes), step), n, 16, "student", sigma=0.02)
         g += F32(0.004)                                         # a drift, so that residuals keep crossing tau
         vgc.accumulate_select_hybrid(torch.from_numpy(g).to(dev), torch.from_numpy(s).to(dev), r, v, plan,
                                      alpha, 0.999, tau, scratch)

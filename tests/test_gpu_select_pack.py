@@ -5,6 +5,7 @@ import pytest
 
 from oracle import vgc_oracle as O
 from paper_1802_06058_amd import workloads as W
+from streams import device_student_stream, sample_stream
 
 pytestmark = pytest.mark.gpu
 
@@ -90,7 +91,7 @@ def test_step_matches_oracle(dev, name, alpha):
     groups = W.groups_from_sizes(GROUP_SETS[name])
     n = sum(GROUP_SETS[name])
     rng = np.random.default_rng(len(name) * 7 + int(alpha))
-    g, s = W.sample_stream(11, (len(name), int(alpha)), n, 16, "student", sigma=0.01)
+    g, s = sample_stream(11, (len(name), int(alpha)), n, 16, "student", sigma=0.01)
     r = (rng.standard_normal(n) * 0.003).astype(F32)
     v = (rng.random(n) * 1e-5).astype(F32)
     gw = GpuWorker(groups, dev, r0=r, v0=v)
@@ -181,8 +182,50 @@ def test_config1_ten_iterations_state_carry(dev):
     assert 0.2 < sent_frac[0] < 0.45                          # fresh state, alpha = 1: about 0.3 for i.i.d. samples
 
 
+def test_config1_whole_chain_from_the_gpu_statistic(dev):
+    """Config 1 with every stage on the GPU: vgc_sqgrad (FC form, float32) feeds vgc_accumulate_select, vgc_pack and
+    vgc_unpack_add directly, five iterations with the state carried.  The statistic is checked against the float64
+    oracle at its tolerance; the stages after it are checked bit for bit against the oracle run on the very g, s the
+    GPU produced (a last-bit difference in s may flip an element that sits on the test's boundary, so the comparison
+    downstream takes the GPU's own statistic as its input)."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    cfg = W.CONFIGS["C1"]
+    n, B = 1024 * 1024, cfg["batch"]
+    groups = W.groups_from_sizes([n])
+    plan = vgc.Plan(groups, dev)
+    r = torch.zeros(n, dtype=torch.float32, device=dev); v = torch.zeros(n, dtype=torch.float32, device=dev)
+    g = torch.empty(1024, 1024, dtype=torch.float32, device=dev); s = torch.empty(1024, 1024, dtype=torch.float32, device=dev)
+    scratch, hdrs, status = plan.new_scratch(), plan.new_headers(), plan.new_status()
+    words = torch.empty(n, dtype=torch.int32, device=dev)
+    dense = torch.zeros(n, dtype=torch.float32, device=dev)
+    r_ref, v_ref, d_ref = np.zeros(n, F32), np.zeros(n, F32), np.zeros(n, F32)
+    for it in range(5):
+        X, D = W.c1_inputs(it)
+        vgc.sqgrad(vgc.FC, _dev(X, dev), _dev(D, dev), 1.0 / B, s, g)
+        vgc.accumulate_select(g.view(-1), s.view(-1), r, v, plan, cfg["alpha"], cfg["zeta"], scratch)
+        vgc.pack(plan, scratch, words, hdrs, status)
+        torch.cuda.synchronize()
+        total, overflow = vgc.read_status(status)
+        vgc.unpack_add(words, total, hdrs, plan, 1.0, dense)
+        gh, sh = g.cpu().numpy().ravel(), s.cpu().numpy().ravel()
+        g64, s64 = O.sqgrad_fc(X, D, 1.0 / B)
+        assert (np.abs(sh - s64.ravel()) <= 1e-5 * s64.ravel()).all()
+        absG = (np.abs(X.astype(np.float64)).T @ np.abs(D.astype(np.float64))).ravel() / B
+        assert (np.abs(gh - g64.ravel()) <= 1e-5 * absG).all()
+        r_acc, r_ref, v_ref, send = O.accumulate_select(gh, sh, r_ref, v_ref, cfg["alpha"], cfg["zeta"])
+        w_ref, h_ref, _ = O.pack(r_acc, send, groups)
+        O.unpack_add(w_ref, h_ref, groups, 1.0, d_ref)
+        assert np.array_equal(plan.send_mask(scratch), send)
+        assert overflow == 0 and total == w_ref.size and vgc.read_headers(hdrs) == h_ref
+        assert np.array_equal(words[:total].cpu().numpy().view(U32), w_ref)
+        assert np.array_equal(_bits(r.cpu().numpy()), _bits(r_ref)) and np.array_equal(_bits(v.cpu().numpy()), _bits(v_ref))
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(dense.cpu().numpy()), _bits(d_ref))
+
+
 def test_config2_mlp_sparse_inputs(dev):
-    """Config 2 (first 5 of its 50 iterations): three groups, ReLU-sparse inputs give exact ties."""
+    """Config 2, all 50 iterations with the state carried: three groups, ReLU-sparse inputs give exact ties."""
     cfg = W.CONFIGS["C2"]
     layers = cfg["layers"]
     groups = W.groups_from_sizes([L["size"] for L in layers])
@@ -190,7 +233,7 @@ def test_config2_mlp_sparse_inputs(dev):
     r = np.zeros(n, F32)
     v = np.zeros(n, F32)
     gw = GpuWorker(groups, dev)
-    for it in range(5):
+    for it in range(cfg["iterations"]):
         gs, ss = [], []
         for li in range(3):
             X, D = W.c2_inputs(it, li)
@@ -204,7 +247,7 @@ def test_capacity_overflow_is_reported_not_written(dev):
     sizes = [2048 * 4, 3000]
     groups = W.groups_from_sizes(sizes)
     n = sum(sizes)
-    g, s = W.sample_stream(3, (0,), n, 16, "normal", sigma=0.1)
+    g, s = sample_stream(3, (0,), n, 16, "normal", sigma=0.1)
     z = np.zeros(n, F32)
     r_acc, _, _, send = O.accumulate_select(g, s, z, z, 1.0, 0.999)
     words, hdrs, _ = O.pack(r_acc, send, groups)
@@ -219,7 +262,7 @@ def test_deterministic_and_independent_of_stale_scratch(dev):
     sizes = [2048 * 9 + 100, 777]
     groups = W.groups_from_sizes(sizes)
     n = sum(sizes)
-    g, s = W.sample_stream(4, (0,), n, 16, "student", sigma=1.0)
+    g, s = sample_stream(4, (0,), n, 16, "student", sigma=1.0)
     outs = []
     for fill in (0x00, 0xFF):
         gw = GpuWorker(groups, dev)
@@ -244,7 +287,7 @@ def test_unpack_add_messages_in_order(dev, scale):
     expect = dense0.copy()
     dense = _dev(dense0, dev)
     for w in range(8):
-        g, s = W.sample_stream(6, (w,), n, 16, "student", sigma=10.0 ** rng.uniform(-3, 0))
+        g, s = sample_stream(6, (w,), n, 16, "student", sigma=10.0 ** rng.uniform(-3, 0))
         z = np.zeros(n, F32)
         r_acc, _, _, send = O.accumulate_select(g, s, z, z, 1.0, 0.999)
         words, hdrs, _ = O.pack(r_acc, send, groups)
@@ -265,7 +308,7 @@ def test_full_round_trip_gpu_pack_to_gpu_unpack(dev):
     sizes = [2048 * 5 + 9, 4000]
     groups = W.groups_from_sizes(sizes)
     n = sum(sizes)
-    g, s = W.sample_stream(8, (0,), n, 16, "student", sigma=0.02)
+    g, s = sample_stream(8, (0,), n, 16, "student", sigma=0.02)
     z = np.zeros(n, F32)
     gw = GpuWorker(groups, dev)
     r_out, v_out, send, words, hdrs = _compare_step(gw, g, s, z, z, groups, 1.0, 0.999, dev)
@@ -318,7 +361,7 @@ def test_unpack_add_batch_equals_sequential(dev, p, overwrite):
     d_words, d_hdrs, counts = [], [], []
     scale = 1.0 / 3.0
     for w in range(p):
-        g, s = W.sample_stream(16, (p, w), n, 16, "student", sigma=10.0 ** rng.uniform(-3, 0))
+        g, s = sample_stream(16, (p, w), n, 16, "student", sigma=10.0 ** rng.uniform(-3, 0))
         z = np.zeros(n, F32)
         alpha = [0.0, 1.0, 4.0, 12.0][w % 4]                   # dense, typical, sparse, very sparse messages
         r_acc, _, _, send = O.accumulate_select(g, s, z, z, alpha, 0.999)

@@ -6,6 +6,7 @@ import pytest
 
 from oracle import vgc_oracle as O
 from paper_1802_06058_amd import workloads as W
+from streams import device_student_stream, sample_stream
 
 pytestmark = pytest.mark.gpu
 F32, U32 = np.float32, np.uint32
@@ -33,7 +34,7 @@ def _messages(seed, p, n, groups, dev, sigma=1e-2):
     msgs, d_words, d_hdrs, counts = [], [], [], []
     rng = np.random.default_rng(seed)
     for w in range(p):
-        g, s = W.sample_stream(31, (seed, w), n, 16, "student", sigma=sigma * 10.0 ** rng.uniform(-1, 1))
+        g, s = sample_stream(31, (seed, w), n, 16, "student", sigma=sigma * 10.0 ** rng.uniform(-1, 1))
         z = np.zeros(n, F32)
         alpha = [1.0, 0.0, 4.0, 12.0][w % 4]
         r_acc, _, _, send = O.accumulate_select(g, s, z, z, alpha, 0.999)
