@@ -65,7 +65,8 @@ typedef struct {
 typedef struct {
     uint64_t total_words; /* words the message has (also when they did not all fit) */
     uint32_t overflow;    /* 1 if total_words > words_cap: words beyond the capacity were not written */
-    uint32_t reserved;
+    uint32_t plan_mismatch; /* 1 if `plan` was not built from the `groups` of this call: nothing was computed, the
+                               message is empty and r, v are untouched */
 } vgc_pack_status;
 
 /* Word layout (Section 4.2: 4-bit value, 28-bit index, one 32-bit word per sent element):
@@ -188,6 +189,9 @@ int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uin
  * base + group offset enables the vector path).  groups: HOST, the list the plan was built from.
  * plan, scratch: DEVICE, 256-byte aligned.  alpha >= 0 finite, 0 < zeta <= 1.
  * Non-finite inputs give an unspecified mask but no fault.
+ * The plan carries a hash of the group list it was built from; the kernels of this and of every other call
+ * that takes a plan compare it with the hash of `groups` and do nothing when they differ (a plan of another
+ * model is never used for addressing).  vgc_pack reports that case in vgc_pack_status.plan_mismatch.
  */
 int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, uint64_t n,
                           const vgc_group* groups, uint32_t n_groups, const void* plan,
@@ -204,6 +208,38 @@ int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, ui
 int vgc_accumulate_select_hybrid(const float* g, const float* s, float* r, float* v, uint64_t n,
                                  const vgc_group* groups, uint32_t n_groups, const void* plan,
                                  float alpha, float zeta, float tau, void* scratch, void* stream);
+
+/* The same pass over a range of consecutive groups only: [first_group, first_group + group_count) of the list.  The
+ * other groups' r, v and staged results are left as they are.  For models some of whose layers go through
+ * vgc_sqgrad_accumulate_select: the remaining groups are covered by one call per run of consecutive groups, and
+ * vgc_pack then runs once over the whole model.  g, s, r, v are the whole-model arrays as above. */
+int vgc_accumulate_select_range(const float* g, const float* s, float* r, float* v, uint64_t n,
+                                const vgc_group* groups, uint32_t n_groups, const void* plan,
+                                uint32_t first_group, uint32_t group_count,
+                                float alpha, float zeta, void* scratch, void* stream);
+
+/* ---- (a) + (b) for one fully-connected layer ---------------------------------------------------
+ * Alg. 1's loop body from its first line on, for the weight matrix that is group `group` of the model:
+ * g = c X^T D and s = c^2 (X.X)^T (D.D) (VGC_FC of vgc_sqgrad) are formed on the matrix cores and consumed in
+ * place by r += g, v += s, the test of Eq. 2 and reset / decay, so that g and s of the layer never reach memory
+ * (the layer moves 16 bytes per parameter instead of 32; Section 5 counts the statistic as the dominant added
+ * cost, and for FC layers that cost is memory traffic).  r, v, scratch and the staged result are exactly what
+ * vgc_accumulate_select would leave given this g and s; the other groups are untouched (see
+ * vgc_accumulate_select_range), and vgc_pack finishes the whole model.
+ *
+ * X [B, J], D [B, C] row-major, dtype VGC_F32 or VGC_BF16 (accumulation in float32; bfloat16 squares are rounded to
+ * bfloat16 before the contraction, 2^-9 relative per factor).  groups[group].size must be J * C, and C a multiple of
+ * 2048 or one of 256, 512, 1024 (so that the 2048-element tiles of the pass are whole rows or whole pieces of
+ * rows), else VGC_ERR_SIZE: use vgc_sqgrad + vgc_accumulate_select for such a layer.
+ * workspace: DEVICE, 16-byte aligned, vgc_sqgrad_accumulate_select_workspace_bytes() bytes (transposed copies of X
+ * and D; 0 from that function means the shape is not supported).
+ * g_out, s_out: both NULL, or DEVICE float [J, C] that also receive the statistic (for inspection and tests).
+ * r, v: the whole-model arrays (DEVICE float[n]); plan, scratch, alpha, zeta, errors as for vgc_accumulate_select. */
+size_t vgc_sqgrad_accumulate_select_workspace_bytes(int dtype, uint32_t B, uint32_t J, uint32_t C);
+int vgc_sqgrad_accumulate_select(int dtype, const void* X, const void* D, uint32_t B, uint32_t J, uint32_t C, float c,
+                                 float* r, float* v, uint64_t n, const vgc_group* groups, uint32_t n_groups,
+                                 const void* plan, uint32_t group, float alpha, float zeta, void* scratch,
+                                 void* workspace, size_t workspace_bytes, float* g_out, float* s_out, void* stream);
 
 /* ---- (c) quantise, compact, pack ------------------------------------------------------------
  * Encode() of Alg. 1 (Sections 4.2 and 4.4): per group, M_k = the largest magnitude among the

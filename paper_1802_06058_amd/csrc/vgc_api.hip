@@ -25,15 +25,17 @@ int hip_check(hipError_t e, const char* what) {
 }
 
 // Validates the group list and counts tiles.  Returns a vgc_status.
-struct GroupStats { uint64_t n_runs; uint32_t n_segs; bool multi_seg; };
+struct GroupStats { uint64_t n_runs; uint32_t n_segs; bool multi_seg; uint64_t hash; };
 
 static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, uint64_t* n_tiles_out,
                         GroupStats* stats_out = nullptr) {
     if (!groups) { set_error("groups is NULL"); return VGC_ERR_NULL; }
     if (n == 0 || n_groups == 0) { set_error("n and n_groups must be positive"); return VGC_ERR_SIZE; }
     uint64_t off = 0, tiles = 0, runs = 0, segs = 0;
+    uint64_t hash = 0xCBF29CE484222325ull ^ n_groups;       // FNV-1a over the sizes (offsets follow from them)
     bool multi = false;
     for (uint32_t k = 0; k < n_groups; ++k) {
+        hash = (hash ^ groups[k].size) * 0x100000001B3ull;
         if (groups[k].size == 0) { set_error("group %u is empty", k); return VGC_ERR_SIZE; }
         if (groups[k].size > VGC_MAX_GROUP_SIZE) {
             set_error("group %u has %u elements; a 28-bit index holds at most 2^28", k, groups[k].size);
@@ -57,7 +59,7 @@ static int check_groups(const vgc_group* groups, uint32_t n_groups, uint64_t n, 
     }
     if (tiles > 0x7FFFFFFFull) { set_error("too many tiles (%llu)", (unsigned long long)tiles); return VGC_ERR_SIZE; }
     if (n_tiles_out) *n_tiles_out = tiles;
-    if (stats_out) { stats_out->n_runs = runs; stats_out->n_segs = (uint32_t)segs; stats_out->multi_seg = multi; }
+    if (stats_out) { stats_out->n_runs = runs; stats_out->n_segs = (uint32_t)segs; stats_out->multi_seg = multi; stats_out->hash = hash; }
     return VGC_OK;
 }
 
@@ -80,6 +82,10 @@ static size_t plan_bytes_for(uint64_t n_tiles, uint32_t n_groups, size_t* groups
 static bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
 struct PlanView { const PlanGroup* groups; const PlanTile* tiles; const PlanRun* runs; const PlanSeg* segs; };
+
+static PlanCheck plan_check(const void* plan_dev, const GroupStats& gs) {
+    return PlanCheck{static_cast<const PlanHeader*>(plan_dev), gs.hash};
+}
 
 static PlanView plan_view(const void* plan_dev, uint64_t n_tiles, uint32_t n_groups) {
     size_t go, to, ro, so;
@@ -163,7 +169,7 @@ int vgc_plan_build(const vgc_group* groups, uint32_t n_groups, uint64_t n, void*
     PlanHeader* h = reinterpret_cast<PlanHeader*>(b);
     h->magic = kPlanMagic; h->n = n; h->n_tiles = n_tiles; h->n_groups = n_groups; h->tile = kTile;
     h->groups_off = go; h->tiles_off = to; h->runs_off = ro; h->n_runs = gs.n_runs;
-    h->segs_off = so; h->n_segs = gs.n_segs;
+    h->segs_off = so; h->n_segs = gs.n_segs; h->groups_hash = gs.hash;
     PlanGroup* G = reinterpret_cast<PlanGroup*>(b + go);
     PlanTile* T = reinterpret_cast<PlanTile*>(b + to);
     PlanRun* R = reinterpret_cast<PlanRun*>(b + ro);
@@ -273,13 +279,20 @@ int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uin
                          static_cast<hipStream_t>(stream));
 }
 
+// first_group, group_count: the groups the launch covers (all of them for the whole-model calls)
 static int accumulate_select_any(const float* g, const float* s, float* r, float* v, uint64_t n,
                                  const vgc_group* groups, uint32_t n_groups, const void* plan,
+                                 uint32_t first_group, uint32_t group_count,
                                  float alpha, float zeta, float tau, bool hybrid, void* scratch, void* stream) {
     if (!g || !s || !r || !v || !plan || !scratch) { set_error("vgc_accumulate_select: NULL pointer"); return VGC_ERR_NULL; }
     uint64_t n_tiles = 0;
-    int rc = check_groups(groups, n_groups, n, &n_tiles);
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
     if (rc != VGC_OK) return rc;
+    if (first_group > n_groups || group_count > n_groups - first_group) {
+        set_error("vgc_accumulate_select_range: groups %u .. %u + %u are not inside the list of %u", first_group, first_group, group_count, n_groups);
+        return VGC_ERR_SIZE;
+    }
     if (!aligned(g, 4) || !aligned(s, 4) || !aligned(r, 4) || !aligned(v, 4) || !aligned(plan, 256) || !aligned(scratch, 256)) {
         set_error("vgc_accumulate_select: g, s, r, v need 4-byte, plan and scratch 256-byte alignment");
         return VGC_ERR_ALIGN;
@@ -292,11 +305,17 @@ static int accumulate_select_any(const float* g, const float* s, float* r, float
         set_error("vgc_accumulate_select_hybrid: need tau >= 0 finite (got %g)", tau);
         return VGC_ERR_PARAM;
     }
+    uint64_t tile0 = 0, tiles = 0;
+    for (uint32_t k = 0; k < first_group + group_count; ++k) {
+        const uint64_t nt = (groups[k].size + kTile - 1) / kTile;
+        if (k < first_group) tile0 += nt; else tiles += nt;
+    }
     const ScratchLayout L = scratch_layout(n_tiles, n_groups);
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
     char* sc = static_cast<char*>(scratch);
     const bool vec = aligned(g, 16) && aligned(s, 16) && aligned(r, 16) && aligned(v, 16);
-    return launch_accumulate_select(g, s, r, v, pv.groups, pv.tiles, n_tiles,
+    return launch_accumulate_select(plan_check(plan, gs), reinterpret_cast<uint32_t*>(sc + L.flags_off), g, s, r, v, pv.groups, pv.tiles,
+                                    tile0, tiles,
                                     reinterpret_cast<TileHdr*>(sc + L.tile_hdr_off),
                                     reinterpret_cast<uint32_t*>(sc + L.bitmap_off),
                                     reinterpret_cast<uint16_t*>(sc + L.staging_off),
@@ -306,13 +325,68 @@ static int accumulate_select_any(const float* g, const float* s, float* r, float
 int vgc_accumulate_select(const float* g, const float* s, float* r, float* v, uint64_t n,
                           const vgc_group* groups, uint32_t n_groups, const void* plan,
                           float alpha, float zeta, void* scratch, void* stream) {
-    return accumulate_select_any(g, s, r, v, n, groups, n_groups, plan, alpha, zeta, 0.0f, false, scratch, stream);
+    return accumulate_select_any(g, s, r, v, n, groups, n_groups, plan, 0, n_groups, alpha, zeta, 0.0f, false, scratch, stream);
 }
 
 int vgc_accumulate_select_hybrid(const float* g, const float* s, float* r, float* v, uint64_t n,
                                  const vgc_group* groups, uint32_t n_groups, const void* plan,
                                  float alpha, float zeta, float tau, void* scratch, void* stream) {
-    return accumulate_select_any(g, s, r, v, n, groups, n_groups, plan, alpha, zeta, tau, true, scratch, stream);
+    return accumulate_select_any(g, s, r, v, n, groups, n_groups, plan, 0, n_groups, alpha, zeta, tau, true, scratch, stream);
+}
+
+int vgc_accumulate_select_range(const float* g, const float* s, float* r, float* v, uint64_t n,
+                                const vgc_group* groups, uint32_t n_groups, const void* plan,
+                                uint32_t first_group, uint32_t group_count,
+                                float alpha, float zeta, void* scratch, void* stream) {
+    return accumulate_select_any(g, s, r, v, n, groups, n_groups, plan, first_group, group_count, alpha, zeta, 0.0f, false, scratch, stream);
+}
+
+size_t vgc_sqgrad_accumulate_select_workspace_bytes(int dtype, uint32_t B, uint32_t J, uint32_t C) {
+    if (dtype != VGC_F32 && dtype != VGC_BF16) return 0;
+    return fused_fc_workspace_bytes(dtype, B, J, C);
+}
+
+int vgc_sqgrad_accumulate_select(int dtype, const void* X, const void* D, uint32_t B, uint32_t J, uint32_t C, float c,
+                                 float* r, float* v, uint64_t n, const vgc_group* groups, uint32_t n_groups, const void* plan,
+                                 uint32_t group, float alpha, float zeta, void* scratch, void* workspace, size_t workspace_bytes,
+                                 float* g_out, float* s_out, void* stream) {
+    if (dtype != VGC_F32 && dtype != VGC_BF16) { set_error("vgc_sqgrad_accumulate_select: unknown dtype %d", dtype); return VGC_ERR_DTYPE; }
+    if (!X || !D || !r || !v || !plan || !scratch || !workspace) { set_error("vgc_sqgrad_accumulate_select: NULL pointer"); return VGC_ERR_NULL; }
+    if ((g_out == nullptr) != (s_out == nullptr)) { set_error("vgc_sqgrad_accumulate_select: g_out and s_out go together"); return VGC_ERR_NULL; }
+    if (B == 0 || J == 0 || C == 0) { set_error("vgc_sqgrad_accumulate_select: zero dimension"); return VGC_ERR_SIZE; }
+    uint64_t n_tiles = 0;
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
+    if (rc != VGC_OK) return rc;
+    if (group >= n_groups || (uint64_t)J * C != groups[group].size) {
+        set_error("vgc_sqgrad_accumulate_select: group %u does not exist or does not have J x C = %llu elements", group,
+                  (unsigned long long)J * C);
+        return VGC_ERR_SIZE;
+    }
+    const size_t need = fused_fc_workspace_bytes(dtype, B, J, C);
+    if (need == 0) {
+        set_error("vgc_sqgrad_accumulate_select: C = %u is neither a multiple of 2048 nor 256, 512 or 1024 "
+                  "(use vgc_sqgrad and vgc_accumulate_select)", C);
+        return VGC_ERR_SIZE;
+    }
+    if (workspace_bytes < need) { set_error("vgc_sqgrad_accumulate_select: workspace has %zu bytes, %zu needed", workspace_bytes, need); return VGC_ERR_SIZE; }
+    const size_t es = dtype == VGC_BF16 ? 2 : 4;
+    if (!aligned(X, es) || !aligned(D, es) || !aligned(r, 4) || !aligned(v, 4) || !aligned(plan, 256) || !aligned(scratch, 256) ||
+        !aligned(workspace, 16) || !aligned(g_out, 4) || !aligned(s_out, 4)) {
+        set_error("vgc_sqgrad_accumulate_select: misaligned pointer");
+        return VGC_ERR_ALIGN;
+    }
+    if (!std::isfinite(c) || !(alpha >= 0.0f) || !std::isfinite(alpha) || !(zeta > 0.0f) || !(zeta <= 1.0f)) {
+        set_error("vgc_sqgrad_accumulate_select: need c finite, alpha >= 0 finite and 0 < zeta <= 1");
+        return VGC_ERR_PARAM;
+    }
+    const ScratchLayout L = scratch_layout(n_tiles, n_groups);
+    const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    char* sc = static_cast<char*>(scratch);
+    return launch_fused_fc_select(plan_check(plan, gs), reinterpret_cast<uint32_t*>(sc + L.flags_off), dtype, X, D, B, J, C, c, r, v,
+                                  pv.groups, group, reinterpret_cast<TileHdr*>(sc + L.tile_hdr_off),
+                                  reinterpret_cast<uint32_t*>(sc + L.bitmap_off), reinterpret_cast<uint16_t*>(sc + L.staging_off),
+                                  alpha, zeta, workspace, g_out, s_out, static_cast<hipStream_t>(stream));
 }
 
 int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void* plan, void* scratch,
@@ -333,7 +407,7 @@ int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void*
     const ScratchLayout L = scratch_layout(n_tiles, n_groups);
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
     char* sc = static_cast<char*>(scratch);
-    return launch_pack(pv.groups, pv.tiles, pv.segs, n_tiles, n_groups, gs.n_segs, gs.multi_seg,
+    return launch_pack(plan_check(plan, gs), reinterpret_cast<const uint32_t*>(sc + L.flags_off), pv.groups, pv.tiles, pv.segs, n_tiles, n_groups, gs.n_segs, gs.multi_seg,
                        reinterpret_cast<TileHdr*>(sc + L.tile_hdr_off),
                        reinterpret_cast<SegTmp*>(sc + L.seg_tmp_off),
                        reinterpret_cast<const uint16_t*>(sc + L.staging_off),
@@ -345,7 +419,8 @@ int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr*
                    float scale, float* dense_out, uint64_t n, void* stream) {
     if (!hdrs || !plan || !dense_out || (!words && n_words)) { set_error("vgc_unpack_add: NULL pointer"); return VGC_ERR_NULL; }
     uint64_t n_tiles = 0;
-    int rc = check_groups(groups, n_groups, n, &n_tiles);
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
     if (rc != VGC_OK) return rc;
     if (!aligned(plan, 256) || !aligned(words, 4) || !aligned(hdrs, 8) || !aligned(dense_out, 4)) {
         set_error("vgc_unpack_add: misaligned pointer");
@@ -353,7 +428,7 @@ int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr*
     }
     if (!std::isfinite(scale)) { set_error("vgc_unpack_add: scale is not finite"); return VGC_ERR_PARAM; }
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
-    return launch_unpack_add(words, n_words, hdrs, pv.groups, n_groups, scale, dense_out, static_cast<hipStream_t>(stream));
+    return launch_unpack_add(plan_check(plan, gs), words, n_words, hdrs, pv.groups, n_groups, scale, dense_out, static_cast<hipStream_t>(stream));
 }
 
 int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
@@ -372,7 +447,7 @@ int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, 
     if (!std::isfinite(scale)) { set_error("vgc_unpack_add_batch: scale is not finite"); return VGC_ERR_PARAM; }
     if (p == 0 && !overwrite) return VGC_OK;
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
-    return launch_unpack_add_batch(words, n_words, hdrs, p, pv.groups, pv.runs, gs.n_runs, scale, overwrite, dense_out,
+    return launch_unpack_add_batch(plan_check(plan, gs), words, n_words, hdrs, p, pv.groups, pv.runs, gs.n_runs, scale, overwrite, dense_out,
                                    static_cast<hipStream_t>(stream));
 }
 
@@ -410,7 +485,7 @@ int vgc_unpack_apply(const uint32_t* const* words, const uint64_t* n_words, cons
         bias2 = (float)(1.0 - std::pow((double)b2, (double)opt->step));
     }
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
-    return launch_unpack_apply(words, n_words, hdrs, p, pv.groups, pv.runs, gs.n_runs, scale, opt->kind, opt->lr, mu, b1, b2,
+    return launch_unpack_apply(plan_check(plan, gs), words, n_words, hdrs, p, pv.groups, pv.runs, gs.n_runs, scale, opt->kind, opt->lr, mu, b1, b2,
                                omb1, omb2, bias1, bias2, eps, param, state1, state2, static_cast<hipStream_t>(stream));
 }
 

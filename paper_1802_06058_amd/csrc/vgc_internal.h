@@ -18,7 +18,7 @@ constexpr uint32_t kThreads = 256;
 constexpr uint32_t kElemsPerThread = kTile / kThreads;   // 8
 constexpr uint32_t kRelBins = 9;                          // staged exponent codes 0..8 (see StagedEntry)
 
-constexpr uint64_t kPlanMagic = 0x32304E414C504756ull;    // "VGPLAN02"
+constexpr uint64_t kPlanMagic = 0x33304E414C504756ull;    // "VGPLAN03"
 
 struct PlanHeader {            // 128 bytes at the start of the plan blob
     uint64_t magic;
@@ -32,8 +32,20 @@ struct PlanHeader {            // 128 bytes at the start of the plan blob
     uint64_t n_runs;
     uint64_t segs_off;         // byte offset of PlanSeg[n_segs]
     uint64_t n_segs;
-    uint64_t reserved[6];
+    uint64_t groups_hash;      // hash of the group list the plan was built from (see groups_hash())
+    uint64_t reserved[5];
 };
+
+// Every compute call takes the host group list and the device plan built from it.  The host hashes the list it
+// was given; every kernel that reads plan tables first compares that hash (and the magic) with the header's and
+// does nothing when they differ: a plan that belongs to another group list is never used for addressing.
+struct PlanCheck {
+    const PlanHeader* header;  // device
+    uint64_t hash;             // of the host group list of this call
+};
+__device__ __forceinline__ bool plan_ok(const PlanCheck& pc) {
+    return pc.header->magic == kPlanMagic && pc.header->groups_hash == pc.hash;
+}
 
 struct PlanGroup {             // 16 bytes
     uint64_t offset;           // first element of the group in the flat parameter space
@@ -91,6 +103,7 @@ struct SegTmp {                // 32 bytes, one per segment
 
 struct ScratchLayout {
     uint64_t n_tiles;
+    size_t flags_off;          // uint32[64]; [0] = 1 if the accumulate kernel found the plan not to match the group list
     size_t tile_hdr_off;       // TileHdr[n_tiles]
     size_t seg_tmp_off;        // SegTmp[n_segs], sized for the bound n_tiles / kSegTiles + n_groups
     size_t bitmap_off;         // uint32[n_tiles * kTile / 32]
@@ -104,6 +117,7 @@ inline ScratchLayout scratch_layout(uint64_t n_tiles, uint32_t n_groups) {
     ScratchLayout L;
     L.n_tiles = n_tiles;
     size_t off = 0;
+    L.flags_off = off;     off += 256;
     L.tile_hdr_off = off;  off = align_up(off + n_tiles * sizeof(TileHdr), 256);
     L.seg_tmp_off = off;   off = align_up(off + (size_t)(n_tiles / kSegTiles + n_groups) * sizeof(SegTmp), 256);
     L.bitmap_off = off;    off = align_up(off + n_tiles * (kTile / 8), 256);
@@ -117,29 +131,35 @@ void set_error(const char* fmt, ...);
 int hip_check(hipError_t e, const char* what);
 
 // kernel launchers
-int launch_accumulate_select(const float* g, const float* s, float* r, float* v,
-                             const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles,
+int launch_accumulate_select(PlanCheck pc, uint32_t* flags, const float* g, const float* s, float* r, float* v,
+                             const PlanGroup* groups, const PlanTile* tiles, uint64_t tile0, uint64_t n_tiles,
                              TileHdr* hdrs, uint32_t* bitmap, uint16_t* staging,
                              float alpha, float zeta, float tau, bool hybrid, bool ptrs_vec_aligned,
                              hipStream_t stream);
 
-int launch_pack(const PlanGroup* groups, const PlanTile* tiles, const PlanSeg* segs, uint64_t n_tiles,
+// statistic of an FC layer fused into the accumulate pass (vgc_fused_fc.hip)
+size_t fused_fc_workspace_bytes(int dtype, uint32_t B, uint32_t J, uint32_t C);
+int launch_fused_fc_select(PlanCheck pc, uint32_t* flags, int dtype, const void* X, const void* D, uint32_t B, uint32_t J, uint32_t C,
+                           float c, float* r, float* v, const PlanGroup* groups, uint32_t group, TileHdr* hdrs, uint32_t* bitmap,
+                           uint16_t* staging, float alpha, float zeta, void* workspace, float* g_out, float* s_out, hipStream_t stream);
+
+int launch_pack(PlanCheck pc, const uint32_t* flags, const PlanGroup* groups, const PlanTile* tiles, const PlanSeg* segs, uint64_t n_tiles,
                 uint32_t n_groups, uint32_t n_segs, bool multi_seg,
                 TileHdr* hdrs, SegTmp* stmp, const uint16_t* staging,
                 uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
                 vgc_pack_status* status_out, hipStream_t stream);
 
-int launch_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
+int launch_unpack_add(PlanCheck pc, const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
                       const PlanGroup* groups, uint32_t n_groups, float scale, float* dense,
                       hipStream_t stream);
 
 constexpr int kBatchMax = 8;   // messages one launch of the batched decoder takes
 constexpr int kApplyMax = 64;  // messages the decoder fused with the parameter update takes (one launch; a lane per message)
-int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+int launch_unpack_add_batch(PlanCheck pc, const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
                             uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs,
                             float scale, int overwrite, float* dense, hipStream_t stream);
 
-int launch_unpack_apply(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+int launch_unpack_apply(PlanCheck pc, const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
                         uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs, float scale,
                         int kind, float lr, float mu, float b1, float b2, float omb1, float omb2, float bias1, float bias2,
                         float eps, float* param, float* state1, float* state2, hipStream_t stream);

@@ -70,9 +70,10 @@ __device__ __forceinline__ uint32_t seg_max_exponent(const TileHdr* __restrict__
 
 // Only for groups of more than one segment: the largest tile exponent of every segment, so that the
 // scan kernel's workgroups can each derive E_k of the whole group.
-__global__ __launch_bounds__(1024) void k_seg_max(const PlanGroup* __restrict__ groups, const PlanSeg* __restrict__ segs,
+__global__ __launch_bounds__(1024) void k_seg_max(PlanCheck pc, const PlanGroup* __restrict__ groups, const PlanSeg* __restrict__ segs,
                                                   const TileHdr* __restrict__ hdrs, SegTmp* __restrict__ stmp) {
     __shared__ uint32_t sh[17];
+    if (!plan_ok(pc)) return;
     const PlanSeg ps = segs[blockIdx.x];
     const PlanGroup pg = groups[ps.group];
     const uint32_t nt = (pg.size + kTile - 1) / kTile;
@@ -85,9 +86,10 @@ __global__ __launch_bounds__(1024) void k_seg_max(const PlanGroup* __restrict__ 
 // One workgroup per segment: E_k, then per tile the number of words it keeps and its exclusive
 // prefix inside the segment.  Each thread owns 8 consecutive tile records: they are loaded together,
 // scanned in registers, and only the per-thread totals go through the workgroup scan.
-__global__ __launch_bounds__(1024) void k_seg_scan(const PlanGroup* __restrict__ groups, const PlanSeg* __restrict__ segs,
+__global__ __launch_bounds__(1024) void k_seg_scan(PlanCheck pc, const PlanGroup* __restrict__ groups, const PlanSeg* __restrict__ segs,
                                                    TileHdr* __restrict__ hdrs, SegTmp* __restrict__ stmp) {
     __shared__ uint32_t sh[17];
+    if (!plan_ok(pc)) return;
     const PlanSeg ps = segs[blockIdx.x];
     const PlanGroup pg = groups[ps.group];
     const uint32_t nt = (pg.size + kTile - 1) / kTile;
@@ -152,11 +154,25 @@ __global__ __launch_bounds__(1024) void k_seg_scan(const PlanGroup* __restrict__
 
 // One workgroup: group counts from the segment counts, exclusive scan over the groups -> headers,
 // status, and the position of every segment's first word.
-__global__ __launch_bounds__(1024) void k_header_scan(const PlanGroup* __restrict__ groups, SegTmp* __restrict__ stmp,
+__global__ __launch_bounds__(1024) void k_header_scan(PlanCheck pc, const uint32_t* __restrict__ flags,
+                                                      const PlanGroup* __restrict__ groups, SegTmp* __restrict__ stmp,
                                                       uint32_t n_groups,
                                                       vgc_group_hdr* __restrict__ hdrs_out,
                                                       vgc_pack_status* __restrict__ status, uint64_t words_cap) {
     __shared__ uint32_t sh[16];
+    if (!plan_ok(pc) || flags[0] != 0u) {                   // the plan belongs to another group list: an empty message
+        for (uint32_t k = threadIdx.x; k < n_groups; k += 1024) {
+            vgc_group_hdr h;
+            h.exp_field = 0; h.count = 0; h.word_offset = 0;
+            hdrs_out[k] = h;
+        }
+        if (threadIdx.x == 0) {
+            vgc_pack_status st;
+            st.total_words = 0; st.overflow = 0; st.plan_mismatch = 1;
+            *status = st;
+        }
+        return;
+    }
     uint64_t running = 0;
     uint32_t seg_cursor = 0;                                // first segment of the chunk's first group
     for (uint32_t base = 0; base < n_groups; base += 1024) {
@@ -198,19 +214,19 @@ __global__ __launch_bounds__(1024) void k_header_scan(const PlanGroup* __restric
         vgc_pack_status st;
         st.total_words = running;
         st.overflow = running > words_cap ? 1u : 0u;
-        st.reserved = 0;
+        st.plan_mismatch = 0;
         *status = st;
     }
 }
 
-__global__ __launch_bounds__(256) void k_emit(const PlanTile* __restrict__ tiles, uint64_t n_tiles,
+__global__ __launch_bounds__(256) void k_emit(PlanCheck pc, const PlanTile* __restrict__ tiles, uint64_t n_tiles,
                                               const TileHdr* __restrict__ hdrs, const uint16_t* __restrict__ staging,
                                               const SegTmp* __restrict__ stmp,
                                               uint32_t* __restrict__ words, uint64_t words_cap) {
     constexpr int kAhead = 8;                               // rounds of 64 entries loaded before anything is known
     const uint32_t lane = threadIdx.x & 63u;
     const uint64_t t = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= n_tiles) return;
+    if (t >= n_tiles || !plan_ok(pc)) return;
     const uint16_t* st = staging + t * kTile;
     // Every tile owns kTile staging slots, so the first rounds can be fetched before the tile's count
     // is known (slots past the count hold stale data and are ignored): the loads overlap the header's.
@@ -253,17 +269,17 @@ __global__ __launch_bounds__(256) void k_emit(const PlanTile* __restrict__ tiles
     }
 }
 
-int launch_pack(const PlanGroup* groups, const PlanTile* tiles, const PlanSeg* segs, uint64_t n_tiles,
+int launch_pack(PlanCheck pc, const uint32_t* flags, const PlanGroup* groups, const PlanTile* tiles, const PlanSeg* segs, uint64_t n_tiles,
                 uint32_t n_groups, uint32_t n_segs, bool multi_seg,
                 TileHdr* hdrs, SegTmp* stmp, const uint16_t* staging,
                 uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
                 vgc_pack_status* status_out, hipStream_t stream) {
-    if (multi_seg) hipLaunchKernelGGL(k_seg_max, dim3(n_segs), dim3(1024), 0, stream, groups, segs, hdrs, stmp);
-    hipLaunchKernelGGL(k_seg_scan, dim3(n_segs), dim3(1024), 0, stream, groups, segs, hdrs, stmp);
-    hipLaunchKernelGGL(k_header_scan, dim3(1), dim3(1024), 0, stream, groups, stmp, n_groups, hdrs_out,
+    if (multi_seg) hipLaunchKernelGGL(k_seg_max, dim3(n_segs), dim3(1024), 0, stream, pc, groups, segs, hdrs, stmp);
+    hipLaunchKernelGGL(k_seg_scan, dim3(n_segs), dim3(1024), 0, stream, pc, groups, segs, hdrs, stmp);
+    hipLaunchKernelGGL(k_header_scan, dim3(1), dim3(1024), 0, stream, pc, flags, groups, stmp, n_groups, hdrs_out,
                        status_out, words_cap);
     const uint64_t blocks = (n_tiles + 3) / 4;
-    hipLaunchKernelGGL(k_emit, dim3((uint32_t)blocks), dim3(256), 0, stream, tiles, n_tiles, hdrs, staging,
+    hipLaunchKernelGGL(k_emit, dim3((uint32_t)blocks), dim3(256), 0, stream, pc, tiles, n_tiles, hdrs, staging,
                        stmp, words_out, words_cap);
     return hip_check(hipGetLastError(), "launch pack kernels");
 }

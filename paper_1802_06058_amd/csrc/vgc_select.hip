@@ -8,113 +8,35 @@
 // histogram of exponent codes relative to it, and one 16-bit staged entry per sent element in
 // ascending position order.  The group-wide exponent floor(log2 M_k) is only known after every
 // tile has run, so the final 3-bit code is fixed by the pack kernels from the tile-relative one.
-#include "vgc_internal.h"
+#include "vgc_tile_core.h"
 
 namespace vgc {
 
-typedef float f4 __attribute__((ext_vector_type(4)));
-typedef uint32_t uint4v __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ uint32_t rank_below(uint64_t mask) {
-    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
-}
-
-// Alg. 1 loop body for one element; every operation is a single float32 rounding
-// (the file is compiled without floating-point contraction).
-__device__ __forceinline__ bool alg1_step(float g, float s, float r, float v, float alpha, float zeta,
-                                          float& r_out, float& v_out, uint32_t& acc_bits) {
-    const float rp = r + g;
-    const float vp = v + s;
-    const float lhs = rp * rp;
-    const float rhs = alpha * vp;
-    const bool send = lhs > rhs;
-    r_out = send ? 0.0f : rp;
-    v_out = send ? 0.0f : zeta * vp;
-    acc_bits = __float_as_uint(rp);
-    return send;
-}
-
-// Alg. 2 loop body (hybrid with the threshold method, Section 4.5) for one element:
-//   send = |r'| > tau and r'^2 > alpha v';  sent: r = r' - sign(r') tau,  v = max((v' - (2|r'|) tau) + tau^2, 0);
-//   v *= zeta always.  What is staged for a sent element is +-1.0f: the message carries signs in units of
-//   tau, so the exponent machinery of the basic algorithm sees one constant magnitude (header 2^0, code 0).
-__device__ __forceinline__ bool alg2_step(float g, float s, float r, float v, float alpha, float zeta, float tau,
-                                          float& r_out, float& v_out, uint32_t& acc_bits) {
-    const float rp = r + g;
-    const float vp = v + s;
-    const float lhs = rp * rp;
-    const float rhs = alpha * vp;
-    const bool send = (fabsf(rp) > tau) && (lhs > rhs);
-    const float r_sent = rp - copysignf(tau, rp);
-    const float two_r_tau = (2.0f * fabsf(rp)) * tau;
-    const float v_sent = fmaxf((vp - two_r_tau) + (tau * tau), 0.0f);
-    r_out = send ? r_sent : rp;
-    v_out = zeta * (send ? v_sent : vp);
-    acc_bits = (__float_as_uint(rp) & 0x80000000u) | 0x3F800000u;
-    return send;
-}
-
-template <bool kHybrid>
-__device__ __forceinline__ bool step_any(float g, float s, float r, float v, float alpha, float zeta, float tau,
-                                         float& r_out, float& v_out, uint32_t& acc_bits) {
-    if (kHybrid) return alg2_step(g, s, r, v, alpha, zeta, tau, r_out, v_out, acc_bits);
-    return alg1_step(g, s, r, v, alpha, zeta, r_out, v_out, acc_bits);
-}
-
-// kVec: lane owns elements {u*1024 + 4*tid + c}, u < 2, c < 4 (16-byte accesses).
-// !kVec: lane owns elements {u*256 + tid}, u < 8 (4-byte accesses, any alignment, bounds-checked).
-// Element e of a thread is (u, c) = (e / 4, e % 4) resp. u = e.  In both layouts the elements of
-// segment (u, wave) are a contiguous index range and segments are ordered by u*4 + wave.
+// Loads the thread's eight elements of the four arrays (non-temporal, 16 bytes per lane where the tile is whole
+// and aligned) and hands them to the tile core.
 template <bool kVec, bool kHybrid>
 __device__ __forceinline__ void tile_body(const float* __restrict__ g, const float* __restrict__ s,
                                           float* __restrict__ r, float* __restrict__ v,
                                           uint32_t m, TileHdr* __restrict__ hdr,
                                           uint32_t* __restrict__ bitmap, uint16_t* __restrict__ staging,
                                           float alpha, float zeta, float tau) {
-    __shared__ uint32_t sh_wmax[4];
-    __shared__ uint32_t sh_seg[32];
-    __shared__ uint32_t sh_hist[4][kRelBins];
-    __shared__ __attribute__((aligned(16))) uint16_t sh_stage[kTile];
-
+    __shared__ TileLds sh;
     const uint32_t tid = threadIdx.x;
-    const uint32_t lane = tid & 63u;
-    const uint32_t wave = tid >> 6;
     constexpr int E = kElemsPerThread;
-
-    uint32_t bits[E];
-    uint32_t sendmask = 0;
-
+    float G[E], S[E], R[E], V[E];
     if (kVec) {
-        const f4* g4 = reinterpret_cast<const f4*>(g);
-        const f4* s4 = reinterpret_cast<const f4*>(s);
-        f4* r4 = reinterpret_cast<f4*>(r);
-        f4* v4 = reinterpret_cast<f4*>(v);
-        f4 G[2], S[2], R[2], V[2];
+        f4 G4[2], S4[2], R4[2], V4[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const uint32_t i = u * 256 + tid;
-            G[u] = __builtin_nontemporal_load(g4 + i);
-            S[u] = __builtin_nontemporal_load(s4 + i);
-            R[u] = __builtin_nontemporal_load(r4 + i);
-            V[u] = __builtin_nontemporal_load(v4 + i);
+            G4[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(g) + i);
+            S4[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(s) + i);
+            R4[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(r) + i);
+            V4[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(v) + i);
         }
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            f4 ro, vo;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                float a, b;
-                const bool send = step_any<kHybrid>(G[u][c], S[u][c], R[u][c], V[u][c], alpha, zeta, tau, a, b, bits[u * 4 + c]);
-                ro[c] = a;
-                vo[c] = b;
-                sendmask |= (send ? 1u : 0u) << (u * 4 + c);
-            }
-            const uint32_t i = u * 256 + tid;
-            __builtin_nontemporal_store(ro, r4 + i);
-            __builtin_nontemporal_store(vo, v4 + i);
-        }
+        for (int e = 0; e < E; ++e) { G[e] = G4[e >> 2][e & 3]; S[e] = S4[e >> 2][e & 3]; R[e] = R4[e >> 2][e & 3]; V[e] = V4[e >> 2][e & 3]; }
     } else {
-        float G[E], S[E], R[E], V[E];
 #pragma unroll
         for (int u = 0; u < E; ++u) {
             const uint32_t i = u * 256 + tid;
@@ -126,154 +48,20 @@ __device__ __forceinline__ void tile_body(const float* __restrict__ g, const flo
                 V[u] = __builtin_nontemporal_load(v + i);
             }
         }
-#pragma unroll
-        for (int u = 0; u < E; ++u) {
-            const uint32_t i = u * 256 + tid;
-            float a, b;
-            const bool send = step_any<kHybrid>(G[u], S[u], R[u], V[u], alpha, zeta, tau, a, b, bits[u]) && (i < m);
-            sendmask |= (send ? 1u : 0u) << u;
-            if (i < m) {
-                __builtin_nontemporal_store(a, r + i);
-                __builtin_nontemporal_store(b, v + i);
-            }
-        }
     }
-
-    // ---- send bitmap of the tile (bit i = element i) and the tile's largest truncated exponent ----
-    uint32_t etr = 0;
-#pragma unroll
-    for (int e = 0; e < E; ++e)
-        if (sendmask & (1u << e)) etr = max(etr, (bits[e] & 0x7FFFFFFFu) >> 23);
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) etr = max(etr, (uint32_t)__shfl_xor((int)etr, off));
-    if (lane == 0) sh_wmax[wave] = etr;
-
-    if (kVec) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            uint32_t x = ((sendmask >> (u * 4)) & 0xFu) << (4 * (lane & 7u));
-            x |= (uint32_t)__shfl_xor((int)x, 1);
-            x |= (uint32_t)__shfl_xor((int)x, 2);
-            x |= (uint32_t)__shfl_xor((int)x, 4);
-            if ((lane & 7u) == 0) bitmap[(u * 1024 + wave * 256) / 32 + (lane >> 3)] = x;
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < E; ++u) {
-            const uint64_t b = __ballot((sendmask >> u) & 1u);
-            if (lane == 0) {
-                uint2 w = make_uint2((uint32_t)b, (uint32_t)(b >> 32));
-                *reinterpret_cast<uint2*>(bitmap + (u * 256 + wave * 64) / 32) = w;
-            }
-        }
-    }
-    __syncthreads();
-    etr = max(max(sh_wmax[0], sh_wmax[1]), max(sh_wmax[2], sh_wmax[3]));
-
-    // ---- tile-relative exponent code of every sent element (Section 4.4 rounding recipe) ----
-    uint32_t entry[E];
-    uint32_t stagedmask = 0;
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const uint32_t ab = bits[e] & 0x7FFFFFFFu;
-        const uint32_t ernd = (ab + 0x00400000u) >> 23;       // add one at the mantissa's top bit, drop the mantissa
-        const uint32_t rel = etr + 1u - ernd;                 // >= 0 for sent elements: ernd <= own exponent + 1 <= etr + 1
-        const bool staged = ((sendmask >> e) & 1u) && ernd >= 1u && rel <= 8u;
-        const uint32_t pos = kVec ? ((e >> 2) * 1024 + 4 * tid + (e & 3)) : (e * 256 + tid);
-        entry[e] = ((rel & 15u) << 12) | ((bits[e] >> 31) << 11) | pos;
-        stagedmask |= (staged ? 1u : 0u) << e;
-    }
-
-    // histogram of rel over the wave (uniform values; scalar popcounts)
-    if (kHybrid) {
-        // every staged element is +-1.0f and so is the tile's maximum: rel = 1 for all of them
-        uint32_t cnt = 0;
-#pragma unroll
-        for (int e = 0; e < E; ++e) cnt += __popcll(__ballot((stagedmask >> e) & 1u));
-        if (lane < kRelBins) sh_hist[wave][lane] = (lane == 1u) ? cnt : 0u;
-    } else {
-#pragma unroll
-        for (int j = 0; j < (int)kRelBins; ++j) {
-            uint32_t cnt = 0;
-#pragma unroll
-            for (int e = 0; e < E; ++e)
-                cnt += __popcll(__ballot(((stagedmask >> e) & 1u) && ((entry[e] >> 12) == (uint32_t)j)));
-            if (lane == 0) sh_hist[wave][j] = cnt;
-        }
-    }
-
-    // rank of each staged element inside its segment, and segment totals
-    uint32_t rank[E];
-    constexpr int kSeg = kVec ? 2 : 8;
-    if (kVec) {
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            uint32_t below = 0, total = 0;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                const uint64_t b = __ballot((stagedmask >> (u * 4 + c)) & 1u);
-                below += rank_below(b);
-                total += __popcll(b);
-            }
-            uint32_t acc = below;
-#pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                rank[u * 4 + c] = acc;
-                acc += (stagedmask >> (u * 4 + c)) & 1u;
-            }
-            if (lane == 0) sh_seg[u * 4 + wave] = total;
-        }
-    } else {
-#pragma unroll
-        for (int u = 0; u < E; ++u) {
-            const uint64_t b = __ballot((stagedmask >> u) & 1u);
-            rank[u] = rank_below(b);
-            if (lane == 0) sh_seg[u * 4 + wave] = (uint32_t)__popcll(b);
-        }
-    }
-    __syncthreads();
-
-    // exclusive scan over the kSeg*4 segment totals, redundantly in every wave
-    uint32_t x = (lane < (uint32_t)(kSeg * 4)) ? sh_seg[lane] : 0u;
-    uint32_t incl = x;
-#pragma unroll
-    for (int off = 1; off < 32; off <<= 1) {
-        const uint32_t y = (uint32_t)__shfl_up((int)incl, off);
-        if (lane >= (uint32_t)off) incl += y;
-    }
-    const uint32_t excl = incl - x;
-    const uint32_t n_staged = (uint32_t)__shfl((int)incl, 31);
-    // compact in LDS, then write the tile's entries as whole 16-byte pieces (the tile's staging area is
-    // 4 KiB-aligned; slots between the count and the next multiple of 8 receive stale values that the
-    // reader ignores)
-#pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const int u = kVec ? (e >> 2) : e;
-        const uint32_t segbase = (uint32_t)__shfl((int)excl, u * 4 + (int)wave);
-        if ((stagedmask >> e) & 1u) sh_stage[segbase + rank[e]] = (uint16_t)entry[e];
-    }
-    __syncthreads();
-    if (tid * 8 < n_staged)
-        __builtin_nontemporal_store(reinterpret_cast<const uint4v*>(sh_stage)[tid], reinterpret_cast<uint4v*>(staging) + tid);
-
-    if (tid == 0) {
-        uint32_t h[kRelBins];
-#pragma unroll
-        for (int j = 0; j < (int)kRelBins; ++j) h[j] = sh_hist[0][j] + sh_hist[1][j] + sh_hist[2][j] + sh_hist[3][j];
-        uint4 lo = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-        uint4 hi = make_uint4(h[8] | (etr << 16), 0u, 0u, 0u);
-        reinterpret_cast<uint4*>(hdr)[0] = lo;
-        reinterpret_cast<uint4*>(hdr)[1] = hi;
-    }
+    tile_core<kVec, kHybrid, false>(G, S, R, V, r, v, m, true, hdr, bitmap, staging, alpha, zeta, tau, sh, tid);
 }
 
 template <bool kHybrid>
 __global__ __launch_bounds__(256) void k_accumulate_select(
-    const float* __restrict__ g, const float* __restrict__ s, float* __restrict__ r, float* __restrict__ v,
+    PlanCheck pc, uint32_t* __restrict__ flags, const float* __restrict__ g, const float* __restrict__ s, float* __restrict__ r, float* __restrict__ v,
     const PlanGroup* __restrict__ groups, const PlanTile* __restrict__ tiles,
     TileHdr* __restrict__ hdrs, uint32_t* __restrict__ bitmap, uint16_t* __restrict__ staging,
-    float alpha, float zeta, float tau, int ptrs_vec_aligned) {
-    const uint64_t t = blockIdx.x;
+    float alpha, float zeta, float tau, int ptrs_vec_aligned, uint32_t tile0) {
+    const uint64_t t = (uint64_t)tile0 + blockIdx.x;            // tile0: first tile of the launch (a range of groups)
+    const bool ok = plan_ok(pc);                                // uniform: a few scalar loads
+    if (blockIdx.x == 0 && threadIdx.x == 0) flags[0] = ok ? 0u : 1u;
+    if (!ok) return;
     const PlanTile pt = tiles[t];
     const PlanGroup pg = groups[pt.group];
     const uint64_t base = pg.offset + pt.start;
@@ -287,21 +75,22 @@ __global__ __launch_bounds__(256) void k_accumulate_select(
         tile_body<false, kHybrid>(g + base, s + base, r + base, v + base, m, hdr, bm, st, alpha, zeta, tau);
 }
 
-int launch_accumulate_select(const float* g, const float* s, float* r, float* v,
-                             const PlanGroup* groups, const PlanTile* tiles, uint64_t n_tiles,
+int launch_accumulate_select(PlanCheck pc, uint32_t* flags, const float* g, const float* s, float* r, float* v,
+                             const PlanGroup* groups, const PlanTile* tiles, uint64_t tile0, uint64_t n_tiles,
                              TileHdr* hdrs, uint32_t* bitmap, uint16_t* staging,
                              float alpha, float zeta, float tau, bool hybrid, bool ptrs_vec_aligned,
                              hipStream_t stream) {
-    if (n_tiles > 0x7FFFFFFFull) {
+    if (n_tiles == 0) return VGC_OK;
+    if (tile0 + n_tiles > 0x7FFFFFFFull) {
         set_error("vgc_accumulate_select: %llu tiles exceed the launch limit", (unsigned long long)n_tiles);
         return VGC_ERR_SIZE;
     }
     if (hybrid)
         hipLaunchKernelGGL(k_accumulate_select<true>, dim3((uint32_t)n_tiles), dim3(kThreads), 0, stream,
-                           g, s, r, v, groups, tiles, hdrs, bitmap, staging, alpha, zeta, tau, ptrs_vec_aligned ? 1 : 0);
+                           pc, flags, g, s, r, v, groups, tiles, hdrs, bitmap, staging, alpha, zeta, tau, ptrs_vec_aligned ? 1 : 0, (uint32_t)tile0);
     else
         hipLaunchKernelGGL(k_accumulate_select<false>, dim3((uint32_t)n_tiles), dim3(kThreads), 0, stream,
-                           g, s, r, v, groups, tiles, hdrs, bitmap, staging, alpha, zeta, 0.0f, ptrs_vec_aligned ? 1 : 0);
+                           pc, flags, g, s, r, v, groups, tiles, hdrs, bitmap, staging, alpha, zeta, 0.0f, ptrs_vec_aligned ? 1 : 0, (uint32_t)tile0);
     return hip_check(hipGetLastError(), "launch k_accumulate_select");
 }
 

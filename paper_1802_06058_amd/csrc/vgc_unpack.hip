@@ -6,11 +6,12 @@
 
 namespace vgc {
 
-__global__ __launch_bounds__(256) void k_unpack_add(const uint32_t* __restrict__ words, uint64_t n_words,
+__global__ __launch_bounds__(256) void k_unpack_add(PlanCheck pc, const uint32_t* __restrict__ words, uint64_t n_words,
                                                     const vgc_group_hdr* __restrict__ hdrs,
                                                     const PlanGroup* __restrict__ groups, uint32_t n_groups,
                                                     float scale, float* __restrict__ dense) {
     const uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (!plan_ok(pc)) return;
     const vgc_group_hdr last = hdrs[n_groups - 1];
     uint64_t total = last.word_offset + last.count;
     if (total > n_words) total = n_words;
@@ -34,7 +35,7 @@ __global__ __launch_bounds__(256) void k_unpack_add(const uint32_t* __restrict__
     *p = *p + contrib;
 }
 
-int launch_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
+int launch_unpack_add(PlanCheck pc, const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
                       const PlanGroup* groups, uint32_t n_groups, float scale, float* dense,
                       hipStream_t stream) {
     if (n_words == 0) return VGC_OK;
@@ -43,7 +44,7 @@ int launch_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_h
         set_error("vgc_unpack_add: %llu words exceed the launch limit", (unsigned long long)n_words);
         return VGC_ERR_SIZE;
     }
-    hipLaunchKernelGGL(k_unpack_add, dim3((uint32_t)blocks), dim3(256), 0, stream, words, n_words, hdrs, groups,
+    hipLaunchKernelGGL(k_unpack_add, dim3((uint32_t)blocks), dim3(256), 0, stream, pc, words, n_words, hdrs, groups,
                        n_groups, scale, dense);
     return hip_check(hipGetLastError(), "launch k_unpack_add");
 }
@@ -116,7 +117,7 @@ __device__ __forceinline__ uint64_t shfl64(uint64_t x, int src) {
 }
 
 template <int kMax, int kMode>
-__global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs<kMax> A, const PlanGroup* __restrict__ groups,
+__global__ __launch_bounds__(256) void k_unpack_add_batch(PlanCheck pc, BatchArgs<kMax> A, const PlanGroup* __restrict__ groups,
                                                           const PlanRun* __restrict__ runs, uint32_t n_runs,
                                                           float scale, float* __restrict__ dense, int overwrite,
                                                           UpdateArgs O, uint32_t tiles_per_wave) {
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(256) void k_unpack_add_batch(BatchArgs<kMax> A, con
     const uint32_t per_run = (uint32_t)kRunTiles / tiles_per_wave;
     const uint32_t gw = blockIdx.x * 4 + wave;
     const uint32_t run = gw / per_run;
-    if (run >= n_runs) return;
+    if (run >= n_runs || !plan_ok(pc)) return;
     float* T = sh_tile[wave];
     const uint32_t k = runs[run].group;
     const PlanGroup pg = groups[k];
@@ -291,7 +292,7 @@ static BatchArgs<kMax> batch_args(const uint32_t* const* words, const uint64_t* 
     return A;
 }
 
-int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+int launch_unpack_add_batch(PlanCheck pc, const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
                             uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs,
                             float scale, int overwrite, float* dense, hipStream_t stream) {
     const uint32_t tpw = tiles_per_wave(n_runs);
@@ -299,13 +300,13 @@ int launch_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_word
     const uint32_t chunks = p ? (p + kBatchMax - 1) / kBatchMax : 1;     // p == 0: only the optional clear
     for (uint32_t ch = 0; ch < chunks; ++ch) {
         const BatchArgs<kBatchMax> A = batch_args<kBatchMax>(words, n_words, hdrs, ch * kBatchMax, p);
-        hipLaunchKernelGGL((k_unpack_add_batch<kBatchMax, kToDense>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
+        hipLaunchKernelGGL((k_unpack_add_batch<kBatchMax, kToDense>), dim3(blocks), dim3(256), 0, stream, pc, A, groups, runs,
                            (uint32_t)n_runs, scale, dense, (overwrite && ch == 0) ? 1 : 0, UpdateArgs{}, tpw);
     }
     return hip_check(hipGetLastError(), "launch k_unpack_add_batch");
 }
 
-int launch_unpack_apply(const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
+int launch_unpack_apply(PlanCheck pc, const uint32_t* const* words, const uint64_t* n_words, const vgc_group_hdr* const* hdrs,
                         uint32_t p, const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs, float scale,
                         int kind, float lr, float mu, float b1, float b2, float omb1, float omb2, float bias1, float bias2,
                         float eps, float* param, float* state1, float* state2, hipStream_t stream) {
@@ -316,10 +317,10 @@ int launch_unpack_apply(const uint32_t* const* words, const uint64_t* n_words, c
     O.w = param; O.s1 = state1; O.s2 = state2;
     O.lr = lr; O.mu = mu; O.b1 = b1; O.b2 = b2; O.omb1 = omb1; O.omb2 = omb2; O.bias1 = bias1; O.bias2 = bias2; O.eps = eps;
     if (kind == VGC_OPT_ADAM)
-        hipLaunchKernelGGL((k_unpack_add_batch<kApplyMax, kAdam>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
+        hipLaunchKernelGGL((k_unpack_add_batch<kApplyMax, kAdam>), dim3(blocks), dim3(256), 0, stream, pc, A, groups, runs,
                            (uint32_t)n_runs, scale, static_cast<float*>(nullptr), 1, O, tpw);
     else
-        hipLaunchKernelGGL((k_unpack_add_batch<kApplyMax, kMomentumSgd>), dim3(blocks), dim3(256), 0, stream, A, groups, runs,
+        hipLaunchKernelGGL((k_unpack_add_batch<kApplyMax, kMomentumSgd>), dim3(blocks), dim3(256), 0, stream, pc, A, groups, runs,
                            (uint32_t)n_runs, scale, static_cast<float*>(nullptr), 1, O, tpw);
     return hip_check(hipGetLastError(), "launch k_unpack_add_batch (update)");
 }

@@ -31,7 +31,7 @@ class GroupHdr(C.Structure):
 
 
 class PackStatus(C.Structure):
-    _fields_ = [("total_words", C.c_uint64), ("overflow", C.c_uint32), ("reserved", C.c_uint32)]
+    _fields_ = [("total_words", C.c_uint64), ("overflow", C.c_uint32), ("plan_mismatch", C.c_uint32)]
 
 
 class Optimizer(C.Structure):
@@ -174,8 +174,11 @@ def read_headers(hdrs):
 
 
 def read_status(status):
-    """(total_words, overflow) from a device status tensor (synchronises)."""
+    """(total_words, overflow) from a device status tensor (synchronises).  Raises if the kernels found that the
+    plan they were given was not built from the group list of the call (nothing was computed then)."""
     a = status.cpu().numpy()
+    if int(a[12:16].view("<u4")[0]):
+        raise VgcError("the device plan was not built from the group list passed with it: nothing was computed")
     return int(a[:8].view("<u8")[0]), int(a[8:12].view("<u4")[0])
 
 

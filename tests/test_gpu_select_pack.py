@@ -380,3 +380,40 @@ def test_unpack_add_batch_equals_sequential(dev, p, overwrite):
     got = dense.cpu().numpy()
     assert np.array_equal(_bits(got), _bits(expect)), f"{np.flatnonzero(_bits(got) != _bits(expect))[:10]}"
     assert np.array_equal(_bits(dense_seq.cpu().numpy()), _bits(expect))
+
+
+def test_plan_of_another_group_list_is_refused_on_the_device(dev):
+    """A device plan used with a host group list it was not built from (same n, same number of groups and tiles,
+    so every table has the same size): the kernels compare the list's hash with the plan's and do nothing; the
+    status says so, r, v, the word buffer and the dense buffer stay as they were, the headers describe an empty message."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    a = vgc.Plan(W.groups_from_sizes([4096, 4096]), dev)
+    b = vgc.Plan(W.groups_from_sizes([2048, 6144]), dev)
+    assert (a.n, a.n_groups, a.n_tiles) == (b.n, b.n_groups, b.n_tiles)
+    b.plan = a.plan                                            # host list of b, device tables of a
+    n = a.n
+    g, s = sample_stream(12, (0,), n, 16, "student", sigma=0.01)
+    r = torch.full((n,), 3.0, dtype=torch.float32, device=dev); v = torch.full((n,), 5.0, dtype=torch.float32, device=dev)
+    scratch, hdrs, status = b.new_scratch(), b.new_headers(), b.new_status()
+    hdrs.fill_(0xEE)
+    words = torch.full((n,), -1, dtype=torch.int32, device=dev)
+    vgc.accumulate_select(_dev(g, dev), _dev(s, dev), r, v, b, 1.0, 0.999, scratch)
+    vgc.pack(b, scratch, words, hdrs, status)
+    torch.cuda.synchronize()
+    with pytest.raises(vgc.VgcError, match="not built from the group list"):
+        vgc.read_status(status)
+    assert float(r.min()) == 3.0 == float(r.max()) and float(v.min()) == 5.0 == float(v.max())
+    assert int((words != -1).sum()) == 0
+    assert vgc.read_headers(hdrs) == [(0, 0, 0), (0, 0, 0)]
+    # the decoders refuse the same way: nothing is added
+    good = GpuWorker(W.groups_from_sizes([2048, 6144]), dev)
+    mask, ghdrs, gwords, total, overflow = good.step(_dev(g, dev), _dev(s, dev), 1.0, 0.999)
+    assert total > 0
+    dense = torch.full((n,), 7.0, dtype=torch.float32, device=dev)
+    vgc.unpack_add(good.words, total, good.hdrs, b, 1.0, dense)
+    vgc.unpack_add_batch([good.words], [total], [good.hdrs], b, 1.0, dense, overwrite=True)
+    m = torch.zeros(n, dtype=torch.float32, device=dev)
+    vgc.unpack_apply([good.words], [total], [good.hdrs], b, 1.0, dense, m, kind=vgc.MOMENTUM_SGD, lr=1.0, momentum=0.5)
+    torch.cuda.synchronize()
+    assert float(dense.min()) == 7.0 == float(dense.max()) and float(m.abs().max()) == 0.0
