@@ -53,7 +53,7 @@ __device__ __forceinline__ u4v sq_bf16x8(u4v x) {
 }
 
 constexpr int kFusedTiles = 16;                     // tiles per workgroup
-constexpr int kLdsPitch = kTile + 16;               // floats per staged tile: the four tiles of a pass start 16 banks apart
+constexpr int kLdsPitch = kTile + 8;                // floats per staged tile: slots 2 q and 2 q + 2 start 16 banks apart
 
 struct FusedArgs {
     const void* XT;          // [J, Kp]
@@ -68,22 +68,206 @@ struct FusedArgs {
     float alpha, zeta;
 };
 
+// One tile of the block as a wave sees it.
+struct TileRef {
+    uint64_t base;           // first element in the flat parameter space
+    uint32_t t;              // tile number in the plan (scratch records)
+    uint32_t in_group;       // tile number inside the group
+    uint32_t m;              // elements
+    bool live;               // false: past the end of the layer (the wave only keeps the barriers company)
+    bool vec;                // whole, 16-byte aligned tile: 16-byte accesses
+};
+
+// Alg. 1's loop body on one tile by ONE wave, from g and s staged in LDS (lg, ls: this wave's slot) and r, v in memory.
+// No workgroup barrier inside: the eight waves of a workgroup each run their own tile.  Element e = 4 u + c of a lane
+// is tile element 256 u + 4 lane + c (whole aligned tiles: 16-byte accesses; R4, V4 hold chunks u = 0, 1 on entry, the
+// rest is loaded two chunks ahead), so chunk u is a contiguous range of 256 elements in (lane, c) order.  The slot's g
+// area is reused for the index-ordered staged entries once g has been consumed.
+__device__ __forceinline__ void wave_tile_vec(const FusedArgs& A, const TileRef& q, float* lg, const float* ls, f4 (&R4)[4], f4 (&V4)[4],
+                                              TileHdr* __restrict__ hdrs, uint32_t* __restrict__ bitmap, uint16_t* __restrict__ staging,
+                                              uint32_t lane) {
+    float* r = A.r + q.base;
+    float* v = A.v + q.base;
+    uint32_t* bm = bitmap + (size_t)q.t * (kTile / 32);
+    uint32_t bits[32];
+    uint32_t sendmask = 0, etr = 0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const f4 g4 = reinterpret_cast<const f4*>(lg)[u * 64 + lane];
+        const f4 s4 = reinterpret_cast<const f4*>(ls)[u * 64 + lane];
+        const f4 r4 = R4[u & 3], v4 = V4[u & 3];
+        if (u + 4 < 8) {                                     // chunk u + 4 into the registers chunk u leaves
+            R4[u & 3] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(r) + (u + 4) * 64 + lane);
+            V4[u & 3] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(v) + (u + 4) * 64 + lane);
+        }
+        if (A.g_out) {
+            const size_t o = (size_t)q.in_group * kTile;
+            reinterpret_cast<f4*>(A.g_out + o)[u * 64 + lane] = g4;
+            reinterpret_cast<f4*>(A.s_out + o)[u * 64 + lane] = s4;
+        }
+        f4 ro, vo;
+        uint32_t nib = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float a, b;
+            const bool send = alg1_step(g4[c], s4[c], r4[c], v4[c], A.alpha, A.zeta, a, b, bits[u * 4 + c]);
+            ro[c] = a;
+            vo[c] = b;
+            nib |= (send ? 1u : 0u) << c;
+            if (send) etr = max(etr, (bits[u * 4 + c] & 0x7FFFFFFFu) >> 23);
+        }
+        __builtin_nontemporal_store(ro, reinterpret_cast<f4*>(r) + u * 64 + lane);
+        __builtin_nontemporal_store(vo, reinterpret_cast<f4*>(v) + u * 64 + lane);
+        sendmask |= nib << (4 * u);
+        // send bitmap: bit 256 u + 4 lane + c; eight lanes make one word
+        uint32_t x = nib << (4 * (lane & 7u));
+        x |= (uint32_t)__shfl_xor((int)x, 1);
+        x |= (uint32_t)__shfl_xor((int)x, 2);
+        x |= (uint32_t)__shfl_xor((int)x, 4);
+        if ((lane & 7u) == 0) bm[u * 8 + (lane >> 3)] = x;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) etr = max(etr, (uint32_t)__shfl_xor((int)etr, off));
+
+    // ---- tile-relative exponent codes (Section 4.4's rounding recipe), histogram, index-ordered compaction ----
+    uint16_t* stage = reinterpret_cast<uint16_t*>(lg);
+    uint64_t hist = 0;                                       // nine 6-bit counters (a lane has at most 32 entries)
+    uint32_t base = 0;                                       // entries of the chunks before u (uniform)
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        uint32_t entry[4], below = 0, total = 0, st = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const int e = u * 4 + c;
+            const uint32_t ab = bits[e] & 0x7FFFFFFFu;
+            const uint32_t ernd = (ab + 0x00400000u) >> 23;  // add one at the mantissa's top bit, drop the mantissa
+            const uint32_t rel = etr + 1u - ernd;            // >= 0 for sent elements
+            const bool staged = ((sendmask >> e) & 1u) && ernd >= 1u && rel <= 8u;
+            entry[c] = ((rel & 15u) << 12) | ((bits[e] >> 31) << 11) | (uint32_t)(u * 256 + c) + 4u * lane;
+            hist += staged ? (1ull << (staged ? 6u * rel : 0u)) : 0ull;
+            const uint64_t b = __ballot(staged);
+            below += rank_below(b);
+            total += (uint32_t)__popcll(b);
+            st |= (staged ? 1u : 0u) << c;
+        }
+        uint32_t pos = base + below;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if ((st >> c) & 1u) stage[pos] = (uint16_t)entry[c];
+            pos += (st >> c) & 1u;
+        }
+        base += total;
+    }
+    // wave totals of the nine bins: 12-bit fields in two 64-bit words (bins 0..4, 5..8)
+    uint64_t h_lo = 0, h_hi = 0;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) h_lo |= ((hist >> (6 * j)) & 63ull) << (12 * j);
+#pragma unroll
+    for (int j = 5; j < 9; ++j) h_hi |= ((hist >> (6 * j)) & 63ull) << (12 * (j - 5));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        h_lo += ((uint64_t)(uint32_t)__shfl_xor((int)(uint32_t)(h_lo >> 32), off) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)h_lo, off);
+        h_hi += ((uint64_t)(uint32_t)__shfl_xor((int)(uint32_t)(h_hi >> 32), off) << 32) | (uint32_t)__shfl_xor((int)(uint32_t)h_hi, off);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    uint16_t* out = staging + (size_t)q.t * kTile;
+    for (uint32_t piece = lane; piece * 8u < base; piece += 64u)
+        __builtin_nontemporal_store(reinterpret_cast<const uint4v*>(stage)[piece], reinterpret_cast<uint4v*>(out) + piece);
+    if (lane == 0) {
+        uint32_t h[kRelBins];
+#pragma unroll
+        for (int j = 0; j < 5; ++j) h[j] = (uint32_t)(h_lo >> (12 * j)) & 0xFFFu;
+#pragma unroll
+        for (int j = 5; j < 9; ++j) h[j] = (uint32_t)(h_hi >> (12 * (j - 5))) & 0xFFFu;
+        uint4 lo = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        uint4 hi = make_uint4(h[8] | (etr << 16), 0u, 0u, 0u);
+        reinterpret_cast<uint4*>(hdrs + q.t)[0] = lo;
+        reinterpret_cast<uint4*>(hdrs + q.t)[1] = hi;
+    }
+}
+
+// The same for a tile that is partial or not 16-byte aligned: element e of a lane is tile element 64 e + lane
+// (4-byte accesses, bounds-checked by m), chunk e is a contiguous range of 64 elements in lane order.
+__device__ __forceinline__ void wave_tile_any(const FusedArgs& A, const TileRef& q, float* lg, const float* ls,
+                                              TileHdr* __restrict__ hdrs, uint32_t* __restrict__ bitmap, uint16_t* __restrict__ staging,
+                                              uint32_t lane) {
+    float* r = A.r + q.base;
+    float* v = A.v + q.base;
+    uint32_t* bm = bitmap + (size_t)q.t * (kTile / 32);
+    uint32_t bits[32];
+    uint32_t sendmask = 0, etr = 0;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const uint32_t i = (uint32_t)e * 64u + lane;
+        const bool in = i < q.m;
+        const float g1 = lg[i], s1 = ls[i];
+        const float r1 = in ? __builtin_nontemporal_load(r + i) : 0.f, v1 = in ? __builtin_nontemporal_load(v + i) : 0.f;
+        if (A.g_out && in) {
+            A.g_out[(size_t)q.in_group * kTile + i] = g1;
+            A.s_out[(size_t)q.in_group * kTile + i] = s1;
+        }
+        float a, b;
+        const bool send = alg1_step(g1, s1, r1, v1, A.alpha, A.zeta, a, b, bits[e]) && in;
+        if (in) {
+            __builtin_nontemporal_store(a, r + i);
+            __builtin_nontemporal_store(b, v + i);
+        }
+        sendmask |= (send ? 1u : 0u) << e;
+        if (send) etr = max(etr, (bits[e] & 0x7FFFFFFFu) >> 23);
+        const uint64_t bal = __ballot(send);
+        if (lane == 0) *reinterpret_cast<uint2*>(bm + 2 * e) = make_uint2((uint32_t)bal, (uint32_t)(bal >> 32));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) etr = max(etr, (uint32_t)__shfl_xor((int)etr, off));
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // every lane's reads of lg precede the entries written over it
+    __builtin_amdgcn_wave_barrier();
+    uint16_t* stage = reinterpret_cast<uint16_t*>(lg);
+    uint32_t h[kRelBins];
+#pragma unroll
+    for (int j = 0; j < (int)kRelBins; ++j) h[j] = 0;
+    uint32_t base = 0;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const uint32_t ab = bits[e] & 0x7FFFFFFFu;
+        const uint32_t ernd = (ab + 0x00400000u) >> 23;
+        const uint32_t rel = etr + 1u - ernd;
+        const bool staged = ((sendmask >> e) & 1u) && ernd >= 1u && rel <= 8u;
+        const uint32_t entry = ((rel & 15u) << 12) | ((bits[e] >> 31) << 11) | ((uint32_t)e * 64u + lane);
+#pragma unroll
+        for (int j = 0; j < (int)kRelBins; ++j) h[j] += (uint32_t)__popcll(__ballot(staged && rel == (uint32_t)j));
+        const uint64_t b = __ballot(staged);
+        if (staged) stage[base + rank_below(b)] = (uint16_t)entry;
+        base += (uint32_t)__popcll(b);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    uint16_t* out = staging + (size_t)q.t * kTile;
+    for (uint32_t piece = lane; piece * 8u < base; piece += 64u)
+        __builtin_nontemporal_store(reinterpret_cast<const uint4v*>(stage)[piece], reinterpret_cast<uint4v*>(out) + piece);
+    if (lane == 0) {
+        uint4 lo = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+        uint4 hi = make_uint4(h[8] | (etr << 16), 0u, 0u, 0u);
+        reinterpret_cast<uint4*>(hdrs + q.t)[0] = lo;
+        reinterpret_cast<uint4*>(hdrs + q.t)[1] = hi;
+    }
+}
+
 // kR: rows of [J, C] per tile (1: C is a multiple of 2048 and a tile is a piece of a row; 2, 4, 8: C = 2048 / kR).
 template <int kR, bool kBf16>
 __global__ __launch_bounds__(512) void k_fused_fc_select(PlanCheck pc, uint32_t* __restrict__ flags, FusedArgs A,
                                                          const PlanGroup* __restrict__ groups,
                                                          TileHdr* __restrict__ hdrs, uint32_t* __restrict__ bitmap,
                                                          uint16_t* __restrict__ staging) {
-    __shared__ __attribute__((aligned(16))) float lds_g[4][kLdsPitch];
-    __shared__ __attribute__((aligned(16))) float lds_s[4][kLdsPitch];
-    __shared__ TileLds sh[2];
+    __shared__ __attribute__((aligned(16))) float lds_g[8][kLdsPitch];
+    __shared__ __attribute__((aligned(16))) float lds_s[8][kLdsPitch];
 
     const bool ok = plan_ok(pc);
     if (blockIdx.x == 0 && threadIdx.x == 0) flags[0] = ok ? 0u : 1u;
     if (!ok) return;
 
-    const uint32_t tid = threadIdx.x, lane = tid & 63u, tid_h = tid & 255u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6), half = wave >> 2;      // uniform per wave: scalar registers, scalar branches
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);      // uniform per wave: scalar registers, scalar branches
     const uint32_t lrow = lane & 15u, lgrp = lane >> 4;
     const PlanGroup pg = groups[A.group];
     constexpr uint32_t Cb = kTile / kR;                       // columns one block spans
@@ -93,6 +277,38 @@ __global__ __launch_bounds__(512) void k_fused_fc_select(PlanCheck pc, uint32_t*
     const uint32_t j0 = rb * 16u * kR;                        // first row of the block
     const uint32_t colbase = cb * kTile;
     const uint32_t nt_group = (pg.size + kTile - 1) / kTile;
+
+    // The block's 16 tiles pass through LDS eight at a time; wave w runs the tile in slot w.  Accumulator element i of MFMA
+    // tile t of a lane is row 16 rt + 4 lgrp + i, column 16 (ct0 + t) + lrow of the block; it belongs to tile tl = row / kR at
+    // position (row % kR) Cb + column.  For kR = 1 pass p takes elements i = 2 p, 2 p + 1 of every lane (tiles 4 lgrp + i, slot
+    // 2 lgrp + i % 2: all lanes write), otherwise the tiles 8 p .. 8 p + 7.
+    auto ref_of = [&](int p) -> TileRef {
+        const uint32_t tl = kR == 1 ? 4u * (wave >> 1) + 2u * (uint32_t)p + (wave & 1u) : 8u * (uint32_t)p + wave;
+        TileRef q;
+        q.in_group = kR == 1 ? (j0 + tl) * ncb + cb : (uint32_t)blockIdx.x * kFusedTiles + tl;
+        q.live = kR == 1 ? (j0 + tl) < A.J : q.in_group < nt_group;
+        if (!q.live) q.in_group = 0;
+        q.t = pg.first_tile + q.in_group;
+        q.base = pg.offset + (uint64_t)q.in_group * kTile;
+        q.m = min(kTile, pg.size - q.in_group * kTile);
+        q.vec = q.live && q.m == kTile && ((reinterpret_cast<uintptr_t>(A.r + q.base) | reinterpret_cast<uintptr_t>(A.v + q.base)) & 15u) == 0 &&
+                (!A.g_out || ((reinterpret_cast<uintptr_t>(A.g_out) | reinterpret_cast<uintptr_t>(A.s_out)) & 15u) == 0);
+        return q;
+    };
+    // r and v of the first four chunks of a tile, requested early: they arrive while the matrix cores (pass 0) or the
+    // previous tile's compaction (pass 1) are busy
+    f4 R4[4], V4[4];
+    auto prefetch = [&](const TileRef& q) {
+        if (q.vec) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                R4[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(A.r + q.base) + u * 64 + lane);
+                V4[u] = __builtin_nontemporal_load(reinterpret_cast<const f4*>(A.v + q.base) + u * 64 + lane);
+            }
+        }
+    };
+    TileRef q0 = ref_of(0);
+    prefetch(q0);
 
     // ---- contraction: this wave's 16 MFMA tiles (one row tile, 16 column tiles) ----
     const uint32_t rt = (16u * wave) / CT, ct0 = (16u * wave) % CT;
@@ -155,114 +371,37 @@ __global__ __launch_bounds__(512) void k_fused_fc_select(PlanCheck pc, uint32_t*
 #pragma unroll
     for (int t = 0; t < 16; ++t) { acc_g[t] = acc_g[t] * A.cg; acc_s[t] = acc_s[t] * A.cs; }
 
-    // ---- the block's tiles.  Accumulator element i of MFMA tile t is row 16 rt + 4 lgrp + i, column 16 (ct0 + t) + lrow
-    // of the block; it belongs to tile tl = row / kR at position (row % kR) Cb + column.  Four tiles pass through LDS at a
-    // time: for kR = 1 pass p takes the tiles with tl % 4 = p (accumulator element p of every lane: all lanes write),
-    // otherwise the tiles 4 p .. 4 p + 3.  Step s = (pass, round): half h of the workgroup runs tile slot 2 round + h.
-    auto tile_of = [&](int p, uint32_t slot) -> uint32_t { return kR == 1 ? 4u * slot + (uint32_t)p : 4u * (uint32_t)p + slot; };
-    struct Ref { uint64_t base; uint32_t t, m, in_group; bool live, vec; };
-    auto ref_of = [&](int step) -> Ref {
-        const uint32_t tl = tile_of(step >> 1, 2u * (uint32_t)(step & 1) + half);
-        Ref q;
-        q.in_group = kR == 1 ? (j0 + tl) * ncb + cb : (uint32_t)blockIdx.x * kFusedTiles + tl;
-        q.live = kR == 1 ? (j0 + tl) < A.J : q.in_group < nt_group;
-        if (!q.live) q.in_group = 0;
-        q.t = pg.first_tile + q.in_group;
-        q.base = pg.offset + (uint64_t)q.in_group * kTile;
-        q.m = min(kTile, pg.size - q.in_group * kTile);
-        q.vec = q.live && q.m == kTile && ((reinterpret_cast<uintptr_t>(A.r + q.base) | reinterpret_cast<uintptr_t>(A.v + q.base)) & 15u) == 0 &&
-                (!A.g_out || ((reinterpret_cast<uintptr_t>(A.g_out) | reinterpret_cast<uintptr_t>(A.s_out)) & 15u) == 0);
-        return q;
-    };
-    auto load_rv = [&](const Ref& q, float (&R)[8], float (&V)[8]) {
-        if (q.vec) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const f4 r4 = q.live ? __builtin_nontemporal_load(reinterpret_cast<const f4*>(A.r + q.base) + u * 256 + tid_h) : (f4){0.f, 0.f, 0.f, 0.f};
-                const f4 v4 = q.live ? __builtin_nontemporal_load(reinterpret_cast<const f4*>(A.v + q.base) + u * 256 + tid_h) : (f4){0.f, 0.f, 0.f, 0.f};
+    for (int p = 0; p < 2; ++p) {
+        if (p) __syncthreads();                               // every wave is done with the slots of pass 0
+        if (kR == 1) {
 #pragma unroll
-                for (int c = 0; c < 4; ++c) { R[u * 4 + c] = r4[c]; V[u * 4 + c] = v4[c]; }
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const uint32_t i = u * 256 + tid_h;
-                const bool in = q.live && i < q.m;
-                R[u] = in ? __builtin_nontemporal_load(A.r + q.base + i) : 0.f;
-                V[u] = in ? __builtin_nontemporal_load(A.v + q.base + i) : 0.f;
-            }
-        }
-    };
-
-    float Rn[8], Vn[8];
-    Ref cur = ref_of(0);
-    load_rv(cur, Rn, Vn);
-#pragma unroll
-    for (int step = 0; step < 8; ++step) {
-        const int p = step >> 1;
-        if ((step & 1) == 0) {
-            if (kR == 1) {
+            for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
                 for (int t = 0; t < 16; ++t) {
                     const uint32_t col = 16u * (ct0 + t) + lrow;
-                    lds_g[lgrp][col] = acc_g[t][p];
-                    lds_s[lgrp][col] = acc_s[t][p];
+                    lds_g[2u * lgrp + ii][col] = acc_g[t][2 * p + ii];
+                    lds_s[2u * lgrp + ii][col] = acc_s[t][2 * p + ii];
                 }
-            } else {
+        } else {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t row = 16u * rt + 4u * lgrp + i, tl = row / kR;
-                    if ((tl >> 2) == (uint32_t)p) {
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t row = 16u * rt + 4u * lgrp + i, tl = row / kR;
+                if ((tl >> 3) == (uint32_t)p) {
 #pragma unroll
-                        for (int t = 0; t < 16; ++t) {
-                            const uint32_t pos = (row % kR) * Cb + 16u * (ct0 + t) + lrow;
-                            lds_g[tl & 3u][pos] = acc_g[t][i];
-                            lds_s[tl & 3u][pos] = acc_s[t][i];
-                        }
+                    for (int t = 0; t < 16; ++t) {
+                        const uint32_t pos = (row % kR) * Cb + 16u * (ct0 + t) + lrow;
+                        lds_g[tl & 7u][pos] = acc_g[t][i];
+                        lds_s[tl & 7u][pos] = acc_s[t][i];
                     }
                 }
             }
-            __syncthreads();
         }
-        float R[8], V[8], G[8], S[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { R[e] = Rn[e]; V[e] = Vn[e]; }
-        const Ref q = cur;
-        if (step + 1 < 8) {
-            cur = ref_of(step + 1);
-            load_rv(cur, Rn, Vn);
-        }
-        const uint32_t slot = 2u * (uint32_t)(step & 1) + half;
-        if (q.vec) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const f4 g4 = reinterpret_cast<const f4*>(lds_g[slot])[u * 256 + tid_h];
-                const f4 s4 = reinterpret_cast<const f4*>(lds_s[slot])[u * 256 + tid_h];
-#pragma unroll
-                for (int c = 0; c < 4; ++c) { G[u * 4 + c] = g4[c]; S[u * 4 + c] = s4[c]; }
-                if (A.g_out && q.live) {
-                    const size_t o = (size_t)q.in_group * kTile;
-                    reinterpret_cast<f4*>(A.g_out + o)[u * 256 + tid_h] = g4;
-                    reinterpret_cast<f4*>(A.s_out + o)[u * 256 + tid_h] = s4;
-                }
-            }
-            tile_core<true, false, true>(G, S, R, V, A.r + q.base, A.v + q.base, q.m, q.live, hdrs + q.t, bitmap + (size_t)q.t * (kTile / 32),
-                                         staging + (size_t)q.t * kTile, A.alpha, A.zeta, 0.0f, sh[half], tid_h);
-        } else {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const uint32_t i = u * 256 + tid_h;
-                G[u] = lds_g[slot][i];
-                S[u] = lds_s[slot][i];
-                if (A.g_out && q.live && i < q.m) {
-                    const size_t o = (size_t)q.in_group * kTile + i;
-                    A.g_out[o] = G[u];
-                    A.s_out[o] = S[u];
-                }
-            }
-            tile_core<false, false, true>(G, S, R, V, A.r + q.base, A.v + q.base, q.m, q.live, hdrs + q.t, bitmap + (size_t)q.t * (kTile / 32),
-                                          staging + (size_t)q.t * kTile, A.alpha, A.zeta, 0.0f, sh[half], tid_h);
-        }
+        __syncthreads();
+        const TileRef q = p == 0 ? q0 : ref_of(1);
+        if (p == 1) prefetch(q);
+        if (q.vec) wave_tile_vec(A, q, lds_g[wave], lds_s[wave], R4, V4, hdrs, bitmap, staging, lane);
+        else if (q.live) wave_tile_any(A, q, lds_g[wave], lds_s[wave], hdrs, bitmap, staging, lane);
     }
 }
 

@@ -65,6 +65,14 @@ EXPORTS = {
     "vgc_accumulate_select_hybrid": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
                                                C.c_uint32, C.c_void_p, C.c_float, C.c_float, C.c_float, C.c_void_p,
                                                C.c_void_p]),
+    "vgc_accumulate_select_range": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
+                                              C.c_uint32, C.c_void_p, C.c_uint32, C.c_uint32, C.c_float, C.c_float,
+                                              C.c_void_p, C.c_void_p]),
+    "vgc_sqgrad_accumulate_select_workspace_bytes": (C.c_size_t, [C.c_int, C.c_uint32, C.c_uint32, C.c_uint32]),
+    "vgc_sqgrad_accumulate_select": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_float,
+                                               C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p,
+                                               C.c_uint32, C.c_float, C.c_float, C.c_void_p, C.c_void_p, C.c_size_t,
+                                               C.c_void_p, C.c_void_p, C.c_void_p]),
     "vgc_pack": (C.c_int, [C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
                            C.c_void_p, C.c_void_p, C.c_void_p]),
     "vgc_unpack_add": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
@@ -337,6 +345,45 @@ def accumulate_select_hybrid(g, s, r, v, plan, alpha, zeta, tau, scratch):
     _check(load().vgc_accumulate_select_hybrid(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups,
                                                plan.n_groups, _ptr(plan.plan), float(alpha), float(zeta), float(tau),
                                                _ptr(scratch), _stream()))
+
+
+def accumulate_select_range(g, s, r, v, plan, first_group, group_count, alpha, zeta, scratch):
+    """vgc_accumulate_select_range: the pass over groups [first_group, first_group + group_count) only."""
+    a = _Args(plan.device)
+    a.need_state(plan, scratch, g=g, s=s, r=r, v=v)
+    a.launchable()
+    _check(load().vgc_accumulate_select_range(_ptr(g), _ptr(s), _ptr(r), _ptr(v), plan.n, plan.c_groups, plan.n_groups,
+                                              _ptr(plan.plan), int(first_group), int(group_count), float(alpha), float(zeta),
+                                              _ptr(scratch), _stream()))
+
+
+def sqgrad_accumulate_select_workspace_bytes(dtype, B, J, Cc):
+    return int(load().vgc_sqgrad_accumulate_select_workspace_bytes(dtype, B, J, Cc))
+
+
+def sqgrad_accumulate_select(X, D, c, r, v, plan, group, alpha, zeta, scratch, workspace, g_out=None, s_out=None):
+    """vgc_sqgrad_accumulate_select: the FC statistic of X [B, J], D [B, C] fused into the accumulate pass of
+    group `group` (whose size is J * C).  workspace: uint8 tensor of sqgrad_accumulate_select_workspace_bytes()."""
+    import torch
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(X.dtype)
+    if dtype is None or D.dtype != X.dtype:
+        raise VgcError(f"unsupported dtypes {X.dtype}, {D.dtype}")
+    if X.dim() != 2 or D.dim() != 2 or D.shape[0] != X.shape[0] or not X.is_contiguous() or not D.is_contiguous():
+        raise VgcError(f"X {tuple(X.shape)} and D {tuple(D.shape)} do not belong together (or are not contiguous)")
+    B, J = X.shape
+    Cc = D.shape[1]
+    a = _Args(plan.device)
+    a.on_device(X, "X"); a.on_device(D, "D")
+    a.need_state(plan, scratch, r=r, v=v)
+    a.need(g_out, J * Cc, torch.float32, "g_out")
+    a.need(s_out, J * Cc, torch.float32, "s_out")
+    a.need(workspace, sqgrad_accumulate_select_workspace_bytes(dtype, B, J, Cc), torch.uint8, "workspace")
+    a.launchable()
+    _check(load().vgc_sqgrad_accumulate_select(dtype, _ptr(X), _ptr(D), B, J, Cc, float(c), _ptr(r), _ptr(v), plan.n,
+                                               plan.c_groups, plan.n_groups, _ptr(plan.plan), int(group), float(alpha),
+                                               float(zeta), _ptr(scratch), _ptr(workspace),
+                                               0 if workspace is None else workspace.numel(), _ptr(g_out), _ptr(s_out),
+                                               _stream()))
 
 
 def pack(plan, scratch, words, hdrs, status):
