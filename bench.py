@@ -190,6 +190,7 @@ def main():
     out["stages"]["sparse_regime_fresh_state"] = alpha_sweep(vgc, plan, pool[0][0], pool[0][1], r[0], v[0], zeta, scratch,
                                                              words[0], hdrs[0], status[0], (8.0, 16.0), dense=dense)
     out["stages"]["model_parameter_sets"] = bench_model_sets(dev, a.alpha, zeta)
+    out["stages"]["fused_fc_statistic_select"] = bench_fused_fc(dev, zeta)
     if not a.no_sqgrad:
         out["stages"]["sqgrad"] = bench_sqgrad(dev)
         out["stages"]["vgg16_iteration"] = bench_vgg_iteration(dev, zeta)
@@ -303,6 +304,45 @@ def bench_model_sets(dev, alpha, zeta):
             # sparse regime the method is meant for
             res[name]["alpha_sweep_fresh_state"] = alpha_sweep(vgc, plan, g, s, r, v, zeta, scratch, words, hdrs, status,
                                                                (0.5, 1.0, 2.0, 4.0, 8.0, 16.0))
+    return res
+
+
+def bench_fused_fc(dev, zeta):
+    """The two large FC layers of the VGG-16-shaped configuration (bf16, batch 64): statistic + accumulate pass as two
+    calls (vgc_sqgrad writes g and s, vgc_accumulate_select reads them back: 32 bytes per parameter) against the fused
+    call (vgc_sqgrad_accumulate_select: g and s stay on chip, 16 bytes per parameter: r and v read and written).  Both
+    are followed by the same vgc_pack, not timed here."""
+    import torch
+    from paper_1802_06058_amd import vgc, workloads as W
+    res = {}
+    for name, B, J, C in (("vgg_fc6_25088x4096_B64_bf16", 64, 25088, 4096), ("vgg_fc7_4096x4096_B64_bf16", 64, 4096, 4096)):
+        plan = vgc.Plan(W.groups_from_sizes([J * C]), dev)
+        n = plan.n
+        gen = torch.Generator(device=dev); gen.manual_seed(2)
+        X = torch.randn((B, J), generator=gen, device=dev).to(torch.bfloat16)
+        D = (torch.randn((B, C), generator=gen, device=dev) * 1e-3).to(torch.bfloat16)
+        r = torch.zeros(n, device=dev); v = torch.zeros(n, device=dev)
+        g = torch.empty(J, C, device=dev); s = torch.empty(J, C, device=dev)
+        scratch, hdrs, status = plan.new_scratch(), plan.new_headers(), plan.new_status()
+        words = torch.empty(n, dtype=torch.int32, device=dev)
+        ws = torch.empty(vgc.sqgrad_accumulate_select_workspace_bytes(vgc.BF16, B, J, C), dtype=torch.uint8, device=dev)
+
+        def two_calls():
+            vgc.sqgrad(vgc.FC, X, D, 1.0 / B, s, g)
+            vgc.accumulate_select(g.view(-1), s.view(-1), r, v, plan, 1.0, zeta, scratch)
+
+        def fused():
+            vgc.sqgrad_accumulate_select(X, D, 1.0 / B, r, v, plan, 0, 1.0, zeta, scratch, ws)
+        t2 = _timed(two_calls, 60.0, 60.0)
+        tf = _timed(fused, 60.0, 60.0)
+        vgc.pack(plan, scratch, words, hdrs, status)
+        torch.cuda.synchronize()
+        rho = vgc.read_status(status)[0] / n
+        res[name] = {"two_calls_ms": round(t2, 4), "two_calls_GBs_32B_per_param": round(32.0 * n / t2 / 1e6, 1),
+                     "fused_ms": round(tf, 4), "fused_GBs_16B_per_param": round(16.0 * n / tf / 1e6, 1),
+                     "fused_frac_of_peak": round(16.0 * n / tf / 1e6 / HBM_PEAK_GBS, 4), "speedup": round(t2 / tf, 3),
+                     "sent_fraction_steady_state": round(rho, 4)}
+        del X, D, r, v, g, s, scratch, words, ws
     return res
 
 

@@ -39,11 +39,14 @@ __global__ __launch_bounds__(256) void k_fc_transpose(const T* __restrict__ src,
     *reinterpret_cast<u4v*>(dst + (size_t)w * Kp + (size_t)kc * kPer) = *reinterpret_cast<const u4v*>(out);
 }
 
-// Square of two packed bf16 values: float32 product, rounded to nearest-even bf16 (2^-9 relative per factor).
+// Squares of packed bf16 values: float32 products, rounded to nearest-even bf16 (2^-9 relative per factor) by the
+// hardware's packed conversion.
+typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
+typedef float f2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t sq_bf16x2(uint32_t w) {
     const float lo = __uint_as_float(w << 16), hi = __uint_as_float(w & 0xFFFF0000u);
-    const uint32_t a = __float_as_uint(lo * lo), b = __float_as_uint(hi * hi);
-    return ((a + 0x7FFFu + ((a >> 16) & 1u)) >> 16) | ((b + 0x7FFFu + ((b >> 16) & 1u)) & 0xFFFF0000u);
+    const f2v p = {lo * lo, hi * hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf2v));
 }
 __device__ __forceinline__ u4v sq_bf16x8(u4v x) {
     u4v y;
