@@ -24,6 +24,8 @@ What is implemented, in the paper's order and notation:
   momentum_sgd_step,  the parameter update that follows it (Sections 4.1, 4.3), with the
   adam_step,          elements nobody sent entering as zero; unpack_apply = decode + one step.
   unpack_apply
+  pack_compact,       the compressed index encoding Section 4.2's last paragraph names without an algorithm
+  unpack_compact      (this build's own format: gap to the previous element, one or two bytes per element).
 
 Readings taken where the paper is silent are stated at the function that needs them.
 Every function here is pinned by tests that do not go through this module's own
@@ -493,3 +495,113 @@ def unpack_apply(messages, groups, scale, n, optimizer, w, state1, state2=None, 
     if optimizer == "adam":
         return adam_step(ghat, w, state1, state2, hyper["lr"], hyper["beta1"], hyper["beta2"], hyper["eps"], hyper["t"])
     raise ValueError(optimizer)
+
+
+# --------------------------------------------------------------------------------------
+# Compressed index encoding (Section 4.2, closing remark: the index bits can be reduced
+# further by compressing the indexes; the paper names the idea and gives no algorithm)
+# --------------------------------------------------------------------------------------
+# Reading taken (the format is this build's own): the words of a message are in ascending
+# index order, so an element is stored as the distance from its predecessor instead of a
+# 28-bit absolute index.  The parameter space of a group is cut into tiles of COMPACT_TILE
+# consecutive elements (the last one of a group may be partial), and tiles into runs of
+# COMPACT_RUN consecutive tiles of one group.  For every tile, in order, every element of
+# the message inside it, in ascending index order, becomes
+#     gap  = pos - prev - 1      pos = index inside the tile, prev = pos of the tile's previous
+#                                element, -1 for its first
+#     code = sign << 3 | d       the 4-bit value of Section 4.2 (top four bits of the word)
+#     gap < 8 :  one byte    gap << 4 | code                       (bit 7 clear)
+#     else    :  two bytes   0x80 | (gap & 7) << 4 | code,  gap >> 3     (gap <= 2047, so <= 255)
+# The message is: the group headers (exp_field, count, byte offset of the group's first tile),
+# tile_bytes[t] (uint16, bytes of every tile), run_offsets[r] (uint64, byte offset of every
+# run's first tile) and the byte stream.  Each element takes one or two bytes where the plain
+# format takes four.
+
+COMPACT_TILE = 2048
+COMPACT_RUN = 64
+
+
+def compact_layout(groups):
+    """[(group, first element inside the group, elements)] per tile and the index of each run's first tile."""
+    tiles, run_first = [], []
+    for k, (off, size) in enumerate(groups):
+        for i, start in enumerate(range(0, size, COMPACT_TILE)):
+            if i % COMPACT_RUN == 0:
+                run_first.append(len(tiles))
+            tiles.append((k, start, min(COMPACT_TILE, size - start)))
+    return tiles, run_first
+
+
+def pack_compact(words, headers, groups):
+    """Re-encode a message (words, headers as `pack` returns them) with compressed indexes.
+    Returns (stream uint8[], tile_bytes uint16[n_tiles], run_offsets uint64[n_runs],
+             headers [(exp_field, count, byte offset of the group's stream)]).
+    Plain loops over tiles and elements, in the order the format is defined."""
+    words = np.asarray(words, dtype=U32)
+    tiles, run_first = compact_layout(groups)
+    stream = bytearray()
+    tile_bytes = np.zeros(len(tiles), np.uint16)
+    tile_offset = np.zeros(len(tiles) + 1, np.uint64)
+    out_headers = []
+    t = 0
+    for k, ((off, size), (exp_field, count, word_offset)) in enumerate(zip(groups, headers)):
+        out_headers.append((exp_field, count, len(stream)))
+        w = words[word_offset:word_offset + count]
+        idx = (w & U32(INDEX_MASK)).astype(np.int64)
+        code = (w >> U32(28)).astype(np.int64)
+        assert np.all(np.diff(idx) > 0) and (count == 0 or idx[-1] < size)
+        j = 0
+        for start in range(0, size, COMPACT_TILE):
+            begin = len(stream)
+            prev = -1
+            while j < count and idx[j] < start + COMPACT_TILE:
+                pos = int(idx[j]) - start
+                gap = pos - prev - 1
+                assert 0 <= gap < COMPACT_TILE
+                if gap < 8:
+                    stream.append((gap << 4) | int(code[j]))
+                else:
+                    stream.append(0x80 | ((gap & 7) << 4) | int(code[j]))
+                    stream.append(gap >> 3)
+                prev = pos
+                j += 1
+            tile_offset[t] = begin
+            tile_bytes[t] = len(stream) - begin
+            t += 1
+        assert j == count
+    tile_offset[t] = len(stream)
+    run_offsets = np.array([tile_offset[f] for f in run_first], np.uint64)
+    return np.frombuffer(bytes(stream), np.uint8).copy(), tile_bytes, run_offsets, out_headers
+
+
+def unpack_compact(stream, tile_bytes, run_offsets, headers, groups):
+    """Inverse of pack_compact: the message in the plain format (words uint32[], headers).  Walks the runs
+    through run_offsets and the tiles through tile_bytes, as a receiver does."""
+    stream = np.asarray(stream, dtype=np.uint8)
+    tiles, run_first = compact_layout(groups)
+    run_of_tile = {f: r for r, f in enumerate(run_first)}
+    words = []
+    out_headers = []
+    word_offset = 0
+    cursor = 0
+    per_group = [0] * len(groups)
+    for t, (k, start, m) in enumerate(tiles):
+        if t in run_of_tile:
+            cursor = int(run_offsets[run_of_tile[t]])
+        end = cursor + int(tile_bytes[t])
+        pos = -1
+        while cursor < end:
+            b = int(stream[cursor]); cursor += 1
+            gap = (b >> 4) & 7
+            if b & 0x80:
+                gap |= int(stream[cursor]) << 3; cursor += 1
+            pos += gap + 1
+            assert pos < m
+            words.append(((b & 15) << 28) | (start + pos))
+            per_group[k] += 1
+        assert cursor == end
+    for k, (exp_field, count, _) in enumerate(headers):
+        assert per_group[k] == count
+        out_headers.append((exp_field, count, word_offset))
+        word_offset += count
+    return np.array(words, dtype=np.uint64).astype(U32), out_headers
