@@ -189,6 +189,7 @@ def main():
     # the sparse regime, one worker of the flat workload on a fresh state
     out["stages"]["sparse_regime_fresh_state"] = alpha_sweep(vgc, plan, pool[0][0], pool[0][1], r[0], v[0], zeta, scratch,
                                                              words[0], hdrs[0], status[0], (8.0, 16.0), dense=dense)
+    out["stages"]["compressed_indexes"] = bench_compact(vgc, plan, pool, r[0], v[0], a.alpha, zeta, scratch, words, hdrs, status, dense, N, P, scale)
     out["stages"]["model_parameter_sets"] = bench_model_sets(dev, a.alpha, zeta)
     out["stages"]["fused_fc_statistic_select"] = bench_fused_fc(dev, zeta)
     if not a.no_sqgrad:
@@ -198,6 +199,31 @@ def main():
     if not a.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(pool[0], a, cfg, min(a.cpu_sample, N))
     print(json.dumps(out))
+
+
+def bench_compact(vgc, plan, pool, r, v, alpha, zeta, scratch, words, hdrs, status, dense, N, P, scale):
+    """The compressed index format on the flat workload: worker 0's steady-state message (its state after the timed
+    steps) packed both ways, sizes compared; then P copies of that message decoded in one pass, plain against compact."""
+    import torch
+    dev = dense.device
+    g, s = pool[0]
+    vgc.accumulate_select(g, s, r, v, plan, alpha, zeta, scratch)
+    stream = torch.empty(N, dtype=torch.uint8, device=dev)
+    tile_bytes = torch.empty(plan.n_tiles, dtype=torch.int16, device=dev)
+    run_offsets = torch.empty(plan.n_runs, dtype=torch.int64, device=dev)
+    chdrs, cstatus = plan.new_headers(), plan.new_status()
+    t_plain = _timed(lambda: vgc.pack(plan, scratch, words[0], hdrs[0], status[0]), 30.0, 60.0)
+    t_comp = _timed(lambda: vgc.pack_compact(plan, scratch, stream, tile_bytes, run_offsets, chdrs, cstatus), 30.0, 60.0)
+    n_words, n_bytes = vgc.read_status(status[0])[0], vgc.read_status(cstatus)[0]
+    plain_bytes = 4.0 * n_words + 16.0 * plan.n_groups
+    comp_bytes = n_bytes + 2.0 * plan.n_tiles + 8.0 * plan.n_runs + 16.0 * plan.n_groups
+    t_dp = _timed(lambda: vgc.unpack_add_batch([words[0]] * P, [n_words] * P, [hdrs[0]] * P, plan, scale, dense, overwrite=True), 30.0, 60.0)
+    t_dc = _timed(lambda: vgc.unpack_compact_add_batch([stream] * P, [n_bytes] * P, [tile_bytes] * P, [run_offsets] * P, [chdrs] * P,
+                                                      plan, scale, dense, overwrite=True), 30.0, 60.0)
+    return {"sent_fraction": round(n_words / N, 5), "plain_message_bytes": plain_bytes, "compact_message_bytes": comp_bytes,
+            "size_ratio": round(plain_bytes / comp_bytes, 3), "bits_per_element_compact": round(8.0 * comp_bytes / max(n_words, 1), 3),
+            "pack_plain_ms": round(t_plain, 4), "pack_compact_ms": round(t_comp, 4),
+            "decode_plain_ms": round(t_dp, 4), "decode_compact_ms": round(t_dc, 4), "messages_decoded": P}
 
 
 def student_stream(W, n, batch, nu, seed, device, chunk=1 << 24):

@@ -285,6 +285,37 @@ int vgc_unpack_add_batch(const uint32_t* const* words, const uint64_t* n_words,
                          const vgc_group* groups, uint32_t n_groups, const void* plan,
                          float scale, int overwrite, float* dense_out, uint64_t n, void* stream);
 
+/* ---- compressed index encoding ----------------------------------------------------------------
+ * Section 4.2 ends by noting that the bits spent on indexes can be reduced further by compressing them, without
+ * giving an algorithm; this format is the library's own.  Elements are in ascending index order, so each is stored
+ * as its distance from the previous element of its tile (vgc_tile_size() consecutive elements of a group):
+ *     gap  = position in tile - position of the tile's previous element - 1      (the first element counts from -1)
+ *     code = sign << 3 | d                                                      (the 4-bit value of Section 4.2)
+ *     gap < 8:  one byte   gap << 4 | code
+ *     else:     two bytes  0x80 | (gap & 7) << 4 | code,  gap >> 3              (gap <= 2047)
+ * A message is: the group headers (exp_field and count as in the plain format; word_offset = BYTE offset of the
+ * group's first tile in the stream), tile_bytes[t] (bytes of tile t, tiles numbered as for vgc_scratch_bitmap_offset),
+ * run_offsets[r] (byte offset of the first tile of run r; a run is 64 consecutive tiles of one group, runs numbered
+ * group after group) and the byte stream.  One or two bytes per element instead of four; with the directory
+ * (2 bytes per tile, 8 per run) it is the smaller format once a message holds one element per tile on average.
+ *
+ * vgc_pack_compact consumes the scratch left by vgc_accumulate_select exactly as vgc_pack does (either or both may
+ * follow one accumulate call).  stream_out: DEVICE uint8[stream_cap], never written past stream_cap (2 * n bytes
+ * cannot overflow); tile_bytes_out: DEVICE uint16[vgc_tile_count()]; run_offsets_out: DEVICE uint64[vgc_run_count()];
+ * status_out->total_words is the stream's length in BYTES, overflow and plan_mismatch as for vgc_pack.
+ *
+ * vgc_unpack_compact_add_batch is vgc_unpack_add_batch for such messages (HOST arrays of p DEVICE pointers;
+ * stream_bytes: HOST array of the streams' lengths, beyond which nothing is read): same sums, bit for bit, as
+ * decoding the messages in the plain format in message order. */
+uint64_t vgc_run_count(const vgc_group* groups, uint32_t n_groups, uint64_t n);
+int vgc_pack_compact(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void* plan, void* scratch,
+                     uint8_t* stream_out, uint64_t stream_cap, uint16_t* tile_bytes_out, uint64_t* run_offsets_out,
+                     vgc_group_hdr* hdrs_out, vgc_pack_status* status_out, void* stream);
+int vgc_unpack_compact_add_batch(const uint8_t* const* streams, const uint64_t* stream_bytes, const uint16_t* const* tile_bytes,
+                                 const uint64_t* const* run_offsets, const vgc_group_hdr* const* hdrs, uint32_t p,
+                                 const vgc_group* groups, uint32_t n_groups, const void* plan, float scale, int overwrite,
+                                 float* dense_out, uint64_t n, void* stream);
+
 /* ---- decode fused with the parameter update --------------------------------------------------
  * CommunicateAndUpdate() of Alg. 1 in one pass (Section 4.3; with Momentum SGD and the like,
  * elements that no worker sent enter the update as zero, Section 4.1): the p messages are decoded

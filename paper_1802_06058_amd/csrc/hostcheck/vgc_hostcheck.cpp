@@ -36,7 +36,7 @@ static uint64_t total(const std::vector<uint32_t>& sizes) {
 // byte offsets the header names.  Only what the header itself states is assumed here.
 struct Header { uint64_t magic, n, n_tiles; uint32_t n_groups, tile; uint64_t groups_off, tiles_off, runs_off, n_runs, segs_off, n_segs; };
 struct PGroup { uint64_t offset; uint32_t size, first_tile; };
-struct PTile { uint32_t group, start, seg, reserved; };
+struct PTile { uint32_t group, start, seg, run; };
 struct PRun { uint32_t group, first_tile; };
 struct PSeg { uint32_t group, first_tile, seg_in_group, group_first_seg; };
 
@@ -49,6 +49,9 @@ static void check_plan(const std::vector<uint32_t>& sizes) {
     uint64_t tiles = 0;
     for (uint32_t s : sizes) tiles += (s + T - 1) / T;
     CHECK(vgc_tile_count(g.data(), (uint32_t)g.size(), n) == tiles);
+    uint64_t n_runs = 0;
+    for (uint32_t s : sizes) n_runs += ((s + T - 1) / T + 63) / 64;
+    CHECK(vgc_run_count(g.data(), (uint32_t)g.size(), n) == n_runs);
     CHECK(vgc_scratch_bytes(g.data(), (uint32_t)g.size(), n) >= tiles * (T * 2 + T / 8 + 32));
     CHECK(vgc_scratch_bitmap_offset(g.data(), (uint32_t)g.size(), n) < vgc_scratch_bytes(g.data(), (uint32_t)g.size(), n));
     // the builder must stay inside exactly `bytes`: the buffer is allocated to the byte, so that the
@@ -80,10 +83,10 @@ static void check_plan(const std::vector<uint32_t>& sizes) {
                       S[seg].group_first_seg == first_seg);
                 ++seg;
             }
-            CHECK(Tl[t].group == k && Tl[t].start == (uint64_t)i * T && Tl[t].seg == seg - 1);
+            CHECK(Tl[t].group == k && Tl[t].start == (uint64_t)i * T && Tl[t].seg == seg - 1 && Tl[t].run == run - 1);
         }
     }
-    CHECK(t == tiles && run == h.n_runs && seg == h.n_segs);
+    CHECK(t == tiles && run == h.n_runs && run == n_runs && seg == h.n_segs);
 }
 
 static void check_group_errors() {
@@ -157,6 +160,8 @@ static void check_compute_errors() {
     CHECK(vgc_pack(n, g.data(), 2, plan, scratch, nullptr, 100, hdrs, st, nullptr) == VGC_ERR_NULL);
     CHECK(vgc_pack(n, g.data(), 1, plan, scratch, words, 100, hdrs, st, nullptr) == VGC_ERR_SIZE);
     CHECK(vgc_pack(n, g.data(), 2, plan, scratch, words, 100, static_cast<vgc_group_hdr*>(fake(0x50004)), st, nullptr) == VGC_ERR_ALIGN);
+    CHECK(vgc_pack_compact(n, g.data(), 2, plan, scratch, nullptr, 100, static_cast<uint16_t*>(fake(0x70000)), static_cast<uint64_t*>(fake(0x80000)), hdrs, st, nullptr) == VGC_ERR_NULL);
+    CHECK(vgc_pack_compact(n, g.data(), 2, plan, scratch, static_cast<uint8_t*>(fake(0x90001)), 100, static_cast<uint16_t*>(fake(0x70001)), static_cast<uint64_t*>(fake(0x80000)), hdrs, st, nullptr) == VGC_ERR_ALIGN);
     // (d)
     CHECK(vgc_unpack_add(words, 10, nullptr, g.data(), 2, plan, 1.f, f, n, nullptr) == VGC_ERR_NULL);
     CHECK(vgc_unpack_add(words, 10, hdrs, g.data(), 2, plan, 0.f / 0.f, f, n, nullptr) == VGC_ERR_PARAM);

@@ -186,8 +186,8 @@ int vgc_plan_build(const vgc_group* groups, uint32_t n_groups, uint64_t n, void*
                 S[sn].group_first_seg = group_first_seg;
                 ++sn;
             }
-            T[t].group = k; T[t].start = (uint32_t)start; T[t].seg = sn - 1;
             if (in_group % kRunTiles == 0) { R[rn].group = k; R[rn].first_tile = in_group; ++rn; }
+            T[t].group = k; T[t].start = (uint32_t)start; T[t].seg = sn - 1; T[t].run = (uint32_t)(rn - 1);
         }
     }
     return VGC_OK;
@@ -412,6 +412,71 @@ int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void*
                        reinterpret_cast<SegTmp*>(sc + L.seg_tmp_off),
                        reinterpret_cast<const uint16_t*>(sc + L.staging_off),
                        words_out, words_cap, hdrs_out, status_out, static_cast<hipStream_t>(stream));
+}
+
+uint64_t vgc_run_count(const vgc_group* groups, uint32_t n_groups, uint64_t n) {
+    uint64_t t = 0;
+    GroupStats gs;
+    return check_groups(groups, n_groups, n, &t, &gs) == VGC_OK ? gs.n_runs : 0;
+}
+
+int vgc_pack_compact(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void* plan, void* scratch,
+                     uint8_t* stream_out, uint64_t stream_cap, uint16_t* tile_bytes_out, uint64_t* run_offsets_out,
+                     vgc_group_hdr* hdrs_out, vgc_pack_status* status_out, void* stream) {
+    if (!plan || !scratch || !hdrs_out || !status_out || !tile_bytes_out || !run_offsets_out || (!stream_out && stream_cap)) {
+        set_error("vgc_pack_compact: NULL pointer");
+        return VGC_ERR_NULL;
+    }
+    uint64_t n_tiles = 0;
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
+    if (rc != VGC_OK) return rc;
+    if (!aligned(plan, 256) || !aligned(scratch, 256) || !aligned(tile_bytes_out, 2) || !aligned(run_offsets_out, 8) ||
+        !aligned(hdrs_out, 8) || !aligned(status_out, 8)) {
+        set_error("vgc_pack_compact: misaligned pointer");
+        return VGC_ERR_ALIGN;
+    }
+    const ScratchLayout L = scratch_layout(n_tiles, n_groups);
+    const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    char* sc = static_cast<char*>(scratch);
+    const PlanCheck pc = plan_check(plan, gs);
+    TileHdr* th = reinterpret_cast<TileHdr*>(sc + L.tile_hdr_off);
+    rc = launch_pack_scans(pc, reinterpret_cast<const uint32_t*>(sc + L.flags_off), pv.groups, pv.segs, n_groups, gs.n_segs, gs.multi_seg, th,
+                           reinterpret_cast<SegTmp*>(sc + L.seg_tmp_off), hdrs_out, status_out, ~0ull, static_cast<hipStream_t>(stream));
+    if (rc != VGC_OK) return rc;
+    return launch_pack_compact(pc, pv.groups, pv.tiles, pv.runs, n_tiles, gs.n_runs, n_groups, th,
+                               reinterpret_cast<const uint16_t*>(sc + L.staging_off), stream_out, stream_cap, tile_bytes_out,
+                               run_offsets_out, hdrs_out, status_out, static_cast<hipStream_t>(stream));
+}
+
+int vgc_unpack_compact_add_batch(const uint8_t* const* streams, const uint64_t* stream_bytes, const uint16_t* const* tile_bytes,
+                                 const uint64_t* const* run_offsets, const vgc_group_hdr* const* hdrs, uint32_t p,
+                                 const vgc_group* groups, uint32_t n_groups, const void* plan, float scale, int overwrite,
+                                 float* dense_out, uint64_t n, void* stream) {
+    if (!plan || !dense_out || (p && (!streams || !stream_bytes || !tile_bytes || !run_offsets || !hdrs))) {
+        set_error("vgc_unpack_compact_add_batch: NULL pointer");
+        return VGC_ERR_NULL;
+    }
+    uint64_t n_tiles = 0;
+    GroupStats gs;
+    int rc = check_groups(groups, n_groups, n, &n_tiles, &gs);
+    if (rc != VGC_OK) return rc;
+    for (uint32_t w = 0; w < p; ++w) {
+        if (!hdrs[w] || !tile_bytes[w] || !run_offsets[w] || (!streams[w] && stream_bytes[w])) {
+            set_error("vgc_unpack_compact_add_batch: message %u has a NULL pointer", w);
+            return VGC_ERR_NULL;
+        }
+        if (!aligned(tile_bytes[w], 2) || !aligned(run_offsets[w], 8) || !aligned(hdrs[w], 8)) {
+            set_error("vgc_unpack_compact_add_batch: message %u is misaligned", w);
+            return VGC_ERR_ALIGN;
+        }
+    }
+    if (!aligned(plan, 256) || !aligned(dense_out, 4)) { set_error("vgc_unpack_compact_add_batch: misaligned pointer"); return VGC_ERR_ALIGN; }
+    if (!std::isfinite(scale)) { set_error("vgc_unpack_compact_add_batch: scale is not finite"); return VGC_ERR_PARAM; }
+    if (p == 0 && !overwrite) return VGC_OK;
+    const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    return launch_unpack_compact_batch(plan_check(plan, gs), streams, stream_bytes, tile_bytes, run_offsets, hdrs, p, pv.groups, pv.runs,
+                                       gs.n_runs, scale, overwrite, dense_out, static_cast<hipStream_t>(stream));
 }
 
 int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,

@@ -18,7 +18,7 @@ constexpr uint32_t kThreads = 256;
 constexpr uint32_t kElemsPerThread = kTile / kThreads;   // 8
 constexpr uint32_t kRelBins = 9;                          // staged exponent codes 0..8 (see StagedEntry)
 
-constexpr uint64_t kPlanMagic = 0x33304E414C504756ull;    // "VGPLAN03"
+constexpr uint64_t kPlanMagic = 0x34304E414C504756ull;    // "VGPLAN04"
 
 struct PlanHeader {            // 128 bytes at the start of the plan blob
     uint64_t magic;
@@ -57,7 +57,7 @@ struct PlanTile {              // 16 bytes
     uint32_t group;
     uint32_t start;            // element offset of the tile inside its group (multiple of kTile)
     uint32_t seg;              // index of the tile's segment in the segment table
-    uint32_t reserved;
+    uint32_t run;              // index of the tile's run in the run table
 };
 
 // A segment is up to kSegTiles consecutive tiles of one group: the unit one workgroup of the scan
@@ -148,6 +148,19 @@ int launch_pack(PlanCheck pc, const uint32_t* flags, const PlanGroup* groups, co
                 TileHdr* hdrs, SegTmp* stmp, const uint16_t* staging,
                 uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
                 vgc_pack_status* status_out, hipStream_t stream);
+
+// the scans of vgc_pack without the word emission (vgc_pack.hip), and the compressed index format (vgc_compact.hip)
+int launch_pack_scans(PlanCheck pc, const uint32_t* flags, const PlanGroup* groups, const PlanSeg* segs, uint32_t n_groups,
+                      uint32_t n_segs, bool multi_seg, TileHdr* hdrs, SegTmp* stmp, vgc_group_hdr* hdrs_out,
+                      vgc_pack_status* status_out, uint64_t words_cap, hipStream_t stream);
+int launch_pack_compact(PlanCheck pc, const PlanGroup* groups, const PlanTile* tiles, const PlanRun* runs, uint64_t n_tiles,
+                        uint64_t n_runs, uint32_t n_groups, const TileHdr* hdrs, const uint16_t* staging, uint8_t* stream_out,
+                        uint64_t stream_cap, uint16_t* tile_bytes_out, uint64_t* run_offsets_out, vgc_group_hdr* hdrs_out,
+                        vgc_pack_status* status_out, hipStream_t stream);
+int launch_unpack_compact_batch(PlanCheck pc, const uint8_t* const* streams, const uint64_t* stream_bytes, const uint16_t* const* tile_bytes,
+                                const uint64_t* const* run_offsets, const vgc_group_hdr* const* hdrs, uint32_t p,
+                                const PlanGroup* groups, const PlanRun* runs, uint64_t n_runs, float scale, int overwrite,
+                                float* dense, hipStream_t stream);
 
 int launch_unpack_add(PlanCheck pc, const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
                       const PlanGroup* groups, uint32_t n_groups, float scale, float* dense,

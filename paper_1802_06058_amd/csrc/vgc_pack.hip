@@ -269,15 +269,23 @@ __global__ __launch_bounds__(256) void k_emit(PlanCheck pc, const PlanTile* __re
     }
 }
 
+int launch_pack_scans(PlanCheck pc, const uint32_t* flags, const PlanGroup* groups, const PlanSeg* segs, uint32_t n_groups,
+                      uint32_t n_segs, bool multi_seg, TileHdr* hdrs, SegTmp* stmp, vgc_group_hdr* hdrs_out,
+                      vgc_pack_status* status_out, uint64_t words_cap, hipStream_t stream) {
+    if (multi_seg) hipLaunchKernelGGL(k_seg_max, dim3(n_segs), dim3(1024), 0, stream, pc, groups, segs, hdrs, stmp);
+    hipLaunchKernelGGL(k_seg_scan, dim3(n_segs), dim3(1024), 0, stream, pc, groups, segs, hdrs, stmp);
+    hipLaunchKernelGGL(k_header_scan, dim3(1), dim3(1024), 0, stream, pc, flags, groups, stmp, n_groups, hdrs_out,
+                       status_out, words_cap);
+    return hip_check(hipGetLastError(), "launch pack scans");
+}
+
 int launch_pack(PlanCheck pc, const uint32_t* flags, const PlanGroup* groups, const PlanTile* tiles, const PlanSeg* segs, uint64_t n_tiles,
                 uint32_t n_groups, uint32_t n_segs, bool multi_seg,
                 TileHdr* hdrs, SegTmp* stmp, const uint16_t* staging,
                 uint32_t* words_out, uint64_t words_cap, vgc_group_hdr* hdrs_out,
                 vgc_pack_status* status_out, hipStream_t stream) {
-    if (multi_seg) hipLaunchKernelGGL(k_seg_max, dim3(n_segs), dim3(1024), 0, stream, pc, groups, segs, hdrs, stmp);
-    hipLaunchKernelGGL(k_seg_scan, dim3(n_segs), dim3(1024), 0, stream, pc, groups, segs, hdrs, stmp);
-    hipLaunchKernelGGL(k_header_scan, dim3(1), dim3(1024), 0, stream, pc, flags, groups, stmp, n_groups, hdrs_out,
-                       status_out, words_cap);
+    const int rc = launch_pack_scans(pc, flags, groups, segs, n_groups, n_segs, multi_seg, hdrs, stmp, hdrs_out, status_out, words_cap, stream);
+    if (rc != VGC_OK) return rc;
     const uint64_t blocks = (n_tiles + 3) / 4;
     hipLaunchKernelGGL(k_emit, dim3((uint32_t)blocks), dim3(256), 0, stream, pc, tiles, n_tiles, hdrs, staging,
                        stmp, words_out, words_cap);

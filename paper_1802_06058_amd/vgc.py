@@ -75,6 +75,12 @@ EXPORTS = {
                                                C.c_void_p, C.c_void_p, C.c_void_p]),
     "vgc_pack": (C.c_int, [C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
                            C.c_void_p, C.c_void_p, C.c_void_p]),
+    "vgc_run_count": (C.c_uint64, [C.c_void_p, C.c_uint32, C.c_uint64]),
+    "vgc_pack_compact": (C.c_int, [C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
+                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]),
+    "vgc_unpack_compact_add_batch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                               C.c_void_p, C.c_uint32, C.c_void_p, C.c_float, C.c_int, C.c_void_p,
+                                               C.c_uint64, C.c_void_p]),
     "vgc_unpack_add": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                  C.c_float, C.c_void_p, C.c_uint64, C.c_void_p]),
     "vgc_unpack_add_batch": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p, C.c_uint32,
@@ -144,6 +150,7 @@ class Plan:
         self.plan_host = host
         self.plan = host.to(device)
         self.n_tiles = int(lib.vgc_tile_count(arr, self.n_groups, self.n))
+        self.n_runs = int(lib.vgc_run_count(arr, self.n_groups, self.n))
         self.scratch_bytes = int(lib.vgc_scratch_bytes(arr, self.n_groups, self.n))
         self.bitmap_offset = int(lib.vgc_scratch_bitmap_offset(arr, self.n_groups, self.n))
         self.device = device
@@ -445,3 +452,44 @@ def unpack_apply(words, n_words, hdrs, plan, scale, param, state1, state2=None, 
     opt = Optimizer(kind, lr, momentum, beta1, beta2, eps, step)
     _check(load().vgc_unpack_apply(wp, nw, hp, p, plan.c_groups, plan.n_groups, _ptr(plan.plan), float(scale),
                                    C.byref(opt), _ptr(param), _ptr(state1), _ptr(state2), plan.n, _stream()))
+
+
+def pack_compact(plan, scratch, stream_out, tile_bytes, run_offsets, hdrs, status):
+    """vgc_pack_compact: the staged result of accumulate_select as a message with compressed indexes.
+    stream_out: uint8 tensor; tile_bytes: int16/uint16 tensor [n_tiles]; run_offsets: int64 tensor [n_runs]."""
+    a = _Args(plan.device)
+    a.on_device(plan.plan, "plan")
+    if stream_out.element_size() != 1:
+        raise VgcError(f"stream: need 8-bit elements, got {stream_out.dtype}")
+    a.need_bytes(stream_out, 0, "stream")
+    a.need_bytes(scratch, plan.scratch_bytes, "scratch")
+    a.need_bytes(tile_bytes, 2 * plan.n_tiles, "tile_bytes")
+    a.need_bytes(run_offsets, 8 * plan.n_runs, "run_offsets")
+    a.need_bytes(hdrs, plan.n_groups * C.sizeof(GroupHdr), "headers")
+    a.need_bytes(status, C.sizeof(PackStatus), "status")
+    a.launchable()
+    _check(load().vgc_pack_compact(plan.n, plan.c_groups, plan.n_groups, _ptr(plan.plan), _ptr(scratch), _ptr(stream_out),
+                                   stream_out.numel(), _ptr(tile_bytes), _ptr(run_offsets), _ptr(hdrs), _ptr(status), _stream()))
+
+
+def unpack_compact_add_batch(streams, stream_bytes, tile_bytes, run_offsets, hdrs, plan, scale, dense, overwrite=False):
+    """vgc_unpack_compact_add_batch: lists (one entry per message) of stream tensors, their lengths in bytes,
+    tile_bytes tensors, run_offsets tensors and header tensors."""
+    p = len(streams)
+    if not (len(stream_bytes) == len(tile_bytes) == len(run_offsets) == len(hdrs) == p):
+        raise VgcError("streams, stream_bytes, tile_bytes, run_offsets and hdrs must have one entry per message")
+    a = _Args(plan.device)
+    for s, nb, tb, ro, h in zip(streams, stream_bytes, tile_bytes, run_offsets, hdrs):
+        if s.element_size() != 1:
+            raise VgcError(f"stream: need 8-bit elements, got {s.dtype}")
+        a.need_bytes(s, int(nb), "stream")
+        a.need_bytes(tb, 2 * plan.n_tiles, "tile_bytes")
+        a.need_bytes(ro, 8 * plan.n_runs, "run_offsets")
+        a.need_bytes(h, plan.n_groups * C.sizeof(GroupHdr), "headers")
+    a.need_state(plan, dense=dense)
+    a.launchable()
+    arr = lambda ts: (C.c_void_p * max(p, 1))(*[t.data_ptr() for t in ts])
+    nb = (C.c_uint64 * max(p, 1))(*[int(x) for x in stream_bytes])
+    _check(load().vgc_unpack_compact_add_batch(arr(streams), nb, arr(tile_bytes), arr(run_offsets), arr(hdrs), p, plan.c_groups,
+                                               plan.n_groups, _ptr(plan.plan), float(scale), 1 if overwrite else 0, _ptr(dense),
+                                               plan.n, _stream()))
