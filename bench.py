@@ -164,6 +164,9 @@ def main():
         print(json.dumps(out))
         return
 
+    # the compressed index format on worker 0's next message (steady state: its state after the timed steps)
+    out["stages"]["compressed_indexes"] = bench_compact(vgc, plan, pool, r[0], v[0], a.alpha, zeta, scratch, words, hdrs, status, dense, N, P, scale)
+
     # hybrid algorithm (Alg. 2) on worker 0's buffers: same kernels with the threshold rule, tau = 0.05
     r[0].zero_(); v[0].zero_()
     hy_ms, hy_words = [], []
@@ -189,7 +192,6 @@ def main():
     # the sparse regime, one worker of the flat workload on a fresh state
     out["stages"]["sparse_regime_fresh_state"] = alpha_sweep(vgc, plan, pool[0][0], pool[0][1], r[0], v[0], zeta, scratch,
                                                              words[0], hdrs[0], status[0], (8.0, 16.0), dense=dense)
-    out["stages"]["compressed_indexes"] = bench_compact(vgc, plan, pool, r[0], v[0], a.alpha, zeta, scratch, words, hdrs, status, dense, N, P, scale)
     out["stages"]["model_parameter_sets"] = bench_model_sets(dev, a.alpha, zeta)
     out["stages"]["fused_fc_statistic_select"] = bench_fused_fc(dev, zeta)
     if not a.no_sqgrad:
