@@ -297,7 +297,11 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     // loads of its last kNB - 2 requests are back, its pieces of the chunk needed next are in LDS.  The trip
     // count of the pipelined loop is rounded up to a multiple of its unroll factor; the surplus chunks are
     // all zeros and add nothing.
-    constexpr int kInFlight = (kNB - 2) * kPer;
+    //
+    // Without g the loop is pipelined across the barrier (below) and refills a buffer one chunk after it was
+    // consumed: kNB - 1 chunks are requested up front and chunk q + kNB - 1 goes into chunk q - 1's buffer.
+    constexpr int kAhead = kWantG ? kNB : kNB - 1;       // requests ahead of the chunk being consumed
+    constexpr int kInFlight = (kAhead - 2) * kPer;
     constexpr uint32_t kNever = 0x3FFFFFFFu;
     // chunks until: the requests reach the end of a sample, the last request, the consumed sample is complete
     uint32_t to_wrap = __builtin_amdgcn_readfirstlane(n_chunks - c_begin);
@@ -305,7 +309,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     {
         uint32_t bo = 0;
 #pragma unroll 1
-        for (int i = 0; i < kNB; ++i) {
+        for (int i = 0; i < kAhead; ++i) {
             issue(bo);
             bo = next_buf(bo);
             if (--to_wrap == 0) { to_wrap = n_chunks; wrap(); }
@@ -325,54 +329,73 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             span = ev = min(left, min(to_wrap, todo));
         }
     };
-    wait_loads_but<kInFlight>();                         // chunks 0 and 1 have landed
-    __syncthreads();
     uint32_t bo_cur = 0;                                 // buffer of the chunk being consumed
     if constexpr (!kWantG) {
-        // Pipelined across the barrier: the operand fragments of chunk q+1 are read from LDS while the
-        // MFMAs of chunk q run from registers.
-        bf8v F[2][2][2][2];                              // [ping-pong][k-step][A / B][32-wide tile]
+        // One k-step (16 positions: one MFMA per 32 x 32 tile) is a phase.  While the MFMAs of a phase run, the
+        // operand fragments of the next phase are read from LDS: the A fragments into the other of two register
+        // sets, a B fragment into the registers of the one it replaces as soon as the two MFMAs that use it are
+        // issued (MFMA order: B-major).  The workgroup meets once per chunk, between the two phases of chunk q:
+        // by then every wave has its pieces of chunk q + 1 in LDS (it waits for its own loads before the barrier)
+        // and has issued every MFMA of chunk q - 1, so has received every fragment of that chunk: its buffer is
+        // free for the next request.  No wave waits for LDS reads still in flight at the barrier.
+        wait_loads_but<kInFlight + kPer>();              // chunk 0 has landed (this wave's pieces)
+        __syncthreads();
+        bf8v FA[2][2], FB[2];
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
+        for (int t = 0; t < 2; ++t) {
+            FA[0][t] = frag_a(0, 0, t);
+            FB[t] = frag_b(0, 0, t);
+        }
+        uint32_t bo_prev = (kNB - 1) * kBufBytes;
+        for (uint32_t q = 0; q < total; ++q) {
+            const uint32_t bo_next = next_buf(bo_cur);
+            // phase 0: k-step 0 of chunk q; fragments of its k-step 1
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                F[0][ks][0][t] = frag_a(0, ks, t);
-                F[0][ks][1][t] = frag_b(0, ks, t);
+            for (int nt = 0; nt < 2; ++nt) {
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[0][mt], FB[nt], acc[mt][nt], 0, 0, 0);
+                    if (nt == 0) FA[1][mt] = frag_a(bo_cur, 1, mt);
+                }
+                FB[nt] = frag_b(bo_cur, 1, nt);
             }
-        __syncthreads();                                 // buffer 0 is free
-        // A wave issues in order, and the two waves of a SIMD run in lockstep between barriers: if the
-        // MFMAs sat in one block and the LDS traffic in another, the matrix pipe would idle during the
-        // LDS phase and vice versa.  So the instruction stream is interleaved by hand: after every MFMA
-        // one operand fragment (two transposing reads) of the next chunk is requested, and the request
-        // for chunk q+kNB goes in the middle of the MFMA sequence.
-        for (uint32_t q0 = 0; q0 < total; q0 += 2) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // MFMA, A', MFMA, A' B', MFMA, MFMA, B'
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            wait_loads_but<kInFlight>();                 // chunk q + 1 has landed (this wave's pieces)
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            // phase 1: k-step 1 of chunk q; fragments of k-step 0 of chunk q + 1; the request for chunk
+            // q + kNB - 1, spread over the phase
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {                // chunk q = q0 + u lives in fragment set u
-                const uint32_t bo_next = next_buf(bo_cur);
+            for (int nt = 0; nt < 2; ++nt) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {            // MFMA i = (ks, mt, nt); fragment i = (ks, A/B, t) of chunk q+1
-                    const int ks = i >> 2, mt = (i >> 1) & 1, nt = i & 1;
-                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(F[u][ks][0][mt], F[u][ks][1][nt], acc[mt][nt], 0, 0, 0);
-                    const int fk = i >> 2, fo = (i >> 1) & 1, ft = i & 1;
-                    if (fo == 0) F[u ^ 1][fk][0][ft] = frag_a(bo_next, fk, ft);
-                    else F[u ^ 1][fk][1][ft] = frag_b(bo_next, fk, ft);
-                    // chunk q + kNB into chunk q's buffer, its loads spread over MFMAs 1 .. 6 (all at once costs 1-3 %)
+                for (int mt = 0; mt < 2; ++mt) {
+                    acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[1][mt], FB[nt], acc[mt][nt], 0, 0, 0);
+                    if (nt == 0) FA[0][mt] = frag_a(bo_next, 0, mt);
+                    const int i = nt * 2 + mt;
 #pragma unroll
                     for (int n = 0; n < kPer; ++n)
-                        if (i == 1 + (n * 6) / kPer) issue_one(bo_cur, n);
+                        if (i == (n * 4) / kPer) issue_one(bo_prev, n);
                 }
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {            // pin the order above for the instruction scheduler
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // one MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);      // two LDS reads
-                }
-                bo_cur = bo_next;
-                tick();
-                wait_loads_but<kInFlight>();             // chunk q+2 has landed (this wave's pieces)
-                __syncthreads();
+                FB[nt] = frag_b(bo_next, 0, nt);
             }
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            bo_prev = bo_cur;
+            bo_cur = bo_next;
+            tick();
         }
     } else {
+        wait_loads_but<kInFlight>();                     // chunks 0 and 1 have landed
+        __syncthreads();
         for (uint32_t q = 0; q < total; ++q) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
