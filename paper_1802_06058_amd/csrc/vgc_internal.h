@@ -205,6 +205,7 @@ size_t sqgrad_workspace_bytes(int kind, int dtype, uint32_t B, uint32_t P, uint3
 struct ConvGeom {
     uint32_t H, W, Cin, kw, sh, sw, ph, pw, Ho, Wo;
     uint32_t step_y, step_x; // one chunk of kKC positions further: kKC = step_y * Wo + step_x
+    uint32_t period;         // bf16 kernel, unit strides and Wo = W: chunks after which the column pattern repeats (0: general path)
 };
 
 bool conv2d_supported(int dtype, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t P);

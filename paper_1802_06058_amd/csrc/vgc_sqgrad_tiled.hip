@@ -92,8 +92,12 @@ struct SampleWindow {
 };
 
 // BM x BN block tile of [J, C]; one wave per 64 x 64 sub-tile.  kImplicit: U is the layer's NHWC input seen
-// through the geometry G (J = kh kw Cin), otherwise a [B, P, J] matrix.
-template <int BM, int BN, bool kWantG, bool kImplicit>
+// through the geometry G (J = kh kw Cin), otherwise a [B, P, J] matrix.  kLinear (with kImplicit): unit strides
+// and an output as wide as the input (G.period > 0), where the input element of output position p and tap
+// (ky, kx) is element p + (ky - ph) W + kx - pw of the sample: the lane's offset moves by a constant per chunk and
+// what is left of the geometry is whether column x + kx - pw lies inside the row, which repeats every G.period
+// chunks (x advances by kKC mod W per chunk) and is kept as one bit per chunk of the period.
+template <int BM, int BN, bool kWantG, bool kImplicit, bool kLinear = false>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
 void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                  uint32_t B, uint32_t P, uint32_t J, uint32_t C,
@@ -151,6 +155,9 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     uint32_t voffA[kPerA], voffB[kPerB];
     uint32_t xsA[kPerA], yA[kPerA], xs0A[kPerA], y0A[kPerA];    // implicit: x sw and y of the lane's row; the same in a sample's first chunk
     int32_t obA[kPerA], ob0A[kPerA], tapX[kPerA];               // implicit: byte offset of the tap's element; kx - pw
+    uint32_t outA[kPerA];                                       // linear: bit k set = column outside the row in chunk k of the period
+    uint32_t kph = __builtin_amdgcn_readfirstlane(kLinear ? c_begin % G.period : 0u);   // chunk of the period requested next
+    const int32_t dLin = (int32_t)(kKC * G.Cin * 2u);
     const uint32_t sxw = G.step_x * G.sw, WoSw = G.Wo * G.sw;
     const int32_t dO = (int32_t)((G.step_y * G.sh * G.W + sxw) * G.Cin * 2u);            // offset change per chunk, no carry
     const int32_t dOC = dO + (int32_t)(G.sh * G.W - WoSw) * (int32_t)(G.Cin * 2u);       // ... with a carry into y
@@ -168,9 +175,22 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             tapX[j] = (int32_t)(tap - ky * G.kw) - (int32_t)G.pw;
             const int32_t tapY = (int32_t)ky - (int32_t)G.ph;
             const int32_t tapOff = (tapY * (int32_t)G.W + tapX[j]) * (int32_t)G.Cin + (int32_t)(col - tap * G.Cin);
-            xs0A[j] = xsA[j] = x0 * G.sw;
-            y0A[j] = yA[j] = y0;
-            ob0A[j] = obA[j] = ((int32_t)((y0 * G.sh * G.W + x0 * G.sw) * G.Cin) + tapOff) * 2;
+            if (kLinear) {
+                ob0A[j] = ((int32_t)(row * G.Cin) + tapOff) * 2;
+                obA[j] = ob0A[j] + (int32_t)(c_begin * kKC * G.Cin * 2u);
+                uint32_t x = row % G.W, bits = 0;
+                const uint32_t sx = kKC % G.W;
+                for (uint32_t k = 0; k < G.period; ++k) {           // chunk k of the period: is the column outside?
+                    bits |= ((uint32_t)((int32_t)x + tapX[j]) < G.W ? 0u : 1u) << k;
+                    x += sx;
+                    x = min(x, x - G.W);
+                }
+                outA[j] = bits;
+            } else {
+                xs0A[j] = xsA[j] = x0 * G.sw;
+                y0A[j] = yA[j] = y0;
+                ob0A[j] = obA[j] = ((int32_t)((y0 * G.sh * G.W + x0 * G.sw) * G.Cin) + tapOff) * 2;
+            }
         } else {
             voffA[j] = (row * J + j0 + piece * 8u) * 2u + c_begin * strideA;
         }
@@ -237,7 +257,11 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
         if (n < kPerA) {
             const int j = n;
             uint32_t voff;
-            if (kImplicit) {
+            if (kLinear) {
+                // (a position past P aliases into a valid element, but the rows of D past P read as zeros)
+                voff = (uint32_t)(obA[j] | __builtin_amdgcn_sbfe((int32_t)outA[j], kph, 1u));
+                obA[j] += dLin;
+            } else if (kImplicit) {
                 // Rows of the input above or below the image need no test: their offset is negative or past the
                 // sample's range, which the buffer load answers with zeros; a column outside would alias into the
                 // neighbouring row, and a position past P into a valid one, so those two are masked.
@@ -259,17 +283,23 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             voffB[j] += strideB;
         }
     };
+    auto request_done = [&]() {                          // after the last load of a request
+        if (kLinear) kph = (kph + 1u == G.period) ? 0u : kph + 1u;
+    };
     auto issue = [&](uint32_t bo) {                      // the whole request
 #pragma unroll
         for (int n = 0; n < kPer; ++n) issue_one(bo, n);
+        request_done();
     };
     // The rare steps, kept out of the per-chunk code: the requests cross into the next sample ...
     auto wrap = [&]() {
         wa.next_sample();
         wb.next_sample();
+        kph = 0u;
 #pragma unroll
         for (int j = 0; j < kPerA; ++j) {
-            if (kImplicit) { xsA[j] = xs0A[j]; yA[j] = y0A[j]; obA[j] = ob0A[j]; }
+            if (kLinear) obA[j] = ob0A[j];
+            else if (kImplicit) { xsA[j] = xs0A[j]; yA[j] = y0A[j]; obA[j] = ob0A[j]; }
             else voffA[j] -= n_chunks * strideA;
         }
 #pragma unroll
@@ -389,6 +419,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            request_done();
             bo_prev = bo_cur;
             bo_cur = bo_next;
             tick();
@@ -634,17 +665,17 @@ void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg,
                            g_out, s_out, lanes);
 }
 
-template <int BM, int BN, bool kImplicit>
+template <int BM, int BN, bool kImplicit, bool kLinear = false>
 static void launch_conv_bf16(uint32_t nblk, hipStream_t stream, const void* X, const void* D, uint32_t B, uint32_t P,
                              uint32_t J, uint32_t C, uint32_t splits, uint32_t split_p, float cg, float cs,
                              float* g_out, float* s_out, float* ws, const ConvGeom& G) {
     constexpr int NT = (BM / 64) * (BN / 64) * 64;
     // with the positions split the partial products are unsquared: the variant without g serves both
     if (g_out && split_p == 1)
-        hipLaunchKernelGGL((k_conv_bf16<BM, BN, true, kImplicit>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
+        hipLaunchKernelGGL((k_conv_bf16<BM, BN, true, kImplicit, kLinear>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
                            (const uint16_t*)D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
     else
-        hipLaunchKernelGGL((k_conv_bf16<BM, BN, false, kImplicit>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
+        hipLaunchKernelGGL((k_conv_bf16<BM, BN, false, kImplicit, kLinear>), dim3(nblk), dim3(NT), 0, stream, (const uint16_t*)X,
                            (const uint16_t*)D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
 }
 
@@ -662,10 +693,20 @@ static int launch_conv_any(const void* X, const void* D, uint32_t B, uint32_t P,
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     const float cg = c, cs = c * c;
     float* ws = static_cast<float*>(workspace);
-    if (t.bm == 256 && t.bn == 128) launch_conv_bf16<256, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
-    else if (t.bm == 256 && t.bn == 64) launch_conv_bf16<256, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
-    else if (t.bm == 128 && t.bn == 128) launch_conv_bf16<128, 128, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
-    else launch_conv_bf16<128, 64, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);
+#define VGC_LAUNCH_BF16(BM_, BN_)                                                                                          \
+    do {                                                                                                                   \
+        if (kImplicit && G.period > 0)                                                                                     \
+            launch_conv_bf16<BM_, BN_, kImplicit, kImplicit>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, \
+                                                             cs, g_out, s_out, ws, G);                                     \
+        else                                                                                                               \
+            launch_conv_bf16<BM_, BN_, kImplicit, false>((uint32_t)nblk, stream, X, D, B, P, J, C, splits, split_p, cg, cs, \
+                                                         g_out, s_out, ws, G);                                             \
+    } while (0)
+    if (t.bm == 256 && t.bn == 128) VGC_LAUNCH_BF16(256, 128);
+    else if (t.bm == 256 && t.bn == 64) VGC_LAUNCH_BF16(256, 64);
+    else if (t.bm == 128 && t.bn == 128) VGC_LAUNCH_BF16(128, 128);
+    else VGC_LAUNCH_BF16(128, 64);
+#undef VGC_LAUNCH_BF16
     if (split_p > 1) {
         launch_sqgrad_reduce_parts(ws, B, split_p, JC, cg, cs, g_out, s_out, stream);
         return hip_check(hipGetLastError(), "launch k_conv_bf16");
@@ -694,11 +735,19 @@ bool conv2d_supported(int dtype, uint32_t H, uint32_t W, uint32_t Cin, uint32_t 
 int launch_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
                   uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw, uint32_t Ho, uint32_t Wo,
                   float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
-    ConvGeom G;
+    ConvGeom G{};
     G.H = H; G.W = W; G.Cin = Cin; G.kw = kw; G.sh = sh; G.sw = sw; G.ph = ph; G.pw = pw; G.Ho = Ho; G.Wo = Wo;
     if (dtype == VGC_F32) return launch_conv2d_f32(act, D, B, Ho * Wo, kh * kw * Cin, C, c, g_out, s_out, workspace, workspace_bytes, G, stream);
     G.step_y = kKC / Wo;
     G.step_x = kKC % Wo;
+    // unit strides and an output as wide as the input: offsets are linear in the output position and the column
+    // test repeats every W / gcd(W, kKC) chunks; the kernel keeps it in a 32-bit mask
+    G.period = 0;
+    if (sh == 1 && sw == 1 && Wo == W) {
+        uint32_t a = W, b = kKC % W;
+        while (b) { const uint32_t t = a % b; a = b; b = t; }
+        if (W / a <= 32) G.period = W / a;
+    }
     return launch_conv_any<true>(act, D, B, Ho * Wo, kh * kw * Cin, C, c, g_out, s_out, workspace, workspace_bytes, G, stream);
 }
 

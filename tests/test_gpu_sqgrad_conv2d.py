@@ -78,6 +78,9 @@ GEOMS = [  # B, H, W, Cin, C, kh, kw, stride, pad
     (6, 23, 31, 32, 24, 4, 2, (3, 3), (0, 0)),     # stride larger than the kernel's width: input columns skipped
     (1, 73, 72, 32, 32, 5, 4, (1, 2), (0, 0)),     # one sample, 2415 positions
     (2, 40, 37, 16, 16, 3, 3, (1, 1), (1, 1)),     # two samples, positions split
+    (4, 12, 25, 16, 24, 3, 3, (1, 1), (0, 1)),     # unit strides, output as wide as the input but less high; column pattern of period 25
+    (3, 10, 20, 8, 16, 1, 3, (1, 1), (0, 1)),      # one kernel row, period 5
+    (2, 30, 96, 8, 8, 3, 3, (1, 1), (1, 1)),       # width a multiple of the chunk: period 3, positions split
 ]
 
 OBSERVED = {}
