@@ -359,7 +359,6 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             span = ev = min(left, min(to_wrap, todo));
         }
     };
-    uint32_t bo_cur = 0;                                 // buffer of the chunk being consumed
     if constexpr (!kWantG) {
         // One k-step (16 positions: one MFMA per 32 x 32 tile) is a phase.  While the MFMAs of a phase run, the
         // operand fragments of the next phase are read from LDS: the A fragments into the other of two register
@@ -376,9 +375,14 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             FA[0][t] = frag_a(0, 0, t);
             FB[t] = frag_b(0, 0, t);
         }
-        uint32_t bo_prev = (kNB - 1) * kBufBytes;
-        for (uint32_t q = 0; q < total; ++q) {
-            const uint32_t bo_next = next_buf(bo_cur);
+        // The ring is unrolled: the loop body exists once per buffer, so that buffer offsets are constants and LDS
+        // addresses are a lane's fragment offset plus an immediate.
+        for (uint32_t q0 = 0; q0 < total; q0 += kNB) {
+#pragma unroll
+            for (int b = 0; b < kNB; ++b) {
+            if (q0 + (uint32_t)b >= total) break;
+            const uint32_t bo_cur = (uint32_t)b * kBufBytes, bo_next = (uint32_t)((b + 1) % kNB) * kBufBytes;
+            const uint32_t bo_prev = (uint32_t)((b + kNB - 1) % kNB) * kBufBytes;
             // phase 0: k-step 0 of chunk q; fragments of its k-step 1
 #pragma unroll
             for (int nt = 0; nt < 2; ++nt) {
@@ -420,13 +424,13 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
             request_done();
-            bo_prev = bo_cur;
-            bo_cur = bo_next;
             tick();
+            }
         }
     } else {
         wait_loads_but<kInFlight>();                     // chunks 0 and 1 have landed
         __syncthreads();
+        uint32_t bo_cur = 0;                             // buffer of the chunk being consumed
         for (uint32_t q = 0; q < total; ++q) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
