@@ -309,6 +309,9 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
     auto close = [&]() { wa.close(); wb.close(); };
     // ... and the per-sample product G_z is complete in acc: square into s, add into g, clear.
     auto sample_end = [&]() {
+        // acc is cleared by the matrix pipe (a product of zero operands onto a zero constant) rather than by 16 moves
+        // per tile: while one wave of a SIMD squares, the other one's clearing MFMAs run beside it
+        const bf8v zf = {0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
@@ -319,7 +322,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                     s_acc[mt][nt][i] = __builtin_fmaf(x, x, s_acc[mt][nt][i]);
                     if (kWantG) g_acc[mt][nt][i] += x;
                 }
-                acc[mt][nt] = (f16v){0};
+                acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf, zf, (f16v){0}, 0, 0, 0);
             }
     };
     // Ring: chunk c lives in buffer c % kNB; kNB chunks are requested up front and one more per iteration,
