@@ -478,9 +478,12 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                     const size_t o = (size_t)row * C + col;
                     if (split_p > 1) {
                         __builtin_nontemporal_store(acc[mt][nt][i], so + o);
-                    } else {
+                    } else if (direct) {
                         __builtin_nontemporal_store(fs * s_acc[mt][nt][i], so + o);
                         if (kWantG) __builtin_nontemporal_store(fg * g_acc[mt][nt][i], go + o);
+                    } else {                             // read again at once by the reduction: leave it in the caches
+                        so[o] = s_acc[mt][nt][i];
+                        if (kWantG) go[o] = g_acc[mt][nt][i];
                     }
                 }
             }
