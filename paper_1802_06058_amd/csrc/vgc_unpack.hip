@@ -124,6 +124,11 @@ __global__ __launch_bounds__(256) void k_unpack_add_batch(PlanCheck pc, BatchArg
     // wave-wide word loads in flight per message: eight where the words are most of what the wave waits for, four
     // where the optimizer's arrays are in flight as well (there the words loaded past the tile's end cost more)
     constexpr int kRounds = kMode == kToDense ? 8 : 4;
+    // A message's words of a tile are requested before their number is known.  The first request of a tile is sized
+    // from the message's density in the group (mean + 3 standard deviations of a tile's count if the sent elements
+    // were spread evenly, at most kFirst x 64 words); if the tile holds more, requests of kRounds x 64 follow.  Words
+    // requested past the tile's end are requested again with the next tile: they are what this sizing keeps small.
+    constexpr int kFirst = 16;
     __shared__ __attribute__((aligned(16))) float sh_tile[4][kTile];
     const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
     // a run of kRunTiles tiles is shared by kRunTiles / tiles_per_wave waves (small parameter sets have few runs)
@@ -142,9 +147,11 @@ __global__ __launch_bounds__(256) void k_unpack_add_batch(PlanCheck pc, BatchArg
 
     // per message (lane w < p): segment of group k and the cursor = first word with index >= run start
     uint64_t cur = 0, seg_end = 0;
-    uint32_t expf = 0;
+    uint32_t expf = 0, first_rounds = 1;
     if (lane < A.p) {
         const vgc_group_hdr h = A.hdrs[lane][k];
+        const float mu = (float)h.count * ((float)kTile / (float)pg.size);
+        first_rounds = min((uint32_t)kFirst, (uint32_t)((mu + 3.0f * sqrtf(mu)) * (1.0f / 64.0f)) + 1u);
         uint64_t lo = h.word_offset, hi = h.word_offset + h.count;
         if (hi > A.n_words[lane]) hi = A.n_words[lane];
         if (lo > hi) lo = hi;
@@ -202,6 +209,38 @@ __global__ __launch_bounds__(256) void k_unpack_add_batch(PlanCheck pc, BatchArg
             const uint64_t se = shfl64(seg_end, (int)w);
             const uint32_t ef = (uint32_t)__shfl((int)expf, (int)w);
             const uint32_t* W = A.words[w];
+            {                                                // first request: first_rounds x 64 words
+                const uint32_t fr = (uint32_t)__shfl((int)first_rounds, (int)w);
+                uint32_t wd[kFirst];
+#pragma unroll
+                for (int j = 0; j < kFirst; ++j) {
+                    const uint64_t i = c + (uint32_t)j * 64u + lane;
+                    wd[j] = ((uint32_t)j < fr && i < se) ? __builtin_nontemporal_load(W + i) : 0xFFFFFFFFu;
+                }
+                uint32_t used = 0;
+#pragma unroll
+                for (int j = 0; j < kFirst; ++j) {
+                    if ((uint32_t)j < fr) {
+                        const uint64_t i = c + (uint32_t)j * 64u + lane;
+                        const uint32_t idx = wd[j] & 0x0FFFFFFFu;
+                        const uint32_t d = (wd[j] >> 28) & 7u;
+                        const bool in_tile = (i < se) && (idx < tile_end);
+                        if (in_tile && idx >= start && ef > d && ef <= 254u) {
+                            const float val = __uint_as_float(((ef - d) << 23) | (wd[j] & 0x80000000u));
+                            const float contrib = scale * val;
+                            T[idx - start] = T[idx - start] + contrib;
+                        }
+                        used += (uint32_t)__popcll(__ballot(in_tile));
+                    }
+                }
+                c += used;
+                if (used != fr * 64u) {                      // the tile's words ended inside the request
+                    if (lane == w) cur = c;
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    continue;
+                }
+            }
             bool more = true;
             while (more) {
                 uint32_t wd[kRounds];
