@@ -136,6 +136,7 @@ def main():
     sp_gbs = (24.0 + 4.0 * rho) * N / ((sel + pk) * 1e-3) / 1e9
     dec_gbs = 12.0 * rho * N * P / (dec * 1e-3) / 1e9
 
+    traffic, traffic_source = measured_traffic(N)
     out = {
         "metric": "compressed params/sec", "value": round(value, 3), "unit": "Gparams/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(ms_per_step, 3),
@@ -146,7 +147,8 @@ def main():
                    "n_groups": len(groups), "tile": vgc.tile_size(), "sent_fraction": round(rho, 5)},
         "roofline": {"bound": "hbm", "kernel": "k_accumulate_select", "achieved": round(sel_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(sel_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic(N), "algorithmic_bytes_per_launch": 24.0 * N, "avg_launch_ms": round(sel, 4),
+                     "traffic": traffic, "traffic_source": traffic_source,
+                     "algorithmic_bytes_per_launch": 24.0 * N, "avg_launch_ms": round(sel, 4),
                      "median_launch_ms": round(float(np.median(sel_ms)), 4), "min_launch_ms": round(float(np.min(sel_ms)), 4),
                      "launches": len(sel_ms)},
         "stages": {
@@ -278,15 +280,18 @@ def bench_update(vgc, plan, words, hdrs, status, param, N, P, scale):
 
 
 def measured_traffic(N):
-    """HBM bytes per k_accumulate_select launch from the committed counter runs (profiles/), which were
-    taken at N = 1e9 and a sent fraction of about 0.2; None for any other size."""
+    """(HBM bytes per k_accumulate_select launch, where the figure comes from) from the committed counter runs
+    (profiles/), which were taken at N = 1e9 and a sent fraction of about 0.2; (None, None) for any other size."""
     path = os.path.join(ROOT, "profiles", "traffic_c5_microbench_pmc.txt")
     if N != 1_000_000_000 or not os.path.exists(path):
-        return None
+        return None, None
+    traffic, taken = None, None
     for line in open(path):
+        if line.startswith("# taken:"):
+            taken = line.split(":", 1)[1].strip()
         if line.startswith("k_accumulate_select_traffic_bytes_per_launch_n1e9:"):
-            return float(line.split(":")[1])
-    return None
+            traffic = float(line.split(":")[1])
+    return traffic, {"file": "profiles/traffic_c5_microbench_pmc.txt", "taken": taken}
 
 
 def bench_model_sets(dev, alpha, zeta):
