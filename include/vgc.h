@@ -175,6 +175,33 @@ int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uin
                       uint32_t pad_h, uint32_t pad_w, float c, float* g_out, float* s_out,
                       void* workspace, size_t workspace_bytes, void* stream);
 
+/* The statistic of several convolution layers in one call.  The layers of a model are independent of each other
+ * (Alg. 1 runs per parameter; a layer is one weight tensor, Section 4.2) and most of them are too small to fill the
+ * chip alone, so the kernels of the small layers (below 2e10 multiply-adds) are spread over four streams of the
+ * library's own, between a fork after what the caller's stream holds so far and a join back into it, while the large
+ * ones run on the caller's stream: kernels of different layers fill each other's tails.  Every result is that of
+ * vgc_sqgrad_conv2d on the same layer, bit for bit.
+ *
+ * layers: HOST array; the fields are the arguments of vgc_sqgrad_conv2d.  The layers run side by side, so each needs
+ * outputs and a workspace of its own.  Every layer is checked before anything is launched; on an argument error
+ * nothing is launched.  The side streams (default priority) and their events are created at the first call on a
+ * device and kept; calls from several host threads are serialised while they submit.  Not for use under stream
+ * capture on hosts where the first call has not been made yet (it creates streams).
+ */
+typedef struct {
+    int dtype;
+    const void* act;
+    const void* D;
+    uint32_t B, H, W, Cin, C, kh, kw, stride_h, stride_w, pad_h, pad_w;
+    float c;
+    float* g_out;          /* nullable */
+    float* s_out;
+    void* workspace;       /* nullable */
+    size_t workspace_bytes;
+} vgc_conv2d_layer;
+
+int vgc_sqgrad_conv2d_batch(const vgc_conv2d_layer* layers, uint32_t n_layers, void* stream);
+
 /* ---- (b) accumulate, test, reset or decay ---------------------------------------------------
  * The body of Alg. 1's parameter loop with the criterion of Eq. 2 and the decay of Section 4.4,
  * for all n parameters in one launch, in float32 with one rounding per operation:

@@ -262,12 +262,12 @@ size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint
     return conv_f32_workspace_bytes(B, Ho * Wo, J, C);
 }
 
-int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin,
-                      uint32_t C, uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw,
-                      float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, void* stream) {
+// Argument checks of vgc_sqgrad_conv2d; the output size on success.
+static int conv2d_check(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin,
+                        uint32_t C, uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw,
+                        float c, const float* g_out, const float* s_out, const void* workspace, uint32_t* Ho, uint32_t* Wo) {
     if (!act || !D || !s_out) { set_error("vgc_sqgrad_conv2d: act, D and s_out are required"); return VGC_ERR_NULL; }
-    uint32_t Ho, Wo;
-    int rc = conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, &Ho, &Wo);
+    int rc = conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, Ho, Wo);
     if (rc != VGC_OK) return rc;
     if (!aligned(act, 16) || !aligned(D, 16) || !aligned(s_out, 16) || (g_out && !aligned(g_out, 16)) ||
         (workspace && !aligned(workspace, 16))) {
@@ -275,8 +275,103 @@ int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uin
         return VGC_ERR_ALIGN;
     }
     if (!std::isfinite(c)) { set_error("vgc_sqgrad_conv2d: c is not finite"); return VGC_ERR_PARAM; }
+    return VGC_OK;
+}
+
+int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin,
+                      uint32_t C, uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw,
+                      float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, void* stream) {
+    uint32_t Ho, Wo;
+    const int rc = conv2d_check(dtype, act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, c, g_out, s_out, workspace, &Ho, &Wo);
+    if (rc != VGC_OK) return rc;
     return launch_conv2d(dtype, act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, Ho, Wo, c, g_out, s_out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
+}
+
+// The library's own streams for vgc_sqgrad_conv2d_batch: one set per device, made on first use (default priority).
+namespace {
+constexpr int kSideStreams = 4;
+struct SideStreams {
+    bool ready = false;
+    hipStream_t s[kSideStreams];
+    hipEvent_t fork, join[kSideStreams];
+};
+std::mutex g_side_mutex;                                  // one batch call submits at a time per process
+SideStreams g_side[64];
+}  // namespace
+
+int vgc_sqgrad_conv2d_batch(const vgc_conv2d_layer* layers, uint32_t n_layers, void* stream) {
+    if (!layers && n_layers) { set_error("vgc_sqgrad_conv2d_batch: layers is NULL"); return VGC_ERR_NULL; }
+    std::vector<uint32_t> Ho(n_layers), Wo(n_layers);
+    for (uint32_t k = 0; k < n_layers; ++k) {             // every layer is checked before anything is launched
+        const vgc_conv2d_layer& L = layers[k];
+        const int rc = conv2d_check(L.dtype, L.act, L.D, L.B, L.H, L.W, L.Cin, L.C, L.kh, L.kw, L.stride_h, L.stride_w, L.pad_h,
+                                    L.pad_w, L.c, L.g_out, L.s_out, L.workspace, &Ho[k], &Wo[k]);
+        if (rc != VGC_OK) return rc;
+    }
+    hipStream_t user = static_cast<hipStream_t>(stream);
+    int dev = 0;
+    int rc = hip_check(hipGetDevice(&dev), "hipGetDevice");
+    if (rc != VGC_OK) return rc;
+    if (dev < 0 || dev >= 64) { set_error("vgc_sqgrad_conv2d_batch: device %d out of range", dev); return VGC_ERR_PARAM; }
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    SideStreams& S = g_side[dev];
+    if (!S.ready) {
+        for (int i = 0; i < kSideStreams; ++i) {
+            if ((rc = hip_check(hipStreamCreateWithFlags(&S.s[i], hipStreamNonBlocking), "hipStreamCreate")) != VGC_OK) return rc;
+            if ((rc = hip_check(hipEventCreateWithFlags(&S.join[i], hipEventDisableTiming), "hipEventCreate")) != VGC_OK) return rc;
+        }
+        if ((rc = hip_check(hipEventCreateWithFlags(&S.fork, hipEventDisableTiming), "hipEventCreate")) != VGC_OK) return rc;
+        S.ready = true;
+    }
+    // Which stream takes which layer.  A layer of 2e10 multiply-adds or more fills the chip by itself (measured:
+    // overlapping such layers costs time); it stays on the caller's stream.  Of the others each goes to the least
+    // loaded side stream.
+    std::vector<int> lane_of(n_layers, 0);
+    double load[kSideStreams + 1] = {0.0};               // multiply-adds queued on each stream so far
+    bool lane_used[kSideStreams + 1] = {false};
+    uint32_t n_small = 0;
+    for (uint32_t k = 0; k < n_layers; ++k) {
+        const vgc_conv2d_layer& L = layers[k];
+        const double macs = (double)L.B * Ho[k] * Wo[k] * L.kh * L.kw * L.Cin * L.C;
+        if (macs < 2e10) ++n_small;
+    }
+    for (uint32_t k = 0; k < n_layers; ++k) {
+        const vgc_conv2d_layer& L = layers[k];
+        const double macs = (double)L.B * Ho[k] * Wo[k] * L.kh * L.kw * L.Cin * L.C;
+        int lane = 0;
+        if (n_small > 1 && macs < 2e10) {
+            lane = 1;
+            for (int i = 2; i <= kSideStreams; ++i)
+                if (load[i] < load[lane]) lane = i;
+        }
+        load[lane] += macs + 2e8;                        // (+ a launch's worth)
+        lane_of[k] = lane;
+        lane_used[lane] = true;
+    }
+    // fork: the side streams that get work start after whatever the caller's stream holds so far
+    bool forked = false;
+    for (int i = 1; i <= kSideStreams; ++i) {
+        if (!lane_used[i]) continue;
+        if (!forked && (rc = hip_check(hipEventRecord(S.fork, user), "hipEventRecord")) != VGC_OK) return rc;
+        forked = true;
+        if ((rc = hip_check(hipStreamWaitEvent(S.s[i - 1], S.fork, 0), "hipStreamWaitEvent")) != VGC_OK) return rc;
+    }
+    int first_error = VGC_OK;
+    for (uint32_t k = 0; k < n_layers; ++k) {
+        const vgc_conv2d_layer& L = layers[k];
+        hipStream_t st = lane_of[k] == 0 ? user : S.s[lane_of[k] - 1];
+        const int r = launch_conv2d(L.dtype, L.act, L.D, L.B, L.H, L.W, L.Cin, L.C, L.kh, L.kw, L.stride_h, L.stride_w, L.pad_h,
+                                    L.pad_w, Ho[k], Wo[k], L.c, L.g_out, L.s_out, L.workspace, L.workspace_bytes, st);
+        if (r != VGC_OK && first_error == VGC_OK) first_error = r;
+    }
+    // join: the caller's stream continues when every side stream is done (also after a failed launch)
+    for (int i = 1; i <= kSideStreams; ++i) {
+        if (!lane_used[i]) continue;
+        if ((rc = hip_check(hipEventRecord(S.join[i - 1], S.s[i - 1]), "hipEventRecord")) != VGC_OK) return rc;
+        if ((rc = hip_check(hipStreamWaitEvent(user, S.join[i - 1], 0), "hipStreamWaitEvent")) != VGC_OK) return rc;
+    }
+    return first_error;
 }
 
 // first_group, group_count: the groups the launch covers (all of them for the whole-model calls)

@@ -39,6 +39,13 @@ class Optimizer(C.Structure):
                 ("beta2", C.c_float), ("eps", C.c_float), ("step", C.c_uint32)]
 
 
+class Conv2dLayer(C.Structure):
+    _fields_ = [("dtype", C.c_int), ("act", C.c_void_p), ("D", C.c_void_p)] + \
+               [(k, C.c_uint32) for k in ("B", "H", "W", "Cin", "C", "kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w")] + \
+               [("c", C.c_float), ("g_out", C.c_void_p), ("s_out", C.c_void_p), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_size_t)]
+
+
 MOMENTUM_SGD, ADAM = 0, 1
 
 HDR_DTYPE = np.dtype([("exp_field", "<u4"), ("count", "<u4"), ("word_offset", "<u8")])
@@ -60,6 +67,7 @@ EXPORTS = {
     "vgc_sqgrad_conv2d_workspace_bytes": (C.c_size_t, [C.c_int] + [C.c_uint32] * 11),
     "vgc_sqgrad_conv2d": (C.c_int, [C.c_int, C.c_void_p, C.c_void_p] + [C.c_uint32] * 11 +
                           [C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]),
+    "vgc_sqgrad_conv2d_batch": (C.c_int, [C.c_void_p, C.c_uint32, C.c_void_p]),
     "vgc_accumulate_select": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
                                         C.c_uint32, C.c_void_p, C.c_float, C.c_float, C.c_void_p, C.c_void_p]),
     "vgc_accumulate_select_hybrid": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64, C.c_void_p,
@@ -335,6 +343,37 @@ def sqgrad_conv2d(act, D, kh, kw, stride, pad, c, s_out, g_out=None, workspace=N
     _check(load().vgc_sqgrad_conv2d(dtype, _ptr(act), _ptr(D), B, H, W, Cin, D.shape[3], kh, kw, stride[0], stride[1],
                                     pad[0], pad[1], float(c), _ptr(g_out), _ptr(s_out), _ptr(workspace),
                                     0 if workspace is None else workspace.numel(), _stream()))
+
+
+def _conv2d_layer(a, act, D, kh, kw, stride, pad, c, s_out, g_out, workspace):
+    """The checks of sqgrad_conv2d on one layer; its record for the batch call."""
+    import torch
+    dtype = {torch.float32: F32, torch.bfloat16: BF16}.get(act.dtype)
+    if dtype is None or D.dtype != act.dtype:
+        raise VgcError(f"unsupported dtypes {act.dtype}, {D.dtype}")
+    B, H, W, Cin = act.shape
+    Ho, Wo = (H + 2 * pad[0] - kh) // stride[0] + 1, (W + 2 * pad[1] - kw) // stride[1] + 1
+    if tuple(D.shape[:3]) != (B, Ho, Wo) or not act.is_contiguous() or not D.is_contiguous():
+        raise VgcError(f"D {tuple(D.shape)} is not the output gradient [B, {Ho}, {Wo}, C] of act {tuple(act.shape)} "
+                       f"(or a tensor is not contiguous)")
+    a.on_device(act, "act"); a.on_device(D, "D")
+    a.need(s_out, kh * kw * Cin * D.shape[3], torch.float32, "s_out")
+    a.need(g_out, kh * kw * Cin * D.shape[3], torch.float32, "g_out")
+    a.need(workspace, 0, torch.uint8, "workspace")
+    addr = lambda t: None if t is None else t.data_ptr()
+    return Conv2dLayer(dtype, addr(act), addr(D), B, H, W, Cin, D.shape[3], kh, kw, stride[0], stride[1], pad[0], pad[1],
+                       float(c), addr(g_out), addr(s_out), addr(workspace), 0 if workspace is None else workspace.numel())
+
+
+def sqgrad_conv2d_batch(layers):
+    """vgc_sqgrad_conv2d_batch.  layers: sequence of dicts with the arguments of sqgrad_conv2d (act, D, kh, kw, stride,
+    pad, c, s_out and optionally g_out, workspace); every layer needs outputs and a workspace of its own."""
+    a = _Args()
+    recs = [_conv2d_layer(a, L["act"], L["D"], L["kh"], L["kw"], L["stride"], L["pad"], L["c"], L["s_out"], L.get("g_out"),
+                          L.get("workspace")) for L in layers]
+    a.launchable()
+    arr = (Conv2dLayer * len(recs))(*recs)
+    _check(load().vgc_sqgrad_conv2d_batch(C.cast(arr, C.c_void_p), len(recs), _stream()))
 
 
 def accumulate_select(g, s, r, v, plan, alpha, zeta, scratch):

@@ -131,6 +131,12 @@ def test_conv2d_and_update_argument_checks_need_no_gpu():
     assert conv(vgc.BF16, 8, 8, 3, 3) == -2 and b"pad" in lib.vgc_last_error()
     assert conv(9, 8, 8, 3, 1) == -4
     assert lib.vgc_sqgrad_conv2d(vgc.BF16, None, fake, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, None, fake, None, 0, None) == -1
+    # the batch call checks every layer before it touches a stream
+    ok = vgc.Conv2dLayer(vgc.BF16, 0x1000, 0x1000, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, None, 0x1000, None, 0)
+    odd = vgc.Conv2dLayer(vgc.BF16, 0x1000, 0x1000, 2, 8, 8, 12, 8, 3, 3, 1, 1, 1, 1, 1.0, None, 0x1000, None, 0)
+    arr2 = (vgc.Conv2dLayer * 2)(ok, odd)
+    assert lib.vgc_sqgrad_conv2d_batch(C.cast(arr2, C.c_void_p), 2, None) == -2 and b"multiples of 16 bytes" in lib.vgc_last_error()
+    assert lib.vgc_sqgrad_conv2d_batch(None, 2, None) == -1
     # the workspace query is pure host code: a layer with few tiles and many positions wants room for partial products
     assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1) > 0
     assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 6, 64, 3, 3, 1, 1, 1, 1) == 0     # unsupported shape

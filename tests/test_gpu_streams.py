@@ -67,3 +67,55 @@ def test_layers_on_three_streams_equal_serial(dev):
     for a, b in zip(serial, overlapped):
         assert np.isfinite(a).all()
         assert np.array_equal(a, b)
+
+
+def test_batch_call_equals_layer_by_layer(dev):
+    """vgc_sqgrad_conv2d_batch (the layers' kernels spread over the caller's stream and the library's side streams,
+    forked from and joined into the caller's stream) gives every layer the bits of vgc_sqgrad_conv2d alone, also when
+    the caller's stream is not the default one and has work queued before and after the call."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    from oracle import vgc_oracle as O
+    layers, ref = [], []
+    for i, (B, H, Wd, Cin, C, k, st, pd, bf16) in enumerate(LAYERS):
+        Ho, Wo = O.conv_out_size(H, k, st, pd), O.conv_out_size(Wd, k, st, pd)
+        A, D = W.conv2d_inputs(90 + i, (i,), B, H, Wd, Cin, Ho, Wo, C, d_sigma=0.02, bf16=bf16)
+        At, Dt = torch.from_numpy(np.ascontiguousarray(A)).to(dev), torch.from_numpy(np.ascontiguousarray(D)).to(dev)
+        if bf16:
+            At, Dt = At.view(torch.bfloat16), Dt.view(torch.bfloat16)
+        code = vgc.BF16 if bf16 else vgc.F32
+        nb = vgc.sqgrad_conv2d_workspace_bytes(code, B, H, Wd, Cin, C, k, k, (st, st), (pd, pd))
+        J = k * k * Cin
+        new = lambda: dict(s_out=torch.full((J, C), float("nan"), dtype=torch.float32, device=dev),
+                           g_out=torch.full((J, C), float("nan"), dtype=torch.float32, device=dev) if i % 2 else None,
+                           workspace=torch.full((max(nb, 1),), 0xFF, dtype=torch.uint8, device=dev) if nb else None)
+        one = new()
+        vgc.sqgrad_conv2d(At, Dt, k, k, (st, st), (pd, pd), 1.0 / B, one["s_out"], one["g_out"], workspace=one["workspace"])
+        ref.append(one)
+        layers.append(dict(act=At, D=Dt, kh=k, kw=k, stride=(st, st), pad=(pd, pd), c=1.0 / B, **new()))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    marker = torch.zeros(1 << 22, device=dev)
+    for rep in range(2):                                           # the second call reuses the side streams and events
+        for L in layers:
+            L["s_out"].fill_(float("nan"))
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            marker.add_(1.0)                                       # queued before the fork
+            vgc.sqgrad_conv2d_batch(layers)
+            total = sum(L["s_out"].sum() for L in layers)          # queued after the join: must see every layer's result
+        side.synchronize()
+        assert torch.isfinite(total).item()
+        for L, one in zip(layers, ref):
+            assert torch.equal(L["s_out"], one["s_out"])
+            if one["g_out"] is not None:
+                assert torch.equal(L["g_out"], one["g_out"])
+    vgc.sqgrad_conv2d_batch([])                                    # nothing to do is not an error
+    # an error in any layer: nothing is launched
+    bad = dict(layers[0]); bad["s_out"] = torch.empty(3, dtype=torch.float32, device=dev)
+    for L in layers:
+        L["s_out"].fill_(float("nan"))
+    with pytest.raises(vgc.VgcError):
+        vgc.sqgrad_conv2d_batch(layers[:2] + [bad])
+    torch.cuda.synchronize()
+    assert all(torch.isnan(L["s_out"]).all().item() for L in layers[:2])
