@@ -325,15 +325,11 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
                 acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf, zf, (f16v){0}, 0, 0, 0);
             }
     };
-    // Ring: chunk c lives in buffer c % kNB; kNB chunks are requested up front and one more per iteration,
-    // into the buffer of the chunk just consumed.  A wave's loads complete in order, so once all but the
-    // loads of its last kNB - 2 requests are back, its pieces of the chunk needed next are in LDS.  The trip
-    // count of the pipelined loop is rounded up to a multiple of its unroll factor; the surplus chunks are
-    // all zeros and add nothing.
-    //
-    // Without g the loop is pipelined across the barrier (below) and refills a buffer one chunk after it was
-    // consumed: kNB - 1 chunks are requested up front and chunk q + kNB - 1 goes into chunk q - 1's buffer.
-    constexpr int kAhead = kWantG ? kNB : kNB - 1;       // requests ahead of the chunk being consumed
+    // Ring: chunk c lives in buffer c % kNB; kNB - 1 chunks are requested up front and one more per iteration:
+    // chunk q + kNB - 1 goes into the buffer of chunk q - 1, one chunk after that was consumed (the loop is
+    // pipelined across its barrier, below).  A wave's loads complete in order, so once all but the loads of its
+    // last kNB - 3 requests are back, its pieces of the chunk needed next are in LDS.
+    constexpr int kAhead = kNB - 1;                      // requests ahead of the chunk being consumed
     constexpr int kInFlight = (kAhead - 2) * kPer;
     constexpr uint32_t kNever = 0x3FFFFFFFu;
     // chunks until: the requests reach the end of a sample, the last request, the consumed sample is complete
@@ -362,7 +358,7 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             span = ev = min(left, min(to_wrap, todo));
         }
     };
-    if constexpr (!kWantG) {
+    {
         // One k-step (16 positions: one MFMA per 32 x 32 tile) is a phase.  While the MFMAs of a phase run, the
         // operand fragments of the next phase are read from LDS: the A fragments into the other of two register
         // sets, a B fragment into the registers of the one it replaces as soon as the two MFMAs that use it are
@@ -429,31 +425,6 @@ void k_conv_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D,
             request_done();
             tick();
             }
-        }
-    } else {
-        wait_loads_but<kInFlight>();                     // chunks 0 and 1 have landed
-        __syncthreads();
-        uint32_t bo_cur = 0;                             // buffer of the chunk being consumed
-        for (uint32_t q = 0; q < total; ++q) {
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                bf8v fa[2], fb[2];
-#pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    fa[t] = frag_a(bo_cur, ks, t);
-                    fb[t] = frag_b(bo_cur, ks, t);
-                }
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt)
-#pragma unroll
-                    for (int nt = 0; nt < 2; ++nt)
-                        acc[mt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mt], fb[nt], acc[mt][nt], 0, 0, 0);
-            }
-            wait_loads_but<kInFlight>();                 // chunk q+1 has landed (this wave's pieces)
-            __syncthreads();                             // ... everybody's, and chunk q's buffer is free
-            issue(bo_cur);                               // chunk q + kNB into chunk q's buffer
-            bo_cur = next_buf(bo_cur);
-            tick();
         }
     }
     wait_loads_but<0>();                                 // nothing may still be landing when the workgroup ends
