@@ -258,7 +258,15 @@ size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint
     uint32_t Ho, Wo;
     if (conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, &Ho, &Wo) != VGC_OK) return 0;
     const uint32_t J = kh * kw * Cin;
-    if (dtype == VGC_BF16) return conv_workspace_bytes(B, Ho * Wo, J, C);
+    if (dtype == VGC_BF16) {
+        // the larger of what the two kernels that may serve the layer want (which one runs depends on whether g is asked for)
+        size_t need = conv_workspace_bytes(B, Ho * Wo, J, C);
+        if (conv_taps_supported(H, W, Cin, C, kh, kw, sh, sw, ph, pw)) {
+            const size_t t = conv_taps_workspace_bytes(B, Ho * Wo, Cin, C);
+            if (t > need) need = t;
+        }
+        return need;
+    }
     return conv_f32_workspace_bytes(B, Ho * Wo, J, C);
 }
 

@@ -186,6 +186,9 @@ int launch_sqgrad_simple(int kind, int dtype, const void* X, const void* D, uint
 // LDS-tiled kernels (vgc_sqgrad_tiled.hip, vgc_sqgrad_fc.hip)
 uint32_t conv_splits(uint32_t B, uint32_t J, uint32_t C);
 size_t conv_workspace_bytes(uint32_t B, uint32_t P, uint32_t J, uint32_t C);
+bool conv_taps_supported(uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw,
+                         uint32_t ph, uint32_t pw);
+size_t conv_taps_workspace_bytes(uint32_t B, uint32_t P, uint32_t Cin, uint32_t C);
 bool conv_tiled_supported(int dtype, uint32_t P, uint32_t J, uint32_t C);
 void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg, float cs, float* g_out, float* s_out,
                           hipStream_t stream);

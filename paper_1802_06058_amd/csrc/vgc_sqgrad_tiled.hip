@@ -27,6 +27,7 @@
 // with a function of the row (swizzle) on the way in, by choosing which global piece each lane
 // fetches, and on the way out in the fragment addresses.
 #include "vgc_internal.h"
+#include <type_traits>
 
 namespace vgc {
 
@@ -646,6 +647,271 @@ void launch_sqgrad_reduce(const float* ws, uint32_t splits, size_t JC, float cg,
                            g_out, s_out, lanes);
 }
 
+// ------------------------------------------------------------------------------------------------
+// 3 x 3 filters with unit stride and padding 1 on few input channels (the first layers of a VGG-like
+// network: 64 or 128 channels at 224^2 and 112^2 positions).  In the kernel above such a layer is bound by
+// the feed: its block tile is small (J = 9 Cin has few 128-column tiles and C is narrow), and the nine
+// taps of the filter fetch the same input elements nine times through the load path.  Here a workgroup
+// owns ALL nine taps of a block of 64 input channels, times 64 output channels (a 576 x 64 tile of
+// [J, C]), and stages the distinct input block of a chunk once: for 16 consecutive output positions of one
+// output row that is 3 input rows x 18 columns x 64 channels, and the fragment of tap (ky, kx) is read
+// from it at a constant offset, (ky 18 + kx) staged pixels further.  A chunk is two such halves of 16
+// positions (one k-step each; W is a multiple of 16, so a half never crosses an output row): 2 x (54
+// pixels x 128 bytes) of input and 2 x (16 x 128 bytes) of output gradient = 18 KiB for 576 x 64 x 32
+// multiply-adds, against 40 KiB through the generic path.
+//
+// Twelve waves, three per SIMD: wave w takes column half cb = w % 2 of the 64 output channels and the
+// three 32-row blocks jb = 3 (w / 2) + {0, 1, 2} of the 18 (tap, channel half) blocks: three MFMAs per
+// k-step from three U fragments and one D fragment.  The 14 + 4 wave-wide loads of a chunk are dealt to
+// the waves in order: waves 0..5 issue two, waves 6..11 one (the loop exists once per count, since a
+// wave waits for its own loads by their number).  Pipeline, ring, sample bookkeeping, splits and the
+// reduction kernels are those of the kernel above.  s only: the variant with g stays with that kernel.
+// Staged layout of one chunk: [half 0: 56 pixel slots x 128 B][half 1][D half 0: 16 rows x 128 B][D half 1];
+// slot = 18 ry + rx for input row y - 1 + ry and column x0 - 1 + rx, slots 54 and 55 unused.  The 64-byte
+// halves of a slot (channels 0..31, 32..63) are swapped in slots with (slot / 2) odd, so that the four
+// consecutive slots a transposing read touches fall on different banks.
+constexpr int kTapHalfA = 56 * 128, kTapHalfB = 16 * 128, kTapBuf = 2 * kTapHalfA + 2 * kTapHalfB;
+constexpr int kTapNB = 6, kTapWaves = 12;
+
+__global__ __launch_bounds__(kTapWaves * 64, 3)
+void k_conv_taps_bf16(const uint16_t* __restrict__ U, const uint16_t* __restrict__ D, uint32_t B, uint32_t H, uint32_t W,
+                      uint32_t Cin, uint32_t C, uint32_t period, uint32_t splits, uint32_t split_p, float cs,
+                      float* __restrict__ s_out, float* __restrict__ ws) {
+    constexpr int kNB = kTapNB, kBufBytes = kTapBuf, kRingBytes = kNB * kBufBytes;
+    __shared__ __attribute__((aligned(1024))) uint8_t sh[kRingBytes + 1024];
+    const uint32_t tid = threadIdx.x, lane = tid & 63u;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t P = H * W, J = 9u * Cin;
+    const uint32_t tiles_c = C / 64u, tiles_cb = Cin / 64u;
+    // every XCD a contiguous range of (split, channel block, column tile): see the kernel above
+    const uint32_t nblk = gridDim.x, per = nblk / 8u, rem = nblk % 8u;
+    const uint32_t xcd = blockIdx.x % 8u, slot_x = blockIdx.x / 8u;
+    const uint32_t logical = xcd * per + min(xcd, rem) + slot_x;
+    const uint32_t tile_c = logical % tiles_c, tile_cb = (logical / tiles_c) % tiles_cb, split = logical / (tiles_c * tiles_cb);
+    const uint32_t n_chunks = (P + kKC - 1) / kKC;
+    const uint32_t part = split_p > 1 ? split % split_p : 0u;
+    const uint32_t chunks_per_part = (n_chunks + split_p - 1) / split_p;
+    const uint32_t c_begin = min(n_chunks, part * chunks_per_part);
+    const uint32_t z_begin = split_p > 1 ? split / split_p : (uint32_t)((uint64_t)split * B / splits);
+    const uint32_t z_end = split_p > 1 ? z_begin + 1u : (uint32_t)((uint64_t)(split + 1u) * B / splits);
+    const uint32_t total = split_p > 1 ? min(n_chunks, c_begin + chunks_per_part) - c_begin : (z_end - z_begin) * n_chunks;
+
+    reinterpret_cast<uint32_t*>(sh + kRingBytes)[tid & 255u] = 0u;      // the compiler must see a store to the array
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)sh;
+
+    // ---- LDS side: fragment addresses inside a staged chunk ----
+    const uint32_t r = lane & 15u, grp = lane >> 4, mhalf = grp & 1u, khalf = grp >> 1;
+    const uint32_t frow = khalf * 8u + (r >> 2);                 // position inside the half (second read: + 4)
+    const uint32_t cb = wave & 1u, jgrp = wave >> 1;
+    uint32_t fA[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        const uint32_t jb = 3u * jgrp + (uint32_t)t, tap = jb >> 1, chb = jb & 1u, ky = tap / 3u, kx = tap - 3u * ky;
+        const uint32_t s0 = ky * 18u + kx + frow;                // staged slot of the fragment's first row
+        fA[t] = s0 * 128u + ((chb ^ ((s0 >> 1) & 1u)) * 64u) + mhalf * 32u + (r & 3u) * 8u;
+    }
+    const uint32_t fB = 2u * kTapHalfA + frow * 128u + ((cb ^ ((frow >> 1) & 1u)) * 64u) + mhalf * 32u + (r & 3u) * 8u;
+    auto frag_a = [&](uint32_t bo, int ks, int t) -> bf8v {      // slots s and s + 4 share the swizzle
+        const uint8_t* p = sh + bo + fA[t] + ks * kTapHalfA;
+        const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p));
+        const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p + 4 * 128));
+        s8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf8v, v);
+    };
+    auto frag_b = [&](uint32_t bo, int ks) -> bf8v {
+        const uint8_t* p = sh + bo + fB + ks * kTapHalfB;
+        const s4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p));
+        const s4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(p + 4 * 128));
+        s8v v = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        return __builtin_bit_cast(bf8v, v);
+    };
+
+    f16v acc[3], s_acc[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) { acc[t] = (f16v){0}; s_acc[t] = (f16v){0}; }
+
+    SampleWindow wa, wb;
+    wa.init(U, z_begin, P, Cin);                                 // the whole input of the sample
+    wb.init(D, z_begin, P, C);
+
+    auto run = [&](auto per_tag) __attribute__((always_inline)) {
+        constexpr int kPer = decltype(per_tag)::value;
+        // ---- global side: load n of this wave is load L = wave + 12 n of the chunk's 18; L < 14: input pixels of
+        // half L / 7, slots 8 (L % 7) .. + 7; else output-gradient rows 8 ((L - 14) % 2) .. + 7 of half (L - 14) / 2.
+        // Per load the lane keeps the byte offset of its 16-byte piece inside the sample for the chunk requested
+        // next (it advances by a constant per chunk), the offset in a sample's first chunk, and for input pixels
+        // one bit per chunk of the period saying that the pixel's column lies outside the row.
+        uint32_t ob[kPer], ob0[kPer], step[kPer], outside[kPer], ldsoff[kPer];
+        bool is_a[kPer];
+        uint32_t kph = __builtin_amdgcn_readfirstlane(c_begin % period);
+#pragma unroll
+        for (int n = 0; n < kPer; ++n) {
+            const uint32_t L = wave + (uint32_t)kTapWaves * n, p = lane & 7u;
+            is_a[n] = L < 14u;
+            if (is_a[n]) {
+                const uint32_t h = L / 7u, i = L - 7u * h, slot = i * 8u + (lane >> 3);
+                const uint32_t piece = (((p >> 2) ^ ((slot >> 1) & 1u)) << 2) | (p & 3u);
+                const uint32_t ry = slot / 18u, rx = slot - 18u * ry;
+                const int32_t pix = (int32_t)(16u * h) + ((int32_t)ry - 1) * (int32_t)W + (int32_t)rx - 1;
+                ob0[n] = (uint32_t)((pix * (int32_t)Cin + (int32_t)(tile_cb * 64u + piece * 8u)) * 2);
+                step[n] = kKC * Cin * 2u;
+                uint32_t bits = 0, x0 = (16u * h) % W;
+                for (uint32_t k = 0; k < period; ++k) {          // chunk k of the period: is the column outside?
+                    bits |= ((uint32_t)((int32_t)x0 + (int32_t)rx - 1) < W ? 0u : 1u) << k;
+                    x0 = (x0 + kKC) % W;
+                }
+                outside[n] = slot < 54u ? bits : 0xFFFFFFFFu;
+                ldsoff[n] = __builtin_amdgcn_readfirstlane(h * kTapHalfA + i * 1024u);
+            } else {
+                const uint32_t q = L - 14u, h = q >> 1, row = (q & 1u) * 8u + (lane >> 3);
+                const uint32_t piece = (((p >> 2) ^ ((row >> 1) & 1u)) << 2) | (p & 3u);
+                ob0[n] = ((16u * h + row) * C + tile_c * 64u + piece * 8u) * 2u;
+                step[n] = kKC * C * 2u;
+                outside[n] = 0u;
+                ldsoff[n] = __builtin_amdgcn_readfirstlane(2u * kTapHalfA + h * kTapHalfB + (q & 1u) * 1024u);
+            }
+            ob[n] = ob0[n] + c_begin * step[n];
+        }
+        auto issue_one = [&](uint32_t bo, int n) {
+            // rows of the input above or below the image need no test: their offset is negative or past the sample's
+            // range and reads as zeros; a column outside would alias into the neighbouring row and is masked; a
+            // position past P aliases into a valid pixel, but the rows of D past P read as zeros
+            const uint32_t voff = ob[n] | (uint32_t)__builtin_amdgcn_sbfe((int32_t)outside[n], kph, 1u);
+            ob[n] += step[n];
+            const i4v ra = wa.rsrc(), rb = wb.rsrc();
+            i4v rs;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) rs[e] = is_a[n] ? ra[e] : rb[e];
+            load_to_lds(lds0 + bo, ldsoff[n], voff, rs);
+        };
+        auto request_done = [&]() { kph = (kph + 1u == period) ? 0u : kph + 1u; };
+        auto issue = [&](uint32_t bo) {
+#pragma unroll
+            for (int n = 0; n < kPer; ++n) issue_one(bo, n);
+            request_done();
+        };
+        auto wrap = [&]() {
+            wa.next_sample();
+            wb.next_sample();
+            kph = 0u;
+#pragma unroll
+            for (int n = 0; n < kPer; ++n) ob[n] = ob0[n];
+        };
+        auto close = [&]() { wa.close(); wb.close(); };
+        auto sample_end = [&]() {
+            const bf8v zf = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float x = acc[t][i];
+                    s_acc[t][i] = __builtin_fmaf(x, x, s_acc[t][i]);
+                }
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(zf, zf, (f16v){0}, 0, 0, 0);
+            }
+        };
+        constexpr int kAhead = kNB - 1;
+        constexpr int kInFlight = (kAhead - 2) * kPer;
+        constexpr uint32_t kNever = 0x3FFFFFFFu;
+        auto next_buf = [&](uint32_t bo) -> uint32_t { return bo + kBufBytes == (uint32_t)kRingBytes ? 0u : bo + kBufBytes; };
+        uint32_t to_wrap = __builtin_amdgcn_readfirstlane(n_chunks - c_begin);
+        uint32_t todo = __builtin_amdgcn_readfirstlane(total);
+        {
+            uint32_t bo = 0;
+#pragma unroll 1
+            for (int i = 0; i < kAhead; ++i) {
+                issue(bo);
+                bo = next_buf(bo);
+                if (--to_wrap == 0) { to_wrap = n_chunks; wrap(); }
+                if (--todo == 0) { todo = kNever; close(); }
+            }
+        }
+        uint32_t left = split_p > 1 ? kNever : n_chunks;
+        uint32_t span = min(left, min(to_wrap, todo)), ev = span;
+        auto tick = [&]() {
+            if (--ev == 0) {
+                left -= span; to_wrap -= span; todo -= span;
+                if (left == 0) { left = n_chunks; sample_end(); }
+                if (to_wrap == 0) { to_wrap = n_chunks; wrap(); }
+                if (todo == 0) { todo = kNever; close(); }
+                span = ev = min(left, min(to_wrap, todo));
+            }
+        };
+        wait_loads_but<kInFlight + kPer>();                      // chunk 0 has landed (this wave's pieces)
+        __syncthreads();
+        bf8v FA[2][3], FB[2];
+#pragma unroll
+        for (int t = 0; t < 3; ++t) FA[0][t] = frag_a(0, 0, t);
+        FB[0] = frag_b(0, 0);
+        for (uint32_t q0 = 0; q0 < total; q0 += kNB) {
+#pragma unroll
+            for (int b = 0; b < kNB; ++b) {
+            if (q0 + (uint32_t)b >= total) break;
+            const uint32_t bo_cur = (uint32_t)b * kBufBytes, bo_next = (uint32_t)((b + 1) % kNB) * kBufBytes;
+            const uint32_t bo_prev = (uint32_t)((b + kNB - 1) % kNB) * kBufBytes;
+            // phase 0: half 0 of chunk q; fragments of its half 1
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[0][t], FB[0], acc[t], 0, 0, 0);
+                FA[1][t] = frag_a(bo_cur, 1, t);
+                if (t == 2) FB[1] = frag_b(bo_cur, 1);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            wait_loads_but<kInFlight>();                         // chunk q + 1 has landed (this wave's pieces)
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            // phase 1: half 1 of chunk q; fragments of half 0 of chunk q + 1; the request for chunk q + kNB - 1
+#pragma unroll
+            for (int t = 0; t < 3; ++t) {
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(FA[1][t], FB[1], acc[t], 0, 0, 0);
+                FA[0][t] = frag_a(bo_next, 0, t);
+                if (t == 2) FB[0] = frag_b(bo_next, 0);
+#pragma unroll
+                for (int n = 0; n < kPer; ++n)
+                    if (t == (n * 3) / kPer) issue_one(bo_prev, n);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+            request_done();
+            tick();
+            }
+        }
+        wait_loads_but<0>();                                     // nothing may still be landing when the workgroup ends
+    };
+    if (wave < 6u) run(std::integral_constant<int, 2>{});
+    else run(std::integral_constant<int, 1>{});
+
+    // ---- epilogue: scaled result, unscaled partial sums for the fixed-order reduction, or (split_p > 1) the partial
+    // per-sample product ----
+    const bool direct = (splits == 1);
+    const size_t JC = (size_t)J * C;
+    float* so = direct ? s_out : ws + (size_t)split * 2 * JC;
+    if (split_p > 1) so = ws + (size_t)split * JC;
+    const float fs = direct ? cs : 1.0f;
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        const uint32_t jb = 3u * jgrp + (uint32_t)t, tap = jb >> 1, chb = jb & 1u;
+        const uint32_t col = tile_c * 64u + cb * 32u + (lane & 31u);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const uint32_t row = tap * Cin + tile_cb * 64u + chb * 32u + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+            const size_t o = (size_t)row * C + col;
+            if (split_p > 1) __builtin_nontemporal_store(acc[t][i], so + o);
+            else if (direct) __builtin_nontemporal_store(fs * s_acc[t][i], so + o);
+            else so[o] = s_acc[t][i];
+        }
+    }
+}
+
 template <int BM, int BN, bool kImplicit, bool kLinear = false>
 static void launch_conv_bf16(uint32_t nblk, hipStream_t stream, const void* X, const void* D, uint32_t B, uint32_t P,
                              uint32_t J, uint32_t C, uint32_t splits, uint32_t split_p, float cg, float cs,
@@ -696,6 +962,68 @@ static int launch_conv_any(const void* X, const void* D, uint32_t B, uint32_t P,
     return hip_check(hipGetLastError(), "launch k_conv_bf16");
 }
 
+// ---- the 3 x 3 kernel for few input channels: when it applies, how it splits, what workspace it wants ----
+static uint32_t taps_period(uint32_t W) {
+    uint32_t a = W, b = kKC % W;
+    while (b) { const uint32_t t = a % b; a = b; b = t; }
+    return W / a;
+}
+
+bool conv_taps_supported(uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw,
+                         uint32_t ph, uint32_t pw) {
+    (void)H;
+    return kh == 3 && kw == 3 && sh == 1 && sw == 1 && ph == 1 && pw == 1 && (Cin == 64 || Cin == 128) && C % 64 == 0 &&
+           W % 16 == 0 && taps_period(W) <= 32;
+}
+
+struct TapsSplit { uint32_t splits, split_p; };
+static TapsSplit taps_split(uint32_t B, uint32_t P, uint32_t Cin, uint32_t C) {
+    const uint64_t tiles = (uint64_t)(Cin / 64) * (C / 64);
+    ConvTile one_per_cu; one_per_cu.bm = 256; one_per_cu.bn = 128;      // eight waves' worth of slots: one workgroup per compute unit
+    const uint64_t slots = conv_slots(one_per_cu);
+    const uint32_t n_chunks = (P + kKC - 1) / kKC;
+    TapsSplit r; r.splits = 1; r.split_p = 1;
+    if (tiles * B * 3 <= slots * 2 && n_chunks >= 16) {                 // the same rule as conv_split_p
+        const uint64_t sp = tiles * B * 2 <= slots ? slots / (tiles * B) : 2 * slots / (tiles * B);
+        r.split_p = (uint32_t)(sp < n_chunks / 8 ? sp : n_chunks / 8);
+    }
+    if (r.split_p > 1) { r.splits = B * r.split_p; return r; }
+    double best = 1e300;                                                // the same cost as conv_splits
+    for (uint32_t s = 1; s <= B; ++s) {
+        const uint32_t zper = (B + s - 1) / s, s2 = (B + zper - 1) / zper;
+        if (s2 != s) continue;
+        const uint64_t rounds = (tiles * s2 + slots - 1) / slots;
+        const double cost = (double)rounds * zper + (s2 > 1 ? 0.5 * s2 * (double)tiles / slots + 0.5 : 0.0);
+        if (cost < best - 1e-9) { best = cost; r.splits = s2; }
+    }
+    return r;
+}
+
+size_t conv_taps_workspace_bytes(uint32_t B, uint32_t P, uint32_t Cin, uint32_t C) {
+    const TapsSplit t = taps_split(B, P, Cin, C);
+    const size_t JC = (size_t)9 * Cin * C;
+    if (t.split_p > 1) return (size_t)B * t.split_p * JC * sizeof(float);
+    return t.splits > 1 ? (size_t)t.splits * 2 * JC * sizeof(float) : 0;
+}
+
+// false: the workspace is too small for this kernel's split (the caller takes the generic path)
+static bool launch_conv_taps(const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
+                             float c, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    const uint32_t P = H * W;
+    const TapsSplit t = taps_split(B, P, Cin, C);
+    if (conv_taps_workspace_bytes(B, P, Cin, C) > (workspace ? workspace_bytes : 0)) return false;
+    const size_t JC = (size_t)9 * Cin * C;
+    const uint64_t nblk = (uint64_t)(Cin / 64) * (C / 64) * t.splits;
+    if (nblk > 0x7FFFFFFFull) return false;
+    float* ws = static_cast<float*>(workspace);
+    const float cs = c * c;
+    hipLaunchKernelGGL(k_conv_taps_bf16, dim3((uint32_t)nblk), dim3(kTapWaves * 64), 0, stream, (const uint16_t*)act,
+                       (const uint16_t*)D, B, H, W, Cin, C, taps_period(W), t.splits, t.split_p, cs, s_out, ws);
+    if (t.split_p > 1) launch_sqgrad_reduce_parts(ws, B, t.split_p, JC, c, cs, nullptr, s_out, stream);
+    else if (t.splits > 1) launch_sqgrad_reduce(ws, t.splits, JC, c, cs, nullptr, s_out, stream);
+    return true;
+}
+
 int launch_conv_tiled(int dtype, const void* X, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C,
                       float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
     (void)dtype;
@@ -719,6 +1047,10 @@ int launch_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_
     ConvGeom G{};
     G.H = H; G.W = W; G.Cin = Cin; G.kw = kw; G.sh = sh; G.sw = sw; G.ph = ph; G.pw = pw; G.Ho = Ho; G.Wo = Wo;
     if (dtype == VGC_F32) return launch_conv2d_f32(act, D, B, Ho * Wo, kh * kw * Cin, C, c, g_out, s_out, workspace, workspace_bytes, G, stream);
+    // s alone of a 3 x 3 layer on 64 or 128 channels: the kernel that stages the input block once for all nine taps
+    if (!g_out && conv_taps_supported(H, W, Cin, C, kh, kw, sh, sw, ph, pw) &&
+        launch_conv_taps(act, D, B, H, W, Cin, C, c, s_out, workspace, workspace_bytes, stream))
+        return hip_check(hipGetLastError(), "launch k_conv_taps_bf16");
     G.step_y = kKC / Wo;
     G.step_x = kKC % Wo;
     // unit strides and an output as wide as the input: offsets are linear in the output position and the column

@@ -146,6 +146,8 @@ def test_conv2d_equals_patch_matrix_path(dev):
 
 @pytest.mark.parametrize("B,H,Cin,C,prec", [(64, 28, 512, 512, "bf16"),      # VGG-16 conv4_2
                                             (64, 14, 512, 512, "bf16"),      # VGG-16 conv5_x
+                                            (64, 112, 128, 128, "bf16"),     # VGG-16 conv2_2 (s alone: the nine-tap kernel)
+                                            (64, 224, 64, 64, "bf16"),       # VGG-16 conv1_2 (the same, positions split)
                                             (32, 56, 64, 64, "f32"),         # ResNet-50 stage 1, 3x3
                                             (32, 14, 256, 256, "f32")])      # ResNet-50 stage 3, 3x3
 def test_conv2d_every_output_at_config_shapes(dev, B, H, Cin, C, prec):
@@ -171,7 +173,49 @@ def test_conv2d_every_output_at_config_shapes(dev, B, H, Cin, C, prec):
             absG[(ky * 3 + kx) * Cin:(ky * 3 + kx + 1) * Cin] = (win.T.astype(np.float64) @ Dm) / B
     assert (np.abs(g - g64) / np.maximum(absG, 1e-300)).max() <= tol
     _, s_only = _run(A, D, 3, 3, stride, pad, 1.0 / B, dev, want_g=False)    # the kernel the benchmark times
-    assert np.array_equal(s_only, s)
+    if prec == "bf16" and Cin in (64, 128) and H % 16 == 0:                  # another kernel, another grouping of the samples
+        OBSERVED[tag + " (s alone)"] = _rel_s(s_only, s64)
+        assert OBSERVED[tag + " (s alone)"] <= tol
+    else:
+        assert np.array_equal(s_only, s)
+
+
+TAP_GEOMS = [  # B, H, W, Cin, C: 3x3, stride 1, padding 1, 64 or 128 input channels, a width that is a multiple of 16
+    (4, 16, 16, 64, 64),        # one tile, one half-chunk per output row: the column pattern has period 1
+    (1, 16, 16, 64, 64),        # one sample
+    (3, 6, 48, 64, 128),        # width 48: period 3; two column tiles
+    (5, 9, 32, 128, 64),        # two channel blocks, odd height
+    (2, 7, 16, 128, 192),       # 112 positions: the last chunk has one half only
+    (8, 36, 32, 64, 64),        # 36 chunks per sample: the positions are split over workgroups
+    (4, 24, 112, 64, 64),       # width 112 (period 7, a chunk straddles two rows), positions split ten ways
+    (6, 10, 224, 64, 128),      # width 224 (period 7), as the first VGG layers
+]
+
+
+@pytest.mark.parametrize("geom", TAP_GEOMS)
+def test_conv2d_tap_kernel_matches_oracle(dev, geom):
+    """s alone of a 3x3 layer on 64 or 128 channels goes through the kernel that stages the input block of a chunk
+    once for all nine taps: every output against the oracle at the stated tolerance; the call that also returns g
+    (the generic kernel) and the call without a workspace agree with it to the same tolerance (they add the samples'
+    squares in a different grouping, so not bit for bit)."""
+    B, H, Wd, Cin, C = geom
+    TOL = RTOL["bf16"]
+    A, D = W.conv2d_inputs(44, geom, B, H, Wd, Cin, H, Wd, C, d_sigma=0.02, bf16=True)
+    if B < 4:                                       # nothing cancels: see the module docstring
+        A, D = A & 0x7FFF, D & 0x7FFF
+    Aw, Dw = W.bf16_bits_to_f32(A).astype(np.float64), W.bf16_bits_to_f32(D).astype(np.float64)
+    c = 1.0 / B
+    g64, s64 = O.sqgrad_conv_nhwc(Aw, Dw, 3, 3, (1, 1), (1, 1), c)
+    _, s = _run(A, D, 3, 3, (1, 1), (1, 1), c, dev, want_g=False)
+    assert np.isfinite(s).all()
+    tag = f"conv2d bf16 tap kernel {geom}"
+    OBSERVED[tag] = _rel_s(s, s64)
+    assert OBSERVED[tag] <= TOL, f"s relative error {OBSERVED[tag]:.3e}"
+    assert np.all(s[s64 == 0] == 0)
+    _, s_g = _run(A, D, 3, 3, (1, 1), (1, 1), c, dev, want_g=True)
+    assert _rel_s(s_g, s64) <= TOL
+    _, s_nows = _run(A, D, 3, 3, (1, 1), (1, 1), c, dev, want_g=False, use_workspace=False)
+    assert _rel_s(s_nows, s64) <= TOL
 
 
 def test_zz_report_observed_errors():
