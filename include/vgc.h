@@ -162,9 +162,10 @@ int vgc_sqgrad_noalloc(int kind, int dtype, const void* X, const void* D,
  * row (ky * kw + kx) * Cin + i, i.e. the weight in [kh, kw, Cin, C] layout.  It is VGC_CONV applied to
  * the im2col matrix of act, which is never materialised: the input is read directly, 1 / (kh kw) of
  * the bytes, and neighbouring filter taps find each other's lines in the cache.
- * dtype: VGC_F32 or VGC_BF16; Cin and C must be multiples of 16 bytes (4 floats, 8 bfloat16) and a sample's
- * tensors below 2 GiB, else VGC_ERR_SIZE (build the patch matrix and call vgc_sqgrad).  Pointers, workspace
- * and errors as for vgc_sqgrad.
+ * dtype: VGC_F32 or VGC_BF16; C must be a multiple of 16 bytes (4 floats, 8 bfloat16), Cin as well or else
+ * kh * kw * Cin at most 160 (a network's first layer: an RGB input under a 3 x 3 or 7 x 7 filter; such a layer needs
+ * the workspace, VGC_ERR_SIZE without it), and a sample's tensors below 2 GiB, else VGC_ERR_SIZE (build the patch
+ * matrix and call vgc_sqgrad).  Pointers, workspace and errors as for vgc_sqgrad.
  */
 size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
                                          uint32_t kh, uint32_t kw, uint32_t stride_h, uint32_t stride_w,

@@ -144,7 +144,9 @@ static void check_compute_errors() {
     CHECK(vgc_sqgrad_conv2d(VGC_BF16, f, f, 2, 8, 8, 8, 8, 3, 3, 0, 1, 1, 1, 1.f, nullptr, f, nullptr, 0, nullptr) == VGC_ERR_SIZE);
     CHECK(vgc_sqgrad_conv2d(9, f, f, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1.f, nullptr, f, nullptr, 0, nullptr) == VGC_ERR_DTYPE);
     CHECK(vgc_sqgrad_conv2d(VGC_F32, nullptr, f, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1.f, nullptr, f, nullptr, 0, nullptr) == VGC_ERR_NULL);
-    CHECK(vgc_sqgrad_conv2d_workspace_bytes(VGC_F32, 2, 8, 8, 6, 8, 3, 3, 1, 1, 1, 1) == 0);
+    CHECK(vgc_sqgrad_conv2d_workspace_bytes(VGC_F32, 2, 8, 8, 6, 8, 7, 7, 1, 1, 3, 3) == 0);       // 6 channels under 7 x 7: not a first layer's shape
+    CHECK(vgc_sqgrad_conv2d_workspace_bytes(VGC_F32, 2, 8, 8, 6, 8, 3, 3, 1, 1, 1, 1) == 2u * 54 * 8 * 4);   // the first-layer kernel: one part per sample
+    CHECK(vgc_sqgrad_conv2d(VGC_BF16, f, f, 2, 8, 8, 4, 8, 7, 7, 1, 1, 3, 3, 1.f, nullptr, f, nullptr, 0, nullptr) == VGC_ERR_SIZE);
     (void)vgc_sqgrad_conv2d_workspace_bytes(VGC_BF16, 64, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1);
     // (b)
     CHECK(vgc_accumulate_select(nullptr, f, f, f, n, g.data(), 2, plan, 1.f, 0.999f, scratch, nullptr) == VGC_ERR_NULL);

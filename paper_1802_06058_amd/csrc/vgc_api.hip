@@ -246,8 +246,10 @@ static int conv2d_geometry(int dtype, uint32_t B, uint32_t H, uint32_t W, uint32
     if ((uint64_t)kh * kw * Cin > 0x7FFFFFFFull || (uint64_t)H * W > 0x7FFFFFFFull) { set_error("vgc_sqgrad_conv2d: shape too large"); return VGC_ERR_SIZE; }
     *Ho = (H + 2 * ph - kh) / sh + 1;
     *Wo = (W + 2 * pw - kw) / sw + 1;
+    if (conv_stem_supported(dtype, Cin, C, kh, kw)) return VGC_OK;        // a first layer: few input channels, small kh kw Cin
     if (!conv2d_supported(dtype, H, W, Cin, C, *Ho * *Wo)) {
-        set_error("vgc_sqgrad_conv2d: needs Cin and C multiples of 16 bytes and per-sample tensors below 2 GiB");
+        set_error("vgc_sqgrad_conv2d: needs C a multiple of 16 bytes, Cin a multiple of 16 bytes or kh kw Cin <= 160, and "
+                  "per-sample tensors below 2 GiB");
         return VGC_ERR_SIZE;
     }
     return VGC_OK;
@@ -258,6 +260,7 @@ size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint
     uint32_t Ho, Wo;
     if (conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, &Ho, &Wo) != VGC_OK) return 0;
     const uint32_t J = kh * kw * Cin;
+    if (conv_stem_supported(dtype, Cin, C, kh, kw)) return conv_stem_workspace_bytes(dtype, B, Ho * Wo, J, C);
     if (dtype == VGC_BF16) {
         // the larger of what the two kernels that may serve the layer want (which one runs depends on whether g is asked for)
         size_t need = conv_workspace_bytes(B, Ho * Wo, J, C);
@@ -273,7 +276,8 @@ size_t vgc_sqgrad_conv2d_workspace_bytes(int dtype, uint32_t B, uint32_t H, uint
 // Argument checks of vgc_sqgrad_conv2d; the output size on success.
 static int conv2d_check(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin,
                         uint32_t C, uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw,
-                        float c, const float* g_out, const float* s_out, const void* workspace, uint32_t* Ho, uint32_t* Wo) {
+                        float c, const float* g_out, const float* s_out, const void* workspace, size_t workspace_bytes,
+                        uint32_t* Ho, uint32_t* Wo) {
     if (!act || !D || !s_out) { set_error("vgc_sqgrad_conv2d: act, D and s_out are required"); return VGC_ERR_NULL; }
     int rc = conv2d_geometry(dtype, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, Ho, Wo);
     if (rc != VGC_OK) return rc;
@@ -283,6 +287,12 @@ static int conv2d_check(int dtype, const void* act, const void* D, uint32_t B, u
         return VGC_ERR_ALIGN;
     }
     if (!std::isfinite(c)) { set_error("vgc_sqgrad_conv2d: c is not finite"); return VGC_ERR_PARAM; }
+    if (conv_stem_supported(dtype, Cin, C, kh, kw) &&
+        (!workspace || workspace_bytes < conv_stem_workspace_bytes(dtype, B, *Ho * *Wo, kh * kw * Cin, C))) {
+        set_error("vgc_sqgrad_conv2d: a layer whose input channels are not a multiple of 16 bytes needs the workspace "
+                  "vgc_sqgrad_conv2d_workspace_bytes() asks for");
+        return VGC_ERR_SIZE;
+    }
     return VGC_OK;
 }
 
@@ -290,7 +300,7 @@ int vgc_sqgrad_conv2d(int dtype, const void* act, const void* D, uint32_t B, uin
                       uint32_t C, uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw,
                       float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, void* stream) {
     uint32_t Ho, Wo;
-    const int rc = conv2d_check(dtype, act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, c, g_out, s_out, workspace, &Ho, &Wo);
+    const int rc = conv2d_check(dtype, act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, c, g_out, s_out, workspace, workspace_bytes, &Ho, &Wo);
     if (rc != VGC_OK) return rc;
     return launch_conv2d(dtype, act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, Ho, Wo, c, g_out, s_out, workspace, workspace_bytes,
                          static_cast<hipStream_t>(stream));
@@ -314,7 +324,7 @@ int vgc_sqgrad_conv2d_batch(const vgc_conv2d_layer* layers, uint32_t n_layers, v
     for (uint32_t k = 0; k < n_layers; ++k) {             // every layer is checked before anything is launched
         const vgc_conv2d_layer& L = layers[k];
         const int rc = conv2d_check(L.dtype, L.act, L.D, L.B, L.H, L.W, L.Cin, L.C, L.kh, L.kw, L.stride_h, L.stride_w, L.pad_h,
-                                    L.pad_w, L.c, L.g_out, L.s_out, L.workspace, &Ho[k], &Wo[k]);
+                                    L.pad_w, L.c, L.g_out, L.s_out, L.workspace, L.workspace_bytes, &Ho[k], &Wo[k]);
         if (rc != VGC_OK) return rc;
     }
     hipStream_t user = static_cast<hipStream_t>(stream);

@@ -212,6 +212,12 @@ struct ConvGeom {
 };
 
 bool conv2d_supported(int dtype, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C, uint32_t P);
+// first layers: input channels that are not a multiple of 16 bytes, small J (vgc_sqgrad_stem.hip)
+bool conv_stem_supported(int dtype, uint32_t Cin, uint32_t C, uint32_t kh, uint32_t kw);
+size_t conv_stem_workspace_bytes(int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C);
+int launch_conv_stem(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
+                     uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw, uint32_t Ho, uint32_t Wo,
+                     float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream);
 int launch_conv2d_f32(const void* act, const void* D, uint32_t B, uint32_t P, uint32_t J, uint32_t C, float c,
                       float* g_out, float* s_out, void* workspace, size_t workspace_bytes, ConvGeom G, hipStream_t stream);
 int launch_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,

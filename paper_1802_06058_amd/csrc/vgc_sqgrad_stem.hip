@@ -1,0 +1,228 @@
+// The conv statistic (Section 4.1's per-sample sums for a weight tensor, Section 4.2) of a network's first
+// layer, read from the NHWC input: few input channels (an RGB image: Cin = 3), so a pixel's channels are
+// not a multiple of 16 bytes and the kernels that move 16-byte pieces of a filter tap do not apply.  Such
+// a layer has a small J = kh kw Cin (27 for a 3 x 3 filter, 147 for 7 x 7) and few multiply-adds; what it
+// costs is reading the output gradient once, so the kernel is a plain one: a workgroup owns one sample,
+// one part of its positions and 64 output channels; per chunk of 32 positions it gathers the patch rows
+// U[p, j] element by element and the rows of D into LDS, both transposed (32 positions contiguous per
+// column), and multiplies them on the matrix cores; the unsquared partial product of the part goes to the
+// workspace and k_sqgrad_reduce_parts adds the parts of each sample, squares, and sums over the samples
+// in a fixed order.  The rows of D of the chunk after the current one are fetched into registers while the
+// current one is multiplied.
+#include "vgc_internal.h"
+
+namespace vgc {
+
+typedef float f16v __attribute__((ext_vector_type(16)));
+typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
+typedef short s4v __attribute__((ext_vector_type(4)));
+typedef short s8v __attribute__((ext_vector_type(8)));
+typedef uint32_t u4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s4v* lds_s4v_ptr;
+
+constexpr int kStemJMax = 160;         // J is padded to a multiple of 32
+constexpr int kStemBN = 64;            // output channels per workgroup
+
+struct StemGeom {
+    uint32_t H, W, Cin, kw, sh, sw, ph, pw, Ho, Wo, J, Jpad;
+};
+
+// Element type T (bfloat16 bits or float): elements per 16-byte piece, positions per chunk.
+template <typename T> struct StemElem;
+template <> struct StemElem<uint16_t> { static constexpr int kPiece = 8, kKC = 64; };
+template <> struct StemElem<float> { static constexpr int kPiece = 4, kKC = 32; };
+
+// LDS row pitches in bytes (rows are positions; 16 bytes of padding keep four consecutive rows off each other's banks)
+__host__ __device__ inline uint32_t stem_pitch_u(uint32_t Jpad, uint32_t esize) { return Jpad * esize + 16u; }
+__host__ __device__ inline uint32_t stem_pitch_d(uint32_t esize) { return kStemBN * esize + 16u; }
+
+// kG: position groups = 256 / Jpad rounded down to a power of two (8, 4, 2 or 1): how many threads share a column of U
+template <typename T, int kG>
+__global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, const T* __restrict__ D, uint32_t B, uint32_t C,
+                                                   StemGeom G, uint32_t parts, float* __restrict__ ws) {
+    constexpr int kPiece = StemElem<T>::kPiece, kKC = StemElem<T>::kKC;
+    constexpr int kDPieces = kKC * kStemBN / kPiece / 256;              // 16-byte pieces of D per thread and chunk (2)
+    extern __shared__ __attribute__((aligned(16))) uint8_t sh[];       // [kKC rows of U][kKC rows of D], rows = positions
+    const uint32_t pitch_u = stem_pitch_u(G.Jpad, sizeof(T)), pitch_d = stem_pitch_d(sizeof(T));
+    uint8_t* const Ush = sh;
+    uint8_t* const Dsh = sh + (size_t)kKC * pitch_u;
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave = tid >> 6;
+    const uint32_t tiles_c = (C + kStemBN - 1) / kStemBN;
+    const uint32_t tile_c = blockIdx.x % tiles_c, part = (blockIdx.x / tiles_c) % parts, z = blockIdx.x / (tiles_c * parts);
+    const uint32_t P = G.Ho * G.Wo, n_chunks = (P + kKC - 1) / kKC;
+    const uint32_t per_part = (n_chunks + parts - 1) / parts;
+    const uint32_t q_begin = min(n_chunks, part * per_part), q_end = min(n_chunks, q_begin + per_part);
+    const T* act_z = act + (size_t)z * G.H * G.W * G.Cin;
+    const T* D_z = D + (size_t)z * P * C;
+    const uint32_t c0 = tile_c * kStemBN;
+
+    // ---- what this thread fetches per chunk; the chunk after the current one waits in registers ----
+    // D: piece i of the thread is row pl = e / (64 / kPiece), columns c0 + kPiece (e % (64 / kPiece)) .. + kPiece - 1,
+    // e = tid + 256 i.
+    // U: thread tid < groups * Jpad (groups = kG <= 256 / Jpad) owns column j = tid % Jpad of the chunk's [kKC, Jpad] block and
+    // the positions pg, pg + groups, ... (pg = tid / Jpad); the column's tap and channel are fixed, so what is left per
+    // element is the position's (y, x), carried along from the chunk's first position, and the bounds tests.
+    constexpr int kUMax = kKC / kG;                                     // elements of a thread per chunk
+    constexpr uint32_t groups = kG;
+    u4v d_next[kDPieces];
+    T u_next[kUMax];
+    const uint32_t uj = tid % G.Jpad, upg = tid / G.Jpad;
+    const uint32_t n_u = upg < groups ? (uint32_t)kUMax : 0u;
+    const bool u_col = uj < G.J;
+    const uint32_t utap = uj / G.Cin, uci = uj - utap * G.Cin, uky = utap / G.kw, ukx = utap - uky * G.kw;
+    const int32_t dy = (int32_t)uky - (int32_t)G.ph, dx = (int32_t)ukx - (int32_t)G.pw;
+    auto fetch = [&](uint32_t q) {
+        const uint32_t p0 = q * kKC;
+#pragma unroll
+        for (int i = 0; i < kDPieces; ++i) {
+            constexpr uint32_t ppr = kStemBN / kPiece;                  // pieces per row
+            const uint32_t e = tid + 256u * i, pl = e / ppr, col = c0 + (e % ppr) * kPiece, p = p0 + pl;
+            d_next[i] = (u4v){0u, 0u, 0u, 0u};
+            if (p < P && col < C) d_next[i] = *reinterpret_cast<const u4v*>(D_z + (size_t)p * C + col);   // C is a multiple of kPiece
+        }
+        const uint32_t y0 = p0 / G.Wo, x0 = p0 - y0 * G.Wo;             // (uniform)
+        uint32_t y = y0, x = x0 + upg;
+#pragma unroll
+        for (int i = 0; i < kUMax; ++i) {
+            u_next[i] = (T)0;
+            if ((uint32_t)i < n_u) {
+                while (x >= G.Wo) { x -= G.Wo; ++y; }
+                const uint32_t iy = (uint32_t)((int32_t)(y * G.sh) + dy), ix = (uint32_t)((int32_t)(x * G.sw) + dx);   // huge when negative
+                if (u_col && y < G.Ho && iy < G.H && ix < G.W) u_next[i] = act_z[((size_t)iy * G.W + ix) * G.Cin + uci];
+                x += groups;
+            }
+        }
+    };
+    auto stage = [&]() {                                                // registers -> LDS, rows = positions
+#pragma unroll
+        for (int i = 0; i < kDPieces; ++i) {
+            constexpr uint32_t ppr = kStemBN / kPiece;
+            const uint32_t e = tid + 256u * i, pl = e / ppr, cl = (e % ppr) * kPiece;
+            *reinterpret_cast<u4v*>(Dsh + pl * pitch_d + cl * sizeof(T)) = d_next[i];
+        }
+#pragma unroll
+        for (int i = 0; i < kUMax; ++i)
+            if ((uint32_t)i < n_u) *reinterpret_cast<T*>(Ush + (upg + (uint32_t)i * groups) * pitch_u + uj * sizeof(T)) = u_next[i];
+    };
+
+    // ---- tiles of the workgroup's [Jpad, 64] block: 32 x 32 each, dealt to the four waves ----
+    const uint32_t n_jt = G.Jpad / 32u, n_tiles = n_jt * 2u;
+    f16v acc[3];
+#pragma unroll
+    for (int t = 0; t < 3; ++t) acc[t] = (f16v){0};
+    // bfloat16: the transposing LDS read hands lane l the 8 consecutive positions 8 (l / 32) .. + 7 of column l % 32 from
+    // rows that are positions: within 16 lanes, lane r points at row r / 4, columns 4 (r % 4) .. + 3
+    const uint32_t r16 = lane & 15u, g16 = lane >> 4, mhalf = g16 & 1u, khalf = g16 >> 1;
+    const uint32_t frow = khalf * 8u + (r16 >> 2), fcol = mhalf * 16u + (r16 & 3u) * 4u;
+
+    if (q_begin < q_end) fetch(q_begin);
+    for (uint32_t q = q_begin; q < q_end; ++q) {
+        __syncthreads();                                                // the previous chunk's fragments have been read
+        stage();
+        __syncthreads();
+        if (q + 1 < q_end) fetch(q + 1);                                // in flight during the multiplications
+#pragma unroll
+        for (int t = 0; t < 3; ++t) {
+            const uint32_t tile = wave + 4u * t;
+            if (tile < n_tiles) {                                       // wave-uniform
+                const uint32_t jt = tile >> 1, ct = tile & 1u;
+                if constexpr (sizeof(T) == 2) {
+                    const uint8_t* ua = Ush + frow * pitch_u + (jt * 32u + fcol) * 2u;
+                    const uint8_t* db = Dsh + frow * pitch_d + (ct * 32u + fcol) * 2u;
+#pragma unroll
+                    for (int ks = 0; ks < kKC / 16; ++ks) {
+                        const s4v alo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(ua + ks * 16 * pitch_u));
+                        const s4v ahi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(ua + (ks * 16 + 4) * pitch_u));
+                        const s4v blo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(db + ks * 16 * pitch_d));
+                        const s4v bhi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s4v_ptr)(db + (ks * 16 + 4) * pitch_d));
+                        const s8v av = {alo[0], alo[1], alo[2], alo[3], ahi[0], ahi[1], ahi[2], ahi[3]};
+                        const s8v bv = {blo[0], blo[1], blo[2], blo[3], bhi[0], bhi[1], bhi[2], bhi[3]};
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8v, av), __builtin_bit_cast(bf8v, bv), acc[t], 0, 0, 0);
+                    }
+                } else {
+                    // float32: lane l supplies U[k = l / 32][m = l % 32] and D[k][n = l % 32] of each pair of positions
+                    const uint8_t* ua = Ush + (lane >> 5) * pitch_u + (jt * 32u + (lane & 31u)) * 4u;
+                    const uint8_t* db = Dsh + (lane >> 5) * pitch_d + (ct * 32u + (lane & 31u)) * 4u;
+#pragma unroll
+                    for (int ks = 0; ks < kKC / 2; ++ks) {
+                        const float a = *reinterpret_cast<const float*>(ua + ks * 2 * pitch_u);
+                        const float b = *reinterpret_cast<const float*>(db + ks * 2 * pitch_d);
+                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[t], 0, 0, 0);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- the part's unsquared product to the workspace: plane (z, part) of [J, C] ----
+    float* out = ws + ((size_t)z * parts + part) * (size_t)G.J * C;
+#pragma unroll
+    for (int t = 0; t < 3; ++t) {
+        const uint32_t tile = wave + 4u * t;
+        if (tile < n_tiles) {
+            const uint32_t jt = tile >> 1, ct = tile & 1u;
+            const uint32_t col = c0 + ct * 32u + (lane & 31u);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const uint32_t row = jt * 32u + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                if (row < G.J && col < C) out[(size_t)row * C + col] = acc[t][i];
+            }
+        }
+    }
+}
+
+bool conv_stem_supported(int dtype, uint32_t Cin, uint32_t C, uint32_t kh, uint32_t kw) {
+    const uint32_t piece = dtype == VGC_BF16 ? 8u : 4u;
+    const uint64_t J = (uint64_t)kh * kw * Cin;
+    // 5 row tiles x 2 column tiles are at most three tiles per wave
+    return (dtype == VGC_BF16 || dtype == VGC_F32) && Cin % piece != 0 && C % piece == 0 && J <= (uint64_t)kStemJMax;
+}
+
+// Parts the positions of a sample are split into: about 4096 workgroups, at least four chunks per part.
+static uint32_t stem_parts(int dtype, uint32_t B, uint32_t P, uint32_t C) {
+    const uint64_t tiles_c = (C + kStemBN - 1) / kStemBN;
+    const uint32_t kc = dtype == VGC_BF16 ? StemElem<uint16_t>::kKC : StemElem<float>::kKC;
+    const uint32_t n_chunks = (P + kc - 1) / kc;
+    uint64_t parts = 4096 / ((uint64_t)B * tiles_c);
+    if (parts > n_chunks / 4) parts = n_chunks / 4;
+    return parts < 1 ? 1u : (uint32_t)parts;
+}
+
+size_t conv_stem_workspace_bytes(int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
+    return (size_t)B * stem_parts(dtype, B, P, C) * J * C * sizeof(float);
+}
+
+int launch_conv_stem(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
+                     uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw, uint32_t Ho, uint32_t Wo,
+                     float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    const uint32_t P = Ho * Wo, J = kh * kw * Cin;
+    if (!workspace || workspace_bytes < conv_stem_workspace_bytes(dtype, B, P, J, C)) {
+        set_error("vgc_sqgrad_conv2d: a layer whose input channels are not a multiple of 16 bytes needs the workspace "
+                  "vgc_sqgrad_conv2d_workspace_bytes() asks for");
+        return VGC_ERR_SIZE;
+    }
+    const uint32_t parts = stem_parts(dtype, B, P, C);
+    const uint64_t nblk = (uint64_t)B * parts * ((C + kStemBN - 1) / kStemBN);
+    if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad_conv2d: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
+    StemGeom G;
+    G.H = H; G.W = W; G.Cin = Cin; G.kw = kw; G.sh = sh; G.sw = sw; G.ph = ph; G.pw = pw; G.Ho = Ho; G.Wo = Wo;
+    G.J = J; G.Jpad = (J + 31u) / 32u * 32u;
+    float* ws = static_cast<float*>(workspace);
+    const uint32_t gmax = 256u / G.Jpad, kg = gmax >= 8 ? 8u : (gmax >= 4 ? 4u : (gmax >= 2 ? 2u : 1u));
+#define VGC_LAUNCH_STEM(T_, KG_)                                                                                              \
+    hipLaunchKernelGGL((k_conv_stem<T_, KG_>), dim3((uint32_t)nblk), dim3(256),                                               \
+                       (size_t)StemElem<T_>::kKC * (stem_pitch_u(G.Jpad, sizeof(T_)) + stem_pitch_d(sizeof(T_))), stream,     \
+                       (const T_*)act, (const T_*)D, B, C, G, parts, ws)
+    if (dtype == VGC_BF16) {
+        if (kg == 8) VGC_LAUNCH_STEM(uint16_t, 8); else if (kg == 4) VGC_LAUNCH_STEM(uint16_t, 4);
+        else if (kg == 2) VGC_LAUNCH_STEM(uint16_t, 2); else VGC_LAUNCH_STEM(uint16_t, 1);
+    } else {
+        if (kg == 8) VGC_LAUNCH_STEM(float, 8); else if (kg == 4) VGC_LAUNCH_STEM(float, 4);
+        else if (kg == 2) VGC_LAUNCH_STEM(float, 2); else VGC_LAUNCH_STEM(float, 1);
+    }
+#undef VGC_LAUNCH_STEM
+    launch_sqgrad_reduce_parts(ws, B, parts, (size_t)J * C, c, c * c, g_out, s_out, stream);
+    return hip_check(hipGetLastError(), "launch k_conv_stem");
+}
+
+}  // namespace vgc

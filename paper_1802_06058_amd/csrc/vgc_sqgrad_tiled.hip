@@ -1044,6 +1044,9 @@ bool conv2d_supported(int dtype, uint32_t H, uint32_t W, uint32_t Cin, uint32_t 
 int launch_conv2d(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
                   uint32_t kh, uint32_t kw, uint32_t sh, uint32_t sw, uint32_t ph, uint32_t pw, uint32_t Ho, uint32_t Wo,
                   float c, float* g_out, float* s_out, void* workspace, size_t workspace_bytes, hipStream_t stream) {
+    if (conv_stem_supported(dtype, Cin, C, kh, kw))
+        return launch_conv_stem(dtype, act, D, B, H, W, Cin, C, kh, kw, sh, sw, ph, pw, Ho, Wo, c, g_out, s_out, workspace,
+                                workspace_bytes, stream);
     ConvGeom G{};
     G.H = H; G.W = W; G.Cin = Cin; G.kw = kw; G.sh = sh; G.sw = sw; G.ph = ph; G.pw = pw; G.Ho = Ho; G.Wo = Wo;
     if (dtype == VGC_F32) return launch_conv2d_f32(act, D, B, Ho * Wo, kh * kw * Cin, C, c, g_out, s_out, workspace, workspace_bytes, G, stream);

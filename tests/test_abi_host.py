@@ -126,8 +126,11 @@ def test_conv2d_and_update_argument_checks_need_no_gpu():
     fake = C.c_void_p(0x1000)                                     # never dereferenced: every call below is rejected first
     conv = lambda dtype, Cin, Cc, kh, ph: lib.vgc_sqgrad_conv2d(dtype, fake, fake, 2, 8, 8, Cin, Cc, kh, 3, 1, 1, ph, 1, 1.0,
                                                                  None, fake, None, 0, None)
-    assert conv(vgc.BF16, 12, 8, 3, 1) == -2 and b"multiples of 16 bytes" in lib.vgc_last_error()
+    # input channels that are not a multiple of 16 bytes: a first layer's kernel takes them while kh kw Cin <= 160, with a workspace
+    assert conv(vgc.BF16, 12, 8, 3, 1) == -2 and b"needs the workspace" in lib.vgc_last_error()
+    assert conv(vgc.BF16, 12, 8, 5, 1) == -2 and b"multiple of 16 bytes" in lib.vgc_last_error()      # kh kw Cin = 180
     assert conv(vgc.F32, 6, 8, 3, 1) == -2
+    assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 3, 64, 3, 3, 1, 1, 1, 1) == 64 * 64 * 27 * 64 * 4
     assert conv(vgc.BF16, 8, 8, 3, 3) == -2 and b"pad" in lib.vgc_last_error()
     assert conv(9, 8, 8, 3, 1) == -4
     assert lib.vgc_sqgrad_conv2d(vgc.BF16, None, fake, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, None, fake, None, 0, None) == -1
@@ -135,11 +138,11 @@ def test_conv2d_and_update_argument_checks_need_no_gpu():
     ok = vgc.Conv2dLayer(vgc.BF16, 0x1000, 0x1000, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, None, 0x1000, None, 0)
     odd = vgc.Conv2dLayer(vgc.BF16, 0x1000, 0x1000, 2, 8, 8, 12, 8, 3, 3, 1, 1, 1, 1, 1.0, None, 0x1000, None, 0)
     arr2 = (vgc.Conv2dLayer * 2)(ok, odd)
-    assert lib.vgc_sqgrad_conv2d_batch(C.cast(arr2, C.c_void_p), 2, None) == -2 and b"multiples of 16 bytes" in lib.vgc_last_error()
+    assert lib.vgc_sqgrad_conv2d_batch(C.cast(arr2, C.c_void_p), 2, None) == -2 and b"needs the workspace" in lib.vgc_last_error()
     assert lib.vgc_sqgrad_conv2d_batch(None, 2, None) == -1
     # the workspace query is pure host code: a layer with few tiles and many positions wants room for partial products
     assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 64, 64, 3, 3, 1, 1, 1, 1) > 0
-    assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 6, 64, 3, 3, 1, 1, 1, 1) == 0     # unsupported shape
+    assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 6, 64, 7, 7, 1, 1, 1, 1) == 0     # unsupported shape: 6 channels, 7 x 7
 
     arr, n = _groups([100, 200])
     opt = vgc.Optimizer(vgc.MOMENTUM_SGD, 0.1, 1.5, 0.9, 0.999, 1e-8, 1)

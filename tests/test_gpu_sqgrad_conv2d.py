@@ -218,6 +218,49 @@ def test_conv2d_tap_kernel_matches_oracle(dev, geom):
     assert _rel_s(s_nows, s64) <= TOL
 
 
+STEM_GEOMS = [  # B, H, W, Cin, C, kh, kw, stride, pad: first layers, input channels not a multiple of 16 bytes
+    (4, 12, 12, 3, 64, 3, 3, (1, 1), (1, 1)),      # an RGB input under a 3x3 filter
+    (4, 20, 18, 3, 64, 7, 7, (2, 2), (3, 3)),      # ... under a 7x7 filter with stride 2: J = 147, five row tiles
+    (5, 9, 11, 3, 24, 3, 3, (1, 1), (1, 1)),       # fewer than 64 output channels
+    (4, 30, 31, 1, 8, 5, 5, (1, 1), (2, 2)),       # one input channel
+    (4, 10, 10, 6, 72, 3, 3, (1, 1), (1, 1)),      # six channels, two ragged column tiles
+    (8, 40, 40, 3, 64, 3, 3, (1, 1), (1, 1)),      # 1600 positions: split into parts
+    (6, 33, 29, 2, 40, 4, 3, (3, 2), (0, 1)),      # two channels, uneven strides
+]
+
+
+@pytest.mark.parametrize("prec", ["bf16", "f32"])
+@pytest.mark.parametrize("geom", STEM_GEOMS)
+def test_conv2d_first_layer_matches_oracle(dev, geom, prec):
+    """Layers whose input channels are not a multiple of 16 bytes (the kernel that gathers the patch rows element by
+    element): every output of s against the oracle at the stated tolerance, g against the magnitudes summed, s alone
+    equal to s with g; without the workspace the call is refused."""
+    from paper_1802_06058_amd import vgc
+    B, H, Wd, Cin, C, kh, kw, stride, pad = geom
+    TOL = RTOL[prec]
+    Ho, Wo = O.conv_out_size(H, kh, stride[0], pad[0]), O.conv_out_size(Wd, kw, stride[1], pad[1])
+    A, D = W.conv2d_inputs(45, geom[:7], B, H, Wd, Cin, Ho, Wo, C, d_sigma=0.02, bf16=prec == "bf16")
+    if prec == "bf16":
+        Aw, Dw = W.bf16_bits_to_f32(A).astype(np.float64), W.bf16_bits_to_f32(D).astype(np.float64)
+    else:
+        Aw, Dw = A.astype(np.float64), D.astype(np.float64)
+    c = 1.0 / B
+    g64, s64 = O.sqgrad_conv_nhwc(Aw, Dw, kh, kw, stride, pad, c)
+    Uabs = _patches(np.abs(Aw), kh, kw, stride, pad, Ho, Wo)
+    absG = np.einsum("zpj,zpc->jc", Uabs, np.abs(Dw).reshape(B, Ho * Wo, C)) * c
+    g, s = _run(A, D, kh, kw, stride, pad, c, dev)
+    assert np.isfinite(g).all() and np.isfinite(s).all()
+    assert (np.abs(g - g64) / np.maximum(absG, 1e-300)).max() <= TOL
+    tag = f"conv2d {prec} first layer {geom}"
+    OBSERVED[tag] = _rel_s(s, s64)
+    assert OBSERVED[tag] <= TOL, f"s relative error {OBSERVED[tag]:.3e}"
+    assert np.all(s[s64 == 0] == 0)
+    _, s2 = _run(A, D, kh, kw, stride, pad, c, dev, want_g=False)
+    assert np.array_equal(s2, s)
+    with pytest.raises(vgc.VgcError):
+        _run(A, D, kh, kw, stride, pad, c, dev, use_workspace=False)
+
+
 def test_zz_report_observed_errors():
     """Not a check: prints the largest relative error of s each case showed (run with -s to see it)."""
     for tag, worst in sorted(OBSERVED.items()):
@@ -234,8 +277,8 @@ def test_conv2d_rejects_what_it_cannot_do(dev):
     args = lambda dtype, Cin, C, kh, ph: (dtype, a.data_ptr(), d.data_ptr(), 2, 8, 8, Cin, C, kh, 3, 1, 1, ph, 1, 1.0, None,
                                           s.data_ptr(), None, 0, None)
     assert lib.vgc_sqgrad_conv2d(*args(7, 8, 8, 3, 1)) == -4                # unknown dtype
-    assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 4, 8, 3, 1)) == -2         # Cin not a multiple of 8 bfloat16
-    assert lib.vgc_sqgrad_conv2d(*args(vgc.F32, 6, 8, 3, 1)) == -2          # Cin not a multiple of 4 floats
+    assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 4, 8, 3, 1)) == -2         # Cin not a multiple of 8 bfloat16: needs the workspace
+    assert lib.vgc_sqgrad_conv2d(*args(vgc.F32, 6, 8, 3, 1)) == -2          # Cin not a multiple of 4 floats: the same
     assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 8, 8, 3, 3)) == -2         # padding as large as the kernel
     assert lib.vgc_sqgrad_conv2d(*args(vgc.BF16, 8, 8, 0, 0)) == -2         # empty kernel
     assert float(s.abs().sum()) == 0.0
