@@ -27,21 +27,23 @@ struct StemGeom {
     uint32_t H, W, Cin, kw, sh, sw, ph, pw, Ho, Wo, J, Jpad;
 };
 
-// Element type T (bfloat16 bits or float): elements per 16-byte piece, positions per chunk.
-template <typename T> struct StemElem;
-template <> struct StemElem<uint16_t> { static constexpr int kPiece = 8, kKC = 64; };
-template <> struct StemElem<float> { static constexpr int kPiece = 4, kKC = 32; };
+// Positions per chunk: as many as keep the elements a thread holds in registers for the next chunk few
+// (16 bytes of D per 256 / (64 / piece) positions, one element of U per position group).
+__host__ __device__ constexpr int stem_kc(int esize, int jt) {
+    return esize == 2 ? (jt == 1 ? 128 : (jt == 2 ? 64 : 32)) : (jt == 1 ? 64 : 32);
+}
 
 // LDS row pitches in bytes (rows are positions; 16 bytes of padding keep four consecutive rows off each other's banks)
 __host__ __device__ inline uint32_t stem_pitch_u(uint32_t Jpad, uint32_t esize) { return Jpad * esize + 16u; }
 __host__ __device__ inline uint32_t stem_pitch_d(uint32_t esize) { return kStemBN * esize + 16u; }
 
-// kG: position groups = 256 / Jpad rounded down to a power of two (8, 4, 2 or 1): how many threads share a column of U
-template <typename T, int kG>
+// kJT = Jpad / 32 (1..5) fixes the position groups kG = 256 / Jpad rounded down to a power of two (how many threads
+// share a column of U) and the 32 x 32 tiles a wave holds at most, kT = ceil(2 kJT / 4).
+template <typename T, int kJT>
 __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, const T* __restrict__ D, uint32_t B, uint32_t C,
                                                    StemGeom G, uint32_t parts, float* __restrict__ ws) {
-    constexpr int kPiece = StemElem<T>::kPiece, kKC = StemElem<T>::kKC;
-    constexpr int kDPieces = kKC * kStemBN / kPiece / 256;              // 16-byte pieces of D per thread and chunk (2)
+    constexpr int kPiece = 16 / (int)sizeof(T), kKC = stem_kc((int)sizeof(T), kJT);
+    constexpr int kDPieces = kKC * kStemBN / kPiece / 256;              // 16-byte pieces of D per thread and chunk
     extern __shared__ __attribute__((aligned(16))) uint8_t sh[];       // [kKC rows of U][kKC rows of D], rows = positions
     const uint32_t pitch_u = stem_pitch_u(G.Jpad, sizeof(T)), pitch_d = stem_pitch_d(sizeof(T));
     uint8_t* const Ush = sh;
@@ -62,6 +64,8 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
     // U: thread tid < groups * Jpad (groups = kG <= 256 / Jpad) owns column j = tid % Jpad of the chunk's [kKC, Jpad] block and
     // the positions pg, pg + groups, ... (pg = tid / Jpad); the column's tap and channel are fixed, so what is left per
     // element is the position's (y, x), carried along from the chunk's first position, and the bounds tests.
+    constexpr int kG = kJT == 1 ? 8 : (kJT == 2 ? 4 : (kJT <= 4 ? 2 : 1));
+    constexpr int kT = (2 * kJT + 3) / 4;
     constexpr int kUMax = kKC / kG;                                     // elements of a thread per chunk
     constexpr uint32_t groups = kG;
     u4v d_next[kDPieces];
@@ -107,9 +111,9 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
 
     // ---- tiles of the workgroup's [Jpad, 64] block: 32 x 32 each, dealt to the four waves ----
     const uint32_t n_jt = G.Jpad / 32u, n_tiles = n_jt * 2u;
-    f16v acc[3];
+    f16v acc[kT];
 #pragma unroll
-    for (int t = 0; t < 3; ++t) acc[t] = (f16v){0};
+    for (int t = 0; t < kT; ++t) acc[t] = (f16v){0};
     // bfloat16: the transposing LDS read hands lane l the 8 consecutive positions 8 (l / 32) .. + 7 of column l % 32 from
     // rows that are positions: within 16 lanes, lane r points at row r / 4, columns 4 (r % 4) .. + 3
     const uint32_t r16 = lane & 15u, g16 = lane >> 4, mhalf = g16 & 1u, khalf = g16 >> 1;
@@ -122,7 +126,7 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
         __syncthreads();
         if (q + 1 < q_end) fetch(q + 1);                                // in flight during the multiplications
 #pragma unroll
-        for (int t = 0; t < 3; ++t) {
+        for (int t = 0; t < kT; ++t) {
             const uint32_t tile = wave + 4u * t;
             if (tile < n_tiles) {                                       // wave-uniform
                 const uint32_t jt = tile >> 1, ct = tile & 1u;
@@ -157,7 +161,7 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
     // ---- the part's unsquared product to the workspace: plane (z, part) of [J, C] ----
     float* out = ws + ((size_t)z * parts + part) * (size_t)G.J * C;
 #pragma unroll
-    for (int t = 0; t < 3; ++t) {
+    for (int t = 0; t < kT; ++t) {
         const uint32_t tile = wave + 4u * t;
         if (tile < n_tiles) {
             const uint32_t jt = tile >> 1, ct = tile & 1u;
@@ -179,9 +183,9 @@ bool conv_stem_supported(int dtype, uint32_t Cin, uint32_t C, uint32_t kh, uint3
 }
 
 // Parts the positions of a sample are split into: about 4096 workgroups, at least four chunks per part.
-static uint32_t stem_parts(int dtype, uint32_t B, uint32_t P, uint32_t C) {
+static uint32_t stem_parts(int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
     const uint64_t tiles_c = (C + kStemBN - 1) / kStemBN;
-    const uint32_t kc = dtype == VGC_BF16 ? StemElem<uint16_t>::kKC : StemElem<float>::kKC;
+    const uint32_t kc = (uint32_t)stem_kc(dtype == VGC_BF16 ? 2 : 4, (int)((J + 31u) / 32u));
     const uint32_t n_chunks = (P + kc - 1) / kc;
     uint64_t parts = 4096 / ((uint64_t)B * tiles_c);
     if (parts > n_chunks / 4) parts = n_chunks / 4;
@@ -189,7 +193,7 @@ static uint32_t stem_parts(int dtype, uint32_t B, uint32_t P, uint32_t C) {
 }
 
 size_t conv_stem_workspace_bytes(int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
-    return (size_t)B * stem_parts(dtype, B, P, C) * J * C * sizeof(float);
+    return (size_t)B * stem_parts(dtype, B, P, J, C) * J * C * sizeof(float);
 }
 
 int launch_conv_stem(int dtype, const void* act, const void* D, uint32_t B, uint32_t H, uint32_t W, uint32_t Cin, uint32_t C,
@@ -201,24 +205,26 @@ int launch_conv_stem(int dtype, const void* act, const void* D, uint32_t B, uint
                   "vgc_sqgrad_conv2d_workspace_bytes() asks for");
         return VGC_ERR_SIZE;
     }
-    const uint32_t parts = stem_parts(dtype, B, P, C);
+    const uint32_t parts = stem_parts(dtype, B, P, J, C);
     const uint64_t nblk = (uint64_t)B * parts * ((C + kStemBN - 1) / kStemBN);
     if (nblk > 0x7FFFFFFFull) { set_error("vgc_sqgrad_conv2d: shape exceeds the launch limit"); return VGC_ERR_SIZE; }
     StemGeom G;
     G.H = H; G.W = W; G.Cin = Cin; G.kw = kw; G.sh = sh; G.sw = sw; G.ph = ph; G.pw = pw; G.Ho = Ho; G.Wo = Wo;
     G.J = J; G.Jpad = (J + 31u) / 32u * 32u;
     float* ws = static_cast<float*>(workspace);
-    const uint32_t gmax = 256u / G.Jpad, kg = gmax >= 8 ? 8u : (gmax >= 4 ? 4u : (gmax >= 2 ? 2u : 1u));
-#define VGC_LAUNCH_STEM(T_, KG_)                                                                                              \
-    hipLaunchKernelGGL((k_conv_stem<T_, KG_>), dim3((uint32_t)nblk), dim3(256),                                               \
-                       (size_t)StemElem<T_>::kKC * (stem_pitch_u(G.Jpad, sizeof(T_)) + stem_pitch_d(sizeof(T_))), stream,     \
+    const uint32_t jt = G.Jpad / 32u;
+#define VGC_LAUNCH_STEM(T_, JT_)                                                                                              \
+    hipLaunchKernelGGL((k_conv_stem<T_, JT_>), dim3((uint32_t)nblk), dim3(256),                                               \
+                       (size_t)stem_kc((int)sizeof(T_), JT_) * (stem_pitch_u(G.Jpad, sizeof(T_)) + stem_pitch_d(sizeof(T_))), stream, \
                        (const T_*)act, (const T_*)D, B, C, G, parts, ws)
     if (dtype == VGC_BF16) {
-        if (kg == 8) VGC_LAUNCH_STEM(uint16_t, 8); else if (kg == 4) VGC_LAUNCH_STEM(uint16_t, 4);
-        else if (kg == 2) VGC_LAUNCH_STEM(uint16_t, 2); else VGC_LAUNCH_STEM(uint16_t, 1);
+        if (jt == 1) VGC_LAUNCH_STEM(uint16_t, 1); else if (jt == 2) VGC_LAUNCH_STEM(uint16_t, 2);
+        else if (jt == 3) VGC_LAUNCH_STEM(uint16_t, 3); else if (jt == 4) VGC_LAUNCH_STEM(uint16_t, 4);
+        else VGC_LAUNCH_STEM(uint16_t, 5);
     } else {
-        if (kg == 8) VGC_LAUNCH_STEM(float, 8); else if (kg == 4) VGC_LAUNCH_STEM(float, 4);
-        else if (kg == 2) VGC_LAUNCH_STEM(float, 2); else VGC_LAUNCH_STEM(float, 1);
+        if (jt == 1) VGC_LAUNCH_STEM(float, 1); else if (jt == 2) VGC_LAUNCH_STEM(float, 2);
+        else if (jt == 3) VGC_LAUNCH_STEM(float, 3); else if (jt == 4) VGC_LAUNCH_STEM(float, 4);
+        else VGC_LAUNCH_STEM(float, 5);
     }
 #undef VGC_LAUNCH_STEM
     launch_sqgrad_reduce_parts(ws, B, parts, (size_t)J * C, c, c * c, g_out, s_out, stream);

@@ -534,6 +534,7 @@ __global__ __launch_bounds__(256) void k_sqgrad_reduce_parts(const float* __rest
     if (i < JC) {
         for (uint32_t z = q; z < B; z += 16) {
             FloatVec<kV> G = {};
+#pragma unroll 4                                     // (the loads of four parts in flight; the additions keep their order)
             for (uint32_t k = 0; k < split_p; ++k) {
                 const FloatVec<kV> part = load_vec<kV>(ws + ((size_t)z * split_p + k) * JC + i);
                 for (int e = 0; e < kV; ++e) G.v[e] += part.v[e];
