@@ -495,8 +495,8 @@ def _timed(fn, warm_ms=150.0, timed_ms=100.0):
 
 def _statistic_of_layers(dev, dt, B, convs, fcs, counts=None):
     """s of every layer of a network: convolutions (cin, cout, input extent, kernel, stride, pad) from their NHWC
-    inputs, those whose channel count is not a multiple of 16 bytes through a patch matrix (columns padded to a
-    multiple of 16 bytes), FC layers in the FC form.  counts[i] says how often layer i occurs in the network (its
+    inputs (a layer whose channel count is not a multiple of 16 bytes and whose kh kw Cin exceeds 160 would go through a
+    patch matrix with columns padded to a multiple of 16 bytes; the two networks here have none), FC layers in the FC form.  counts[i] says how often layer i occurs in the network (its
     inputs are shared, every occurrence has outputs and a workspace of its own).  Each distinct layer is timed
     alone; then the calls of the whole network are timed in one sweep, on one stream, spread over four by the caller
     (the layers are independent, so kernels of different layers can fill each other's tails), and with the NHWC
@@ -516,7 +516,7 @@ def _statistic_of_layers(dev, dt, B, convs, fcs, counts=None):
         D = rnd(B, so, so, cout) * 1e-3
         J = k * k * cin
         mine = []
-        if cin % piece == 0:
+        if cin % piece == 0 or J <= 160:                                # (a first layer on few channels has a kernel of its own)
             A = rnd(B, sp, sp, cin)
             nb = vgc.sqgrad_conv2d_workspace_bytes(code, B, sp, sp, cin, cout, k, k, (st, st), (pd, pd))
             for _ in range(cnt):

@@ -37,13 +37,18 @@ __host__ __device__ constexpr int stem_kc(int esize, int jt) {
 __host__ __device__ inline uint32_t stem_pitch_u(uint32_t Jpad, uint32_t esize) { return Jpad * esize + 16u; }
 __host__ __device__ inline uint32_t stem_pitch_d(uint32_t esize) { return kStemBN * esize + 16u; }
 
-// kJT = Jpad / 32 (1..5) fixes the position groups kG = 256 / Jpad rounded down to a power of two (how many threads
-// share a column of U) and the 32 x 32 tiles a wave holds at most, kT = ceil(2 kJT / 4).
+// kJT = Jpad / 32 (1..5) fixes the workgroup's size (four waves, eight from three row tiles on: ten 32 x 32 tiles on
+// four waves would be three on the slowest), the position groups kG = threads / Jpad rounded down to a power of two
+// (how many threads share a column of U) and the tiles a wave holds at most, kT = ceil(2 kJT / waves).
+__host__ __device__ constexpr int stem_threads(int jt) { return jt >= 3 ? 512 : 256; }
+
 template <typename T, int kJT>
-__global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, const T* __restrict__ D, uint32_t B, uint32_t C,
+__global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __restrict__ act, const T* __restrict__ D, uint32_t B, uint32_t C,
                                                    StemGeom G, uint32_t parts, float* __restrict__ ws) {
     constexpr int kPiece = 16 / (int)sizeof(T), kKC = stem_kc((int)sizeof(T), kJT);
-    constexpr int kDPieces = kKC * kStemBN / kPiece / 256;              // 16-byte pieces of D per thread and chunk
+    constexpr int kNT = stem_threads(kJT), kWaves = kNT / 64;
+    constexpr int kDTotal = kKC * kStemBN / kPiece;                     // 16-byte pieces of D per chunk
+    constexpr int kDPieces = (kDTotal + kNT - 1) / kNT;                 // ... per thread
     extern __shared__ __attribute__((aligned(16))) uint8_t sh[];       // [kKC rows of U][kKC rows of D], rows = positions
     const uint32_t pitch_u = stem_pitch_u(G.Jpad, sizeof(T)), pitch_d = stem_pitch_d(sizeof(T));
     uint8_t* const Ush = sh;
@@ -60,12 +65,12 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
 
     // ---- what this thread fetches per chunk; the chunk after the current one waits in registers ----
     // D: piece i of the thread is row pl = e / (64 / kPiece), columns c0 + kPiece (e % (64 / kPiece)) .. + kPiece - 1,
-    // e = tid + 256 i.
-    // U: thread tid < groups * Jpad (groups = kG <= 256 / Jpad) owns column j = tid % Jpad of the chunk's [kKC, Jpad] block and
+    // e = tid + threads x i.
+    // U: thread tid < groups * Jpad (groups = kG <= threads / Jpad) owns column j = tid % Jpad of the chunk's [kKC, Jpad] block and
     // the positions pg, pg + groups, ... (pg = tid / Jpad); the column's tap and channel are fixed, so what is left per
     // element is the position's (y, x), carried along from the chunk's first position, and the bounds tests.
-    constexpr int kG = kJT == 1 ? 8 : (kJT == 2 ? 4 : (kJT <= 4 ? 2 : 1));
-    constexpr int kT = (2 * kJT + 3) / 4;
+    constexpr int kG = kJT == 1 ? 8 : (kJT == 2 ? 4 : (kJT <= 4 ? 4 : 2));   // 256 / 32, 256 / 64, 512 / 96, 512 / 128, 512 / 160
+    constexpr int kT = (2 * kJT + kWaves - 1) / kWaves;
     constexpr int kUMax = kKC / kG;                                     // elements of a thread per chunk
     constexpr uint32_t groups = kG;
     u4v d_next[kDPieces];
@@ -80,9 +85,9 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
 #pragma unroll
         for (int i = 0; i < kDPieces; ++i) {
             constexpr uint32_t ppr = kStemBN / kPiece;                  // pieces per row
-            const uint32_t e = tid + 256u * i, pl = e / ppr, col = c0 + (e % ppr) * kPiece, p = p0 + pl;
+            const uint32_t e = tid + (uint32_t)kNT * i, pl = e / ppr, col = c0 + (e % ppr) * kPiece, p = p0 + pl;
             d_next[i] = (u4v){0u, 0u, 0u, 0u};
-            if (p < P && col < C) d_next[i] = *reinterpret_cast<const u4v*>(D_z + (size_t)p * C + col);   // C is a multiple of kPiece
+            if (e < (uint32_t)kDTotal && p < P && col < C) d_next[i] = *reinterpret_cast<const u4v*>(D_z + (size_t)p * C + col);   // C is a multiple of kPiece
         }
         const uint32_t y0 = p0 / G.Wo, x0 = p0 - y0 * G.Wo;             // (uniform)
         uint32_t y = y0, x = x0 + upg;
@@ -101,15 +106,15 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
 #pragma unroll
         for (int i = 0; i < kDPieces; ++i) {
             constexpr uint32_t ppr = kStemBN / kPiece;
-            const uint32_t e = tid + 256u * i, pl = e / ppr, cl = (e % ppr) * kPiece;
-            *reinterpret_cast<u4v*>(Dsh + pl * pitch_d + cl * sizeof(T)) = d_next[i];
+            const uint32_t e = tid + (uint32_t)kNT * i, pl = e / ppr, cl = (e % ppr) * kPiece;
+            if (e < (uint32_t)kDTotal) *reinterpret_cast<u4v*>(Dsh + pl * pitch_d + cl * sizeof(T)) = d_next[i];
         }
 #pragma unroll
         for (int i = 0; i < kUMax; ++i)
             if ((uint32_t)i < n_u) *reinterpret_cast<T*>(Ush + (upg + (uint32_t)i * groups) * pitch_u + uj * sizeof(T)) = u_next[i];
     };
 
-    // ---- tiles of the workgroup's [Jpad, 64] block: 32 x 32 each, dealt to the four waves ----
+    // ---- tiles of the workgroup's [Jpad, 64] block: 32 x 32 each, dealt to the waves ----
     const uint32_t n_jt = G.Jpad / 32u, n_tiles = n_jt * 2u;
     f16v acc[kT];
 #pragma unroll
@@ -127,7 +132,7 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
         if (q + 1 < q_end) fetch(q + 1);                                // in flight during the multiplications
 #pragma unroll
         for (int t = 0; t < kT; ++t) {
-            const uint32_t tile = wave + 4u * t;
+            const uint32_t tile = wave + (uint32_t)kWaves * t;
             if (tile < n_tiles) {                                       // wave-uniform
                 const uint32_t jt = tile >> 1, ct = tile & 1u;
                 if constexpr (sizeof(T) == 2) {
@@ -162,7 +167,7 @@ __global__ __launch_bounds__(256) void k_conv_stem(const T* __restrict__ act, co
     float* out = ws + ((size_t)z * parts + part) * (size_t)G.J * C;
 #pragma unroll
     for (int t = 0; t < kT; ++t) {
-        const uint32_t tile = wave + 4u * t;
+        const uint32_t tile = wave + (uint32_t)kWaves * t;
         if (tile < n_tiles) {
             const uint32_t jt = tile >> 1, ct = tile & 1u;
             const uint32_t col = c0 + ct * 32u + (lane & 31u);
@@ -182,12 +187,12 @@ bool conv_stem_supported(int dtype, uint32_t Cin, uint32_t C, uint32_t kh, uint3
     return (dtype == VGC_BF16 || dtype == VGC_F32) && Cin % piece != 0 && C % piece == 0 && J <= (uint64_t)kStemJMax;
 }
 
-// Parts the positions of a sample are split into: about 4096 workgroups, at least four chunks per part.
+// Parts the positions of a sample are split into: about 2048 workgroups, at least four chunks per part.
 static uint32_t stem_parts(int dtype, uint32_t B, uint32_t P, uint32_t J, uint32_t C) {
     const uint64_t tiles_c = (C + kStemBN - 1) / kStemBN;
     const uint32_t kc = (uint32_t)stem_kc(dtype == VGC_BF16 ? 2 : 4, (int)((J + 31u) / 32u));
     const uint32_t n_chunks = (P + kc - 1) / kc;
-    uint64_t parts = 4096 / ((uint64_t)B * tiles_c);
+    uint64_t parts = 2048 / ((uint64_t)B * tiles_c);
     if (parts > n_chunks / 4) parts = n_chunks / 4;
     return parts < 1 ? 1u : (uint32_t)parts;
 }
@@ -214,7 +219,7 @@ int launch_conv_stem(int dtype, const void* act, const void* D, uint32_t B, uint
     float* ws = static_cast<float*>(workspace);
     const uint32_t jt = G.Jpad / 32u;
 #define VGC_LAUNCH_STEM(T_, JT_)                                                                                              \
-    hipLaunchKernelGGL((k_conv_stem<T_, JT_>), dim3((uint32_t)nblk), dim3(256),                                               \
+    hipLaunchKernelGGL((k_conv_stem<T_, JT_>), dim3((uint32_t)nblk), dim3(stem_threads(JT_)),                                 \
                        (size_t)stem_kc((int)sizeof(T_), JT_) * (stem_pitch_u(G.Jpad, sizeof(T_)) + stem_pitch_d(sizeof(T_))), stream, \
                        (const T_*)act, (const T_*)D, B, C, G, parts, ws)
     if (dtype == VGC_BF16) {

@@ -130,7 +130,7 @@ def test_conv2d_and_update_argument_checks_need_no_gpu():
     assert conv(vgc.BF16, 12, 8, 3, 1) == -2 and b"needs the workspace" in lib.vgc_last_error()
     assert conv(vgc.BF16, 12, 8, 5, 1) == -2 and b"multiple of 16 bytes" in lib.vgc_last_error()      # kh kw Cin = 180
     assert conv(vgc.F32, 6, 8, 3, 1) == -2
-    assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 3, 64, 3, 3, 1, 1, 1, 1) == 64 * 64 * 27 * 64 * 4
+    assert lib.vgc_sqgrad_conv2d_workspace_bytes(vgc.BF16, 64, 224, 224, 3, 64, 3, 3, 1, 1, 1, 1) == 64 * 32 * 27 * 64 * 4    # 32 parts per sample
     assert conv(vgc.BF16, 8, 8, 3, 3) == -2 and b"pad" in lib.vgc_last_error()
     assert conv(9, 8, 8, 3, 1) == -4
     assert lib.vgc_sqgrad_conv2d(vgc.BF16, None, fake, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 1, 1.0, None, fake, None, 0, None) == -1
