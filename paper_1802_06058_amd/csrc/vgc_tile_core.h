@@ -124,11 +124,16 @@ __device__ __forceinline__ void tile_core(const float (&G)[8], const float (&S)[
 
     // ---- send bitmap of the tile (bit i = element i) and the tile's largest truncated exponent ----
     uint32_t etr = 0;
+    if (kHybrid) {
+        // every sent element is staged as +-1.0f: the largest exponent field is that of 1.0f wherever anything is sent
+        etr = __ballot(sendmask != 0u) ? 127u : 0u;
+    } else {
 #pragma unroll
-    for (int e = 0; e < E; ++e)
-        if (sendmask & (1u << e)) etr = max(etr, (bits[e] & 0x7FFFFFFFu) >> 23);
+        for (int e = 0; e < E; ++e)
+            if (sendmask & (1u << e)) etr = max(etr, (bits[e] & 0x7FFFFFFFu) >> 23);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) etr = max(etr, (uint32_t)__shfl_xor((int)etr, off));
+        for (int off = 32; off > 0; off >>= 1) etr = max(etr, (uint32_t)__shfl_xor((int)etr, off));
+    }
     if (lane == 0) sh.wmax[wave] = etr;
 
     if (kVec) {
@@ -156,15 +161,22 @@ __device__ __forceinline__ void tile_core(const float (&G)[8], const float (&S)[
     // ---- tile-relative exponent code of every sent element (Section 4.4 rounding recipe) ----
     uint32_t entry[E];
     uint32_t stagedmask = 0;
+    if (kHybrid) {
+        // 1.0f rounds to 2^0 and the tile's maximum is 2^0: the relative code is 1 for every sent element
 #pragma unroll
-    for (int e = 0; e < E; ++e) {
-        const uint32_t ab = bits[e] & 0x7FFFFFFFu;
-        const uint32_t ernd = (ab + 0x00400000u) >> 23;       // add one at the mantissa's top bit, drop the mantissa
-        const uint32_t rel = etr + 1u - ernd;                 // >= 0 for sent elements: ernd <= own exponent + 1 <= etr + 1
-        const bool staged = ((sendmask >> e) & 1u) && ernd >= 1u && rel <= 8u;
-        const uint32_t pos = tile_element<kVec>(tid, e);
-        entry[e] = ((rel & 15u) << 12) | ((bits[e] >> 31) << 11) | pos;
-        stagedmask |= (staged ? 1u : 0u) << e;
+        for (int e = 0; e < E; ++e) entry[e] = (1u << 12) | ((bits[e] >> 31) << 11) | tile_element<kVec>(tid, e);
+        stagedmask = sendmask;
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) {
+            const uint32_t ab = bits[e] & 0x7FFFFFFFu;
+            const uint32_t ernd = (ab + 0x00400000u) >> 23;   // add one at the mantissa's top bit, drop the mantissa
+            const uint32_t rel = etr + 1u - ernd;             // >= 0 for sent elements: ernd <= own exponent + 1 <= etr + 1
+            const bool staged = ((sendmask >> e) & 1u) && ernd >= 1u && rel <= 8u;
+            const uint32_t pos = tile_element<kVec>(tid, e);
+            entry[e] = ((rel & 15u) << 12) | ((bits[e] >> 31) << 11) | pos;
+            stagedmask |= (staged ? 1u : 0u) << e;
+        }
     }
 
     // histogram of rel over the wave (uniform values; scalar popcounts)
