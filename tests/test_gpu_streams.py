@@ -25,6 +25,9 @@ LAYERS = [  # B, H, W, Cin, C, k, stride, pad, bf16
     (6, 28, 28, 32, 64, 3, 1, 1, False),
     (6, 14, 14, 64, 256, 1, 1, 0, False),
     (6, 56, 56, 16, 16, 3, 1, 1, False),
+    (8, 32, 32, 64, 64, 3, 1, 1, True),        # s alone (even index): the nine-tap kernel
+    (4, 24, 24, 3, 64, 3, 1, 1, True),         # a first layer on three channels, with g
+    (4, 30, 30, 3, 64, 7, 2, 3, False),        # ... in float32 under a 7 x 7 filter, s alone
 ]
 
 
