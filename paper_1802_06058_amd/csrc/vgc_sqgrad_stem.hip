@@ -45,6 +45,7 @@ __host__ __device__ constexpr int stem_threads(int jt) { return jt >= 3 ? 512 : 
 template <typename T, int kJT>
 __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __restrict__ act, const T* __restrict__ D, uint32_t B, uint32_t C,
                                                    StemGeom G, uint32_t parts, float* __restrict__ ws) {
+    (void)B;                                                            // (the grid carries the sample count)
     constexpr int kPiece = 16 / (int)sizeof(T), kKC = stem_kc((int)sizeof(T), kJT);
     constexpr int kNT = stem_threads(kJT), kWaves = kNT / 64;
     constexpr int kDTotal = kKC * kStemBN / kPiece;                     // 16-byte pieces of D per chunk
