@@ -94,6 +94,7 @@ def test_fc_form(dev, B, J, C, prec):
 
 @pytest.mark.parametrize("B,P,J,C", [(4, 49, 64, 64), (3, 5, 27, 16), (2, 1, 40, 40), (8, 196, 576, 64), (5, 9, 100, 33),
                                      (6, 33, 200, 136), (3, 64, 384, 256), (6, 784, 128, 128),
+                                     (5, 20, 72, 40), (4, 39, 64, 200),          # last chunk of a sample a quarter / half full
                                      (8, 2000, 64, 72), (8, 1111, 24, 16),       # few tiles, many positions: split over positions
                                      (2, 1111, 24, 16), (1, 300, 40, 24),        # one or two samples (non-negative inputs)
                                      (40, 100, 1024, 512)])                      # more (tile, sample) pairs than workgroup slots: several samples per workgroup
