@@ -290,8 +290,11 @@ int vgc_pack(uint64_t n, const vgc_group* groups, uint32_t n_groups, const void*
  * distinct, so the result is deterministic; several messages are applied by several calls on
  * the same stream, in call order.  scale = 1/p gives the mean over p workers.
  *
- * words, hdrs: DEVICE (as written by vgc_pack; n_words = the message's total word count, known to
- * the receiver from the transfer size).  plan: DEVICE.  dense_out: DEVICE float[n].
+ * words, hdrs: DEVICE (as written by vgc_pack: indices ascending inside a group; n_words = the
+ * message's total word count, known to the receiver from the transfer size; an upper bound is
+ * allowed, the headers' counts decide).  plan: DEVICE.  dense_out: DEVICE float[n].
+ * The kernel is chosen from n_words: one thread per word below n / 8, above it one pass over
+ * dense_out tile by tile; the sums are the same bit for bit, so a loose upper bound costs time only.
  */
 int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr* hdrs,
                    const vgc_group* groups, uint32_t n_groups, const void* plan,

@@ -606,6 +606,16 @@ int vgc_unpack_add(const uint32_t* words, uint64_t n_words, const vgc_group_hdr*
     }
     if (!std::isfinite(scale)) { set_error("vgc_unpack_add: scale is not finite"); return VGC_ERR_PARAM; }
     const PlanView pv = plan_view(plan, n_tiles, n_groups);
+    // A message that touches most cache lines of the buffer anyway (an eighth of the elements or more, going by
+    // n_words) is decoded tile by tile like a batch of one: the same additions, the buffer streamed once instead of
+    // read and written line by line under 64 scattered lanes (1.2 to 2.7 times faster from a sixth to two thirds sent).
+    if (n_words && n_words >= n / 8) {
+        const uint32_t* const wl[1] = {words};
+        const uint64_t nl[1] = {n_words};
+        const vgc_group_hdr* const hl[1] = {hdrs};
+        return launch_unpack_add_batch(plan_check(plan, gs), wl, nl, hl, 1, pv.groups, pv.runs, gs.n_runs, scale, 0, dense_out,
+                                       static_cast<hipStream_t>(stream));
+    }
     return launch_unpack_add(plan_check(plan, gs), words, n_words, hdrs, pv.groups, n_groups, scale, dense_out, static_cast<hipStream_t>(stream));
 }
 
