@@ -14,6 +14,7 @@
 namespace vgc {
 
 typedef float f16v __attribute__((ext_vector_type(16)));
+typedef float f4v __attribute__((ext_vector_type(4)));
 typedef __bf16 bf8v __attribute__((ext_vector_type(8)));
 typedef short s4v __attribute__((ext_vector_type(4)));
 typedef short s8v __attribute__((ext_vector_type(8)));
@@ -115,11 +116,23 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
             if ((uint32_t)i < n_u) *reinterpret_cast<T*>(Ush + (upg + (uint32_t)i * groups) * pitch_u + uj * sizeof(T)) = u_next[i];
     };
 
-    // ---- tiles of the workgroup's [Jpad, 64] block: 32 x 32 each, dealt to the waves ----
+    // ---- tiles of the workgroup's [Jpad, 64] block, dealt to the waves ----
+    // bfloat16: 32 x 32 tiles, tile = wave + waves x t.  float32: 16 x 16 tiles (v_mfma_f32_16x16x4_f32 runs at the
+    // rate of the 32 x 32 x 2 one), which deal evenly: a wave owns 16 columns (wave % 4) and kT16 row tiles, all
+    // 2 kJT of them with four waves, one half of them each with eight (ten 32 x 32 tiles on eight waves left two
+    // waves with twice the work of the others).
     const uint32_t n_jt = G.Jpad / 32u, n_tiles = n_jt * 2u;
+    constexpr int kT16 = kWaves == 4 ? 2 * kJT : kJT;
     f16v acc[kT];
+    f4v acc16[kT16];
+    if constexpr (sizeof(T) == 2) {
 #pragma unroll
-    for (int t = 0; t < kT; ++t) acc[t] = (f16v){0};
+        for (int t = 0; t < kT; ++t) acc[t] = (f16v){0};
+    } else {
+#pragma unroll
+        for (int t = 0; t < kT16; ++t) acc16[t] = (f4v){0};
+    }
+    const uint32_t ct16 = wave & 3u, jt16 = kWaves == 4 ? 0u : (wave >> 2) * (uint32_t)kJT;   // first row tile of the wave
     // bfloat16: the transposing LDS read hands lane l the 8 consecutive positions 8 (l / 32) .. + 7 of column l % 32 from
     // rows that are positions: within 16 lanes, lane r points at row r / 4, columns 4 (r % 4) .. + 3
     const uint32_t r16 = lane & 15u, g16 = lane >> 4, mhalf = g16 & 1u, khalf = g16 >> 1;
@@ -131,12 +144,12 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
         stage();
         __syncthreads();
         if (q + 1 < q_end) fetch(q + 1);                                // in flight during the multiplications
+        if constexpr (sizeof(T) == 2) {
 #pragma unroll
-        for (int t = 0; t < kT; ++t) {
-            const uint32_t tile = wave + (uint32_t)kWaves * t;
-            if (tile < n_tiles) {                                       // wave-uniform
-                const uint32_t jt = tile >> 1, ct = tile & 1u;
-                if constexpr (sizeof(T) == 2) {
+            for (int t = 0; t < kT; ++t) {
+                const uint32_t tile = wave + (uint32_t)kWaves * t;
+                if (tile < n_tiles) {                                   // wave-uniform
+                    const uint32_t jt = tile >> 1, ct = tile & 1u;
                     const uint8_t* ua = Ush + frow * pitch_u + (jt * 32u + fcol) * 2u;
                     const uint8_t* db = Dsh + frow * pitch_d + (ct * 32u + fcol) * 2u;
 #pragma unroll
@@ -149,16 +162,19 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
                         const s8v bv = {blo[0], blo[1], blo[2], blo[3], bhi[0], bhi[1], bhi[2], bhi[3]};
                         acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf8v, av), __builtin_bit_cast(bf8v, bv), acc[t], 0, 0, 0);
                     }
-                } else {
-                    // float32: lane l supplies U[k = l / 32][m = l % 32] and D[k][n = l % 32] of each pair of positions
-                    const uint8_t* ua = Ush + (lane >> 5) * pitch_u + (jt * 32u + (lane & 31u)) * 4u;
-                    const uint8_t* db = Dsh + (lane >> 5) * pitch_d + (ct * 32u + (lane & 31u)) * 4u;
+                }
+            }
+        } else {
+            // float32: of each four positions lane l supplies U[k = l / 16][m = l % 16] and D[k][n = l % 16]
+            const uint8_t* ua = Ush + (lane >> 4) * pitch_u + (jt16 * 16u + (lane & 15u)) * 4u;
+            const uint8_t* db = Dsh + (lane >> 4) * pitch_d + (ct16 * 16u + (lane & 15u)) * 4u;
 #pragma unroll
-                    for (int ks = 0; ks < kKC / 2; ++ks) {
-                        const float a = *reinterpret_cast<const float*>(ua + ks * 2 * pitch_u);
-                        const float b = *reinterpret_cast<const float*>(db + ks * 2 * pitch_d);
-                        acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, acc[t], 0, 0, 0);
-                    }
+            for (int ks = 0; ks < kKC / 4; ++ks) {
+                const float b = *reinterpret_cast<const float*>(db + ks * 4 * pitch_d);
+#pragma unroll
+                for (int t = 0; t < kT16; ++t) {
+                    const float a = *reinterpret_cast<const float*>(ua + ks * 4 * pitch_u + t * 64);
+                    acc16[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, acc16[t], 0, 0, 0);
                 }
             }
         }
@@ -166,18 +182,29 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
 
     // ---- the part's unsquared product to the workspace: plane (z, part) of [J, C] ----
     float* out = ws + ((size_t)z * parts + part) * (size_t)G.J * C;
+    if constexpr (sizeof(T) == 2) {
 #pragma unroll
-    for (int t = 0; t < kT; ++t) {
-        const uint32_t tile = wave + (uint32_t)kWaves * t;
-        if (tile < n_tiles) {
-            const uint32_t jt = tile >> 1, ct = tile & 1u;
-            const uint32_t col = c0 + ct * 32u + (lane & 31u);
+        for (int t = 0; t < kT; ++t) {
+            const uint32_t tile = wave + (uint32_t)kWaves * t;
+            if (tile < n_tiles) {
+                const uint32_t jt = tile >> 1, ct = tile & 1u;
+                const uint32_t col = c0 + ct * 32u + (lane & 31u);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const uint32_t row = jt * 32u + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
-                if (row < G.J && col < C) out[(size_t)row * C + col] = acc[t][i];
+                for (int i = 0; i < 16; ++i) {
+                    const uint32_t row = jt * 32u + 8 * (i >> 2) + 4 * (lane >> 5) + (i & 3);
+                    if (row < G.J && col < C) out[(size_t)row * C + col] = acc[t][i];
+                }
             }
         }
+    } else {
+        const uint32_t col = c0 + ct16 * 16u + (lane & 15u);
+#pragma unroll
+        for (int t = 0; t < kT16; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t row = (jt16 + (uint32_t)t) * 16u + 4u * (lane >> 4) + (uint32_t)i;
+                if (row < G.J && col < C) out[(size_t)row * C + col] = acc16[t][i];
+            }
     }
 }
 
