@@ -43,7 +43,20 @@ __host__ __device__ inline uint32_t stem_pitch_d(uint32_t esize) { return kStemB
 // (how many threads share a column of U) and the tiles a wave holds at most, kT = ceil(2 kJT / waves).
 __host__ __device__ constexpr int stem_threads(int jt) { return jt >= 3 ? 512 : 256; }
 
-template <typename T, int kJT>
+// Three float32 channels of a pixel, 4-byte aligned: fetched with one 12-byte load.
+struct __attribute__((packed, aligned(4))) StemPixel3 { float c[3]; };
+constexpr int kStemPixMax = 4;         // pixels a thread holds for the next chunk at most (kPix3)
+
+// Position groups of the pixel-wise gather: the largest power of two that threads / taps and the chunk allow.
+__host__ __device__ inline uint32_t stem_pix_groups(uint32_t threads, uint32_t taps, uint32_t kc) {
+    uint32_t g = 1;
+    while (2u * g * taps <= threads && 2u * g <= kc) g *= 2u;
+    return g;
+}
+
+// kPix3 (float32, Cin = 3): the patch rows are gathered pixel by pixel (one 12-byte load per tap and position) instead
+// of element by element.
+template <typename T, int kJT, bool kPix3 = false>
 __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __restrict__ act, const T* __restrict__ D, uint32_t B, uint32_t C,
                                                    StemGeom G, uint32_t parts, float* __restrict__ ws) {
     (void)B;                                                            // (the grid carries the sample count)
@@ -82,6 +95,15 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
     const bool u_col = uj < G.J;
     const uint32_t utap = uj / G.Cin, uci = uj - utap * G.Cin, uky = utap / G.kw, ukx = utap - uky * G.kw;
     const int32_t dy = (int32_t)uky - (int32_t)G.ph, dx = (int32_t)ukx - (int32_t)G.pw;
+    // kPix3: thread tid < pgroups * taps owns tap tid % taps (columns 3 tap .. + 2) and the positions ppg, ppg + pgroups, ...
+    const uint32_t n_taps = kPix3 ? G.J / 3u : 1u, pgroups = stem_pix_groups(kNT, n_taps, kKC);
+    const uint32_t ptap = tid % n_taps, ppg = tid / n_taps, pky = ptap / G.kw, pkx = ptap - pky * G.kw;
+    const uint32_t n_pix = kPix3 && ppg < pgroups ? (uint32_t)kKC / pgroups : 0u;     // <= kStemPixMax (the launcher checks)
+    const int32_t pdy = (int32_t)pky - (int32_t)G.ph, pdx = (int32_t)pkx - (int32_t)G.pw;
+    StemPixel3 pix_next[kPix3 ? kStemPixMax : 1];
+    if (kPix3) {                                                        // the columns J .. Jpad - 1 are never staged
+        for (uint32_t e = tid * 16u; e < (uint32_t)kKC * pitch_u; e += (uint32_t)kNT * 16u) *reinterpret_cast<u4v*>(Ush + e) = (u4v){0u, 0u, 0u, 0u};
+    }
     auto fetch = [&](uint32_t q) {
         const uint32_t p0 = q * kKC;
 #pragma unroll
@@ -92,6 +114,20 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
             if (e < (uint32_t)kDTotal && p < P && col < C) d_next[i] = *reinterpret_cast<const u4v*>(D_z + (size_t)p * C + col);   // C is a multiple of kPiece
         }
         const uint32_t y0 = p0 / G.Wo, x0 = p0 - y0 * G.Wo;             // (uniform)
+        if constexpr (kPix3) {
+            uint32_t y = y0, x = x0 + ppg;
+#pragma unroll
+            for (int i = 0; i < kStemPixMax; ++i) {
+                pix_next[i] = StemPixel3{{0.0f, 0.0f, 0.0f}};
+                if ((uint32_t)i < n_pix) {
+                    while (x >= G.Wo) { x -= G.Wo; ++y; }
+                    const uint32_t iy = (uint32_t)((int32_t)(y * G.sh) + pdy), ix = (uint32_t)((int32_t)(x * G.sw) + pdx);
+                    if (y < G.Ho && iy < G.H && ix < G.W) pix_next[i] = *reinterpret_cast<const StemPixel3*>(act_z + ((size_t)iy * G.W + ix) * 3u);
+                    x += pgroups;
+                }
+            }
+            return;
+        }
         uint32_t y = y0, x = x0 + upg;
 #pragma unroll
         for (int i = 0; i < kUMax; ++i) {
@@ -110,6 +146,15 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
             constexpr uint32_t ppr = kStemBN / kPiece;
             const uint32_t e = tid + (uint32_t)kNT * i, pl = e / ppr, cl = (e % ppr) * kPiece;
             if (e < (uint32_t)kDTotal) *reinterpret_cast<u4v*>(Dsh + pl * pitch_d + cl * sizeof(T)) = d_next[i];
+        }
+        if constexpr (kPix3) {
+#pragma unroll
+            for (int i = 0; i < kStemPixMax; ++i)
+                if ((uint32_t)i < n_pix) {
+                    float* dst = reinterpret_cast<float*>(Ush + (ppg + (uint32_t)i * pgroups) * pitch_u + ptap * 12u);
+                    dst[0] = pix_next[i].c[0]; dst[1] = pix_next[i].c[1]; dst[2] = pix_next[i].c[2];
+                }
+            return;
         }
 #pragma unroll
         for (int i = 0; i < kUMax; ++i)
@@ -246,20 +291,31 @@ int launch_conv_stem(int dtype, const void* act, const void* D, uint32_t B, uint
     G.J = J; G.Jpad = (J + 31u) / 32u * 32u;
     float* ws = static_cast<float*>(workspace);
     const uint32_t jt = G.Jpad / 32u;
-#define VGC_LAUNCH_STEM(T_, JT_)                                                                                              \
-    hipLaunchKernelGGL((k_conv_stem<T_, JT_>), dim3((uint32_t)nblk), dim3(stem_threads(JT_)),                                 \
+#define VGC_LAUNCH_STEM_P(T_, JT_, PIX_)                                                                                      \
+    hipLaunchKernelGGL((k_conv_stem<T_, JT_, PIX_>), dim3((uint32_t)nblk), dim3(stem_threads(JT_)),                           \
                        (size_t)stem_kc((int)sizeof(T_), JT_) * (stem_pitch_u(G.Jpad, sizeof(T_)) + stem_pitch_d(sizeof(T_))), stream, \
                        (const T_*)act, (const T_*)D, B, C, G, parts, ws)
+#define VGC_LAUNCH_STEM(T_, JT_) VGC_LAUNCH_STEM_P(T_, JT_, false)
+    // float32 RGB input: pixel by pixel, where a thread's share of a chunk's pixels fits what the kernel holds
+#define VGC_LAUNCH_STEM_F32(JT_)                                                                                              \
+    do {                                                                                                                      \
+        const uint32_t kc_ = (uint32_t)stem_kc(4, JT_);                                                                       \
+        if (Cin == 3 && kc_ / stem_pix_groups((uint32_t)stem_threads(JT_), J / 3u, kc_) <= (uint32_t)kStemPixMax)             \
+            VGC_LAUNCH_STEM_P(float, JT_, true);                                                                              \
+        else VGC_LAUNCH_STEM_P(float, JT_, false);                                                                            \
+    } while (0)
     if (dtype == VGC_BF16) {
         if (jt == 1) VGC_LAUNCH_STEM(uint16_t, 1); else if (jt == 2) VGC_LAUNCH_STEM(uint16_t, 2);
         else if (jt == 3) VGC_LAUNCH_STEM(uint16_t, 3); else if (jt == 4) VGC_LAUNCH_STEM(uint16_t, 4);
         else VGC_LAUNCH_STEM(uint16_t, 5);
     } else {
-        if (jt == 1) VGC_LAUNCH_STEM(float, 1); else if (jt == 2) VGC_LAUNCH_STEM(float, 2);
-        else if (jt == 3) VGC_LAUNCH_STEM(float, 3); else if (jt == 4) VGC_LAUNCH_STEM(float, 4);
-        else VGC_LAUNCH_STEM(float, 5);
+        if (jt == 1) VGC_LAUNCH_STEM_F32(1); else if (jt == 2) VGC_LAUNCH_STEM_F32(2);
+        else if (jt == 3) VGC_LAUNCH_STEM_F32(3); else if (jt == 4) VGC_LAUNCH_STEM_F32(4);
+        else VGC_LAUNCH_STEM_F32(5);
     }
+#undef VGC_LAUNCH_STEM_F32
 #undef VGC_LAUNCH_STEM
+#undef VGC_LAUNCH_STEM_P
     launch_sqgrad_reduce_parts(ws, B, parts, (size_t)J * C, c, c * c, g_out, s_out, stream);
     return hip_check(hipGetLastError(), "launch k_conv_stem");
 }
