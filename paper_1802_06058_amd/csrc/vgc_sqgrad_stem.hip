@@ -43,9 +43,13 @@ __host__ __device__ inline uint32_t stem_pitch_d(uint32_t esize) { return kStemB
 // (how many threads share a column of U) and the tiles a wave holds at most, kT = ceil(2 kJT / waves).
 __host__ __device__ constexpr int stem_threads(int jt) { return jt >= 3 ? 512 : 256; }
 
-// Three float32 channels of a pixel, 4-byte aligned: fetched with one 12-byte load.
-struct __attribute__((packed, aligned(4))) StemPixel3 { float c[3]; };
-constexpr int kStemPixMax = 4;         // pixels a thread holds for the next chunk at most (kPix3)
+// The three channels of a pixel, aligned like one element: fetched with one 12-byte load (float32) or whatever the
+// compiler makes of 6 bytes at a 2-byte boundary (bfloat16).
+template <typename T> struct StemPixel3;
+template <> struct __attribute__((packed, aligned(4))) StemPixel3<float> { float c[3]; };
+template <> struct __attribute__((packed, aligned(2))) StemPixel3<uint16_t> { uint16_t c[3]; };
+// pixels a thread holds for the next chunk at most (kPix3)
+__host__ __device__ constexpr int stem_pix_max(int esize) { return esize == 2 ? 8 : 4; }
 
 // Position groups of the pixel-wise gather: the largest power of two that threads / taps and the chunk allow.
 __host__ __device__ inline uint32_t stem_pix_groups(uint32_t threads, uint32_t taps, uint32_t kc) {
@@ -54,8 +58,8 @@ __host__ __device__ inline uint32_t stem_pix_groups(uint32_t threads, uint32_t t
     return g;
 }
 
-// kPix3 (float32, Cin = 3): the patch rows are gathered pixel by pixel (one 12-byte load per tap and position) instead
-// of element by element.
+// kPix3 (Cin = 3): the patch rows are gathered pixel by pixel (one load per tap and position) instead of element by
+// element.
 template <typename T, int kJT, bool kPix3 = false>
 __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __restrict__ act, const T* __restrict__ D, uint32_t B, uint32_t C,
                                                    StemGeom G, uint32_t parts, float* __restrict__ ws) {
@@ -98,9 +102,10 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
     // kPix3: thread tid < pgroups * taps owns tap tid % taps (columns 3 tap .. + 2) and the positions ppg, ppg + pgroups, ...
     const uint32_t n_taps = kPix3 ? G.J / 3u : 1u, pgroups = stem_pix_groups(kNT, n_taps, kKC);
     const uint32_t ptap = tid % n_taps, ppg = tid / n_taps, pky = ptap / G.kw, pkx = ptap - pky * G.kw;
+    constexpr int kStemPixMax = stem_pix_max((int)sizeof(T));
     const uint32_t n_pix = kPix3 && ppg < pgroups ? (uint32_t)kKC / pgroups : 0u;     // <= kStemPixMax (the launcher checks)
     const int32_t pdy = (int32_t)pky - (int32_t)G.ph, pdx = (int32_t)pkx - (int32_t)G.pw;
-    StemPixel3 pix_next[kPix3 ? kStemPixMax : 1];
+    StemPixel3<T> pix_next[kPix3 ? kStemPixMax : 1];
     if (kPix3) {                                                        // the columns J .. Jpad - 1 are never staged
         for (uint32_t e = tid * 16u; e < (uint32_t)kKC * pitch_u; e += (uint32_t)kNT * 16u) *reinterpret_cast<u4v*>(Ush + e) = (u4v){0u, 0u, 0u, 0u};
     }
@@ -118,11 +123,11 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
             uint32_t y = y0, x = x0 + ppg;
 #pragma unroll
             for (int i = 0; i < kStemPixMax; ++i) {
-                pix_next[i] = StemPixel3{{0.0f, 0.0f, 0.0f}};
+                pix_next[i] = StemPixel3<T>{{(T)0, (T)0, (T)0}};
                 if ((uint32_t)i < n_pix) {
                     while (x >= G.Wo) { x -= G.Wo; ++y; }
                     const uint32_t iy = (uint32_t)((int32_t)(y * G.sh) + pdy), ix = (uint32_t)((int32_t)(x * G.sw) + pdx);
-                    if (y < G.Ho && iy < G.H && ix < G.W) pix_next[i] = *reinterpret_cast<const StemPixel3*>(act_z + ((size_t)iy * G.W + ix) * 3u);
+                    if (y < G.Ho && iy < G.H && ix < G.W) pix_next[i] = *reinterpret_cast<const StemPixel3<T>*>(act_z + ((size_t)iy * G.W + ix) * 3u);
                     x += pgroups;
                 }
             }
@@ -151,7 +156,7 @@ __global__ __launch_bounds__(stem_threads(kJT)) void k_conv_stem(const T* __rest
 #pragma unroll
             for (int i = 0; i < kStemPixMax; ++i)
                 if ((uint32_t)i < n_pix) {
-                    float* dst = reinterpret_cast<float*>(Ush + (ppg + (uint32_t)i * pgroups) * pitch_u + ptap * 12u);
+                    T* dst = reinterpret_cast<T*>(Ush + (ppg + (uint32_t)i * pgroups) * pitch_u + ptap * 3u * sizeof(T));
                     dst[0] = pix_next[i].c[0]; dst[1] = pix_next[i].c[1]; dst[2] = pix_next[i].c[2];
                 }
             return;
@@ -295,25 +300,23 @@ int launch_conv_stem(int dtype, const void* act, const void* D, uint32_t B, uint
     hipLaunchKernelGGL((k_conv_stem<T_, JT_, PIX_>), dim3((uint32_t)nblk), dim3(stem_threads(JT_)),                           \
                        (size_t)stem_kc((int)sizeof(T_), JT_) * (stem_pitch_u(G.Jpad, sizeof(T_)) + stem_pitch_d(sizeof(T_))), stream, \
                        (const T_*)act, (const T_*)D, B, C, G, parts, ws)
-#define VGC_LAUNCH_STEM(T_, JT_) VGC_LAUNCH_STEM_P(T_, JT_, false)
-    // float32 RGB input: pixel by pixel, where a thread's share of a chunk's pixels fits what the kernel holds
-#define VGC_LAUNCH_STEM_F32(JT_)                                                                                              \
+    // RGB input: pixel by pixel, where a thread's share of a chunk's pixels fits what the kernel holds
+#define VGC_LAUNCH_STEM(T_, JT_)                                                                                              \
     do {                                                                                                                      \
-        const uint32_t kc_ = (uint32_t)stem_kc(4, JT_);                                                                       \
-        if (Cin == 3 && kc_ / stem_pix_groups((uint32_t)stem_threads(JT_), J / 3u, kc_) <= (uint32_t)kStemPixMax)             \
-            VGC_LAUNCH_STEM_P(float, JT_, true);                                                                              \
-        else VGC_LAUNCH_STEM_P(float, JT_, false);                                                                            \
+        const uint32_t kc_ = (uint32_t)stem_kc((int)sizeof(T_), JT_);                                                         \
+        if (Cin == 3 && kc_ / stem_pix_groups((uint32_t)stem_threads(JT_), J / 3u, kc_) <= (uint32_t)stem_pix_max((int)sizeof(T_))) \
+            VGC_LAUNCH_STEM_P(T_, JT_, true);                                                                                 \
+        else VGC_LAUNCH_STEM_P(T_, JT_, false);                                                                               \
     } while (0)
     if (dtype == VGC_BF16) {
         if (jt == 1) VGC_LAUNCH_STEM(uint16_t, 1); else if (jt == 2) VGC_LAUNCH_STEM(uint16_t, 2);
         else if (jt == 3) VGC_LAUNCH_STEM(uint16_t, 3); else if (jt == 4) VGC_LAUNCH_STEM(uint16_t, 4);
         else VGC_LAUNCH_STEM(uint16_t, 5);
     } else {
-        if (jt == 1) VGC_LAUNCH_STEM_F32(1); else if (jt == 2) VGC_LAUNCH_STEM_F32(2);
-        else if (jt == 3) VGC_LAUNCH_STEM_F32(3); else if (jt == 4) VGC_LAUNCH_STEM_F32(4);
-        else VGC_LAUNCH_STEM_F32(5);
+        if (jt == 1) VGC_LAUNCH_STEM(float, 1); else if (jt == 2) VGC_LAUNCH_STEM(float, 2);
+        else if (jt == 3) VGC_LAUNCH_STEM(float, 3); else if (jt == 4) VGC_LAUNCH_STEM(float, 4);
+        else VGC_LAUNCH_STEM(float, 5);
     }
-#undef VGC_LAUNCH_STEM_F32
 #undef VGC_LAUNCH_STEM
 #undef VGC_LAUNCH_STEM_P
     launch_sqgrad_reduce_parts(ws, B, parts, (size_t)J * C, c, c * c, g_out, s_out, stream);
