@@ -3,12 +3,12 @@
 // not a multiple of 16 bytes and the kernels that move 16-byte pieces of a filter tap do not apply.  Such
 // a layer has a small J = kh kw Cin (27 for a 3 x 3 filter, 147 for 7 x 7) and few multiply-adds; what it
 // costs is reading the output gradient once, so the kernel is a plain one: a workgroup owns one sample,
-// one part of its positions and 64 output channels; per chunk of 32 positions it gathers the patch rows
-// U[p, j] element by element and the rows of D into LDS, both transposed (32 positions contiguous per
-// column), and multiplies them on the matrix cores; the unsquared partial product of the part goes to the
-// workspace and k_sqgrad_reduce_parts adds the parts of each sample, squares, and sums over the samples
-// in a fixed order.  The rows of D of the chunk after the current one are fetched into registers while the
-// current one is multiplied.
+// one part of its positions and 64 output channels; per chunk of 32 to 128 positions it gathers the patch
+// rows U[p, j] (pixel by pixel for three channels, element by element otherwise) and the rows of D into
+// LDS, rows = positions, and multiplies them on the matrix cores; the unsquared partial product of the part
+// goes to the workspace and k_sqgrad_reduce_parts adds the parts of each sample, squares, and sums over the
+// samples in a fixed order.  What a thread gathers for the chunk after the current one waits in registers
+// while the current one is multiplied.
 #include "vgc_internal.h"
 
 namespace vgc {
