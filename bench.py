@@ -170,18 +170,20 @@ def main():
     out["stages"]["compressed_indexes"] = bench_compact(vgc, plan, pool, r[0], v[0], a.alpha, zeta, scratch, words, hdrs, status, dense, N, P, scale)
 
     # hybrid algorithm (Alg. 2) on worker 0's buffers: same kernels with the threshold rule, tau = 0.05
+    # (the steps are queued back to back like the workers of the flat workload above; each has a status record of its own)
     r[0].zero_(); v[0].zero_()
-    hy_ms, hy_words = [], []
+    hy_marks, hy_status = [], [plan.new_status() for _ in range(4)]
     for k in range(4):
         g, s = pool[k % P]
         e0, e1 = ev(), ev()
         e0.record()
         vgc.accumulate_select_hybrid(g, s, r[0], v[0], plan, 2.0, zeta, 0.05, scratch)
-        vgc.pack(plan, scratch, words[0], hdrs[0], status[0])
+        vgc.pack(plan, scratch, words[0], hdrs[0], hy_status[k])
         e1.record()
-        torch.cuda.synchronize()
-        if k:
-            hy_ms.append(e0.elapsed_time(e1)); hy_words.append(vgc.read_status(status[0])[0])
+        hy_marks.append((e0, e1))
+    torch.cuda.synchronize()
+    hy_ms = [e0.elapsed_time(e1) for e0, e1 in hy_marks[1:]]
+    hy_words = [vgc.read_status(hy_status[k])[0] for k in range(1, 4)]
     hy, hrho = float(np.mean(hy_ms)), float(np.mean(hy_words)) / N
     out["stages"]["hybrid_select_plus_pack"] = {
         "alpha": 2.0, "tau": 0.05, "ms": round(hy, 4), "sent_fraction": round(hrho, 5),
