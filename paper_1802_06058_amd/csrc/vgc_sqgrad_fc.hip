@@ -191,7 +191,8 @@ __device__ __forceinline__ void stage32(float* A, float* Bm, const Chunk32<PA, P
 //         is formed per chunk from the output position of its row, which is kept incrementally.
 // BM x BN: the block tile (64 or 128 each), one wave per 64 x 64 of it; rows of LDS are padded by 32 floats.
 // kTail: the k-steps of a sample's last chunk that lie wholly past its rows are skipped (see conv_f32_tail).
-template <bool kConv, bool kWantG, bool kImplicit, int BM = 128, int BN = 128, bool kTail = false>
+// kDepth: sets of staging registers, i.e. chunks requested ahead of the one being staged (2, or 3 where the registers allow).
+template <bool kConv, bool kWantG, bool kImplicit, int BM = 128, int BN = 128, bool kTail = false, int kDepth = 2>
 __global__ __launch_bounds__((BM / 64) * (BN / 64) * 64, 2)
 void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
                  uint32_t B, uint32_t P, uint32_t J, uint32_t C,
@@ -245,7 +246,7 @@ void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
             if (colj >= J) tapX[i] = -0x400000;              // a column past J: never inside the input
         }
     }
-    Chunk32<PA, PB> R[2];
+    Chunk32<PA, PB> R[kDepth];
     uint32_t zl = z_begin, pcl = c_begin, issued = 0;
     auto issue = [&](int slot_) {
         const bool live = issued < total;
@@ -287,8 +288,8 @@ void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
         }
         ++issued;
     };
-    issue(0);
-    issue(1);
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) issue(d);
     stage32<BM, BN, NT>(shA[0], shB[0], R[0], tid);
     issue(0);
     __syncthreads();
@@ -301,10 +302,13 @@ void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
     // shapes with little to skip take the kernel without them.
     const uint32_t tail_steps = (rowsP - (n_chunks - 1u) * kR32 + 1u) / 2u;
     uint32_t cpos = split_p > 1 ? c_begin : 0u;                      // the chunk's place in its sample
-    for (uint32_t q0 = 0; q0 < total; q0 += 2) {
+    // chunk q sits in LDS buffer q % 2 and came through register set q % kDepth; the loop is unrolled over both
+    constexpr int kUnroll = kDepth % 2 == 0 ? kDepth : 2 * kDepth;
+    for (uint32_t q0 = 0; q0 < total; q0 += kUnroll) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            const uint32_t buf = (uint32_t)u;                       // q = q0 + u, and q0 is even
+        for (int u = 0; u < kUnroll; ++u) {
+            if (u > 0 && q0 + (uint32_t)u >= total) break;
+            const uint32_t buf = (uint32_t)(u & 1);                 // q = q0 + u, and q0 is even
             const float* A = shA[buf];
             const float* Bm = shB[buf];
             auto k_step = [&](uint32_t ks) __attribute__((always_inline)) {
@@ -343,7 +347,7 @@ void k_tiled_f32(const float* __restrict__ X, const float* __restrict__ D,
 #pragma unroll
                 for (int ks = 0; ks < kR32 / 2; ++ks) k_step((uint32_t)ks);
             }
-            const int ns = u ^ 1;
+            const int ns = (u + 1) % kDepth;
             stage32<BM, BN, NT>(shA[buf ^ 1u], shB[buf ^ 1u], R[ns], tid);
             issue(ns);
             if (kConv && --left == 0) {                           // sample finished: G_z is complete in acc
@@ -490,8 +494,8 @@ static int launch_conv_f32_any(const void* X, const void* D, uint32_t B, uint32_
         const dim3 grid((uint32_t)nblk), block((BM_ / 64) * (BN_ / 64) * 64);                                              \
         if (with_g) hipLaunchKernelGGL((k_tiled_f32<true, true, kImplicit, BM_, BN_, TAIL_>), grid, block, 0, stream, Xf,  \
                                        Df, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);                      \
-        else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit, BM_, BN_, TAIL_>), grid, block, 0, stream, Xf, Df, B, \
-                                P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G);                                    \
+        else hipLaunchKernelGGL((k_tiled_f32<true, false, kImplicit, BM_, BN_, TAIL_, (BM_ == 128 && BN_ == 128) ? 3 : 2>), \
+                                grid, block, 0, stream, Xf, Df, B, P, J, C, splits, split_p, cg, cs, g_out, s_out, ws, G); \
     } while (0)
 #define VGC_LAUNCH_F32(BM_, BN_)                                                                                           \
     do {                                                                                                                   \
