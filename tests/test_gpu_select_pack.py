@@ -300,6 +300,38 @@ def test_unpack_add_messages_in_order(dev, scale):
     assert np.array_equal(_bits(dense.cpu().numpy()), _bits(expect))
 
 
+@pytest.mark.parametrize("alpha", [0.0, 1.0, 6.0])
+def test_unpack_add_both_kernels_decode_the_same_message(dev, alpha):
+    """vgc_unpack_add picks its kernel from n_words (one thread per word below n / 8, tile by tile from there on) and
+    accepts an upper bound for it: the same message given with its exact count and with a bound on the other side of
+    n / 8 (where the count allows) must decode to the oracle's bits both times."""
+    import torch
+    from paper_1802_06058_amd import vgc
+    sizes = [2048 * 9 + 77, 3, 2048 * 4, 5000]
+    groups = W.groups_from_sizes(sizes)
+    n = sum(sizes)
+    plan = vgc.Plan(groups, dev)
+    g, s = sample_stream(31, (int(alpha),), n, 16, "student", sigma=0.05)
+    z = np.zeros(n, F32)
+    r_acc, _, _, send = O.accumulate_select(g, s, z, z, alpha, 0.999)
+    words, hdrs, _ = O.pack(r_acc, send, groups)
+    rng = np.random.default_rng(5)
+    dense0 = rng.standard_normal(n).astype(F32)
+    expect = dense0.copy()
+    O.unpack_add(words, hdrs, groups, 0.25, expect)
+    pad = np.full(n + 8, 0x0BADC0DE, np.uint32)                 # junk past the message
+    pad[:words.size] = words
+    d_words = _dev(pad.view(np.int32), dev)
+    d_hdrs = _dev(np.array(hdrs, dtype=vgc.HDR_DTYPE).view(np.uint8), dev)
+    counts = {words.size, max(words.size, n // 8), max(words.size, n // 8 - 1), n}
+    assert any(c >= n // 8 for c in counts) and (words.size >= n // 8 or any(c < n // 8 for c in counts))
+    for c in sorted(counts):
+        dense = _dev(dense0, dev)
+        vgc.unpack_add(d_words, c, d_hdrs, plan, 0.25, dense)
+        torch.cuda.synchronize()
+        assert np.array_equal(_bits(dense.cpu().numpy()), _bits(expect)), f"n_words = {c} of n = {n}, message of {words.size}"
+
+
 def test_full_round_trip_gpu_pack_to_gpu_unpack(dev):
     """GPU-packed message decoded by the GPU equals the oracle's decode of the oracle's message,
     and the conservation invariant holds on the GPU results."""
